@@ -1,0 +1,172 @@
+/*
+ * comet.h -- C ABI of the MI355X (gfx950) sparse x dense contraction library.
+ *
+ * The library evaluates the mixed sparse/dense contractions of the COMET paper
+ * (arXiv 2102.05187) -- SpMV, SpMM, SpTTV, SpTTM (Section 8.2, "Sparse Tensor
+ * Operations") and MTTKRP (named in Section 8.3) -- on tensors held in the paper's
+ * per-dimension level storage (Section 4, "Tensor Storage Format").
+ *
+ * General conventions
+ *   - Every array pointer is a DEVICE pointer unless a parameter says "host".
+ *   - Index arrays (pos, crd) are int32, values are fp64 (Section 6.1, "Sparse Tensor
+ *     Data Type"); coordinates, positions and modes are 0-based.
+ *   - Dense operands and dense results are contiguous and row-major, last index fastest
+ *     (Section 6.2 Step II: the dense index update vIdx = vIdx*SIZE + arg).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Operations
+ *     enqueue work on it and return without synchronising; comet_tensor_create and
+ *     comet_tensor_destroy synchronise with the stream they are given.
+ *   - Every call returns a comet_status; nothing aborts or throws.  Device faults caused
+ *     by arrays that violate the format (and were not validated) are not detected.
+ *   - A tensor handle owns per-tensor scratch memory: at most one operation per handle may
+ *     be in flight at a time (operations on one stream are ordered and therefore safe).
+ */
+#ifndef COMET_H
+#define COMET_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define COMET_MAX_ORDER 4
+
+/* Storage attribute of one level (Section 4):
+ *   D   dense:               pos = {size}, no crd; every coordinate 0..size-1 is visited and the
+ *                            child position is parent*size + coordinate.
+ *   CU  compressed-unique:   crd holds each distinct coordinate once per parent; the children
+ *                            of parent position m are positions pos[m] .. pos[m+1]-1.  At the
+ *                            root m = 0, so pos = {0, n}.
+ *   CN  compressed-nonunique: crd holds the coordinate of every nonzero (duplicates kept);
+ *                            pos = {0, n} (start and extent of crd).  Root level only.
+ *   S   singleton:           no pos; crd[m] is the coordinate that belongs to parent position m.
+ * Level l stores mode l of the tensor.                                                        */
+typedef enum { COMET_D = 0, COMET_CU = 1, COMET_CN = 2, COMET_S = 3 } comet_level_t;
+
+typedef enum {
+    COMET_OK = 0,
+    COMET_ERR_INVALID_ARG = 1,   /* null pointer, negative size, bad flag                      */
+    COMET_ERR_BAD_FORMAT  = 2,   /* arrays do not form a valid tensor of the stated levels     */
+    COMET_ERR_SHAPE       = 3,   /* operand sizes do not match the tensor                      */
+    COMET_ERR_UNSUPPORTED = 4,   /* level tuple / mode / rank outside what the kernels cover   */
+    COMET_ERR_ALLOC       = 5,   /* device or host allocation failed                           */
+    COMET_ERR_DEVICE      = 6    /* a HIP call failed                                          */
+} comet_status;
+
+/* comet_tensor_create flags */
+#define COMET_BORROW   0u   /* default: the caller keeps pos/crd/vals alive until destroy       */
+#define COMET_COPY     1u   /* the library copies pos/crd/vals into memory it owns              */
+#define COMET_VALIDATE 2u   /* run the device-side structure check (see below)                  */
+
+typedef struct comet_tensor comet_tensor;   /* opaque, library-owned */
+
+/* Read-only description of a handle (host struct filled by comet_tensor_info). */
+typedef struct {
+    int32_t        order;
+    int64_t        dims[COMET_MAX_ORDER];
+    int32_t        levels[COMET_MAX_ORDER];   /* comet_level_t                                  */
+    const int32_t *pos[COMET_MAX_ORDER];      /* device pointers (NULL where the level has none) */
+    int64_t        pos_len[COMET_MAX_ORDER];
+    const int32_t *crd[COMET_MAX_ORDER];
+    int64_t        crd_len[COMET_MAX_ORDER];
+    const double  *vals;                      /* device pointer                                 */
+    int64_t        nvals;
+} comet_tensor_info_t;
+
+/*
+ * Build a tensor handle from per-level pos/crd arrays and a value array -- the construction
+ * `sptensor_construct(A1pos, A1crd, A2pos, A2crd, AVal)` of Section 6.1, generalised to
+ * `order` levels.
+ *
+ *   out      host; receives the handle.
+ *   order    number of modes = number of levels (2 or 3 for the operations below).
+ *   dims     host, [order]; logical size of each mode (each < 2^31).
+ *   levels   host, [order]; storage attribute of each level.
+ *   pos      host array of [order] device pointers; pos_len host, [order].  NULL / 0 for S.
+ *            Expected lengths: D 1; root CU or CN 2; non-root CU (#parent positions)+1.
+ *   crd      host array of [order] device pointers; crd_len host, [order].  NULL / 0 for D.
+ *   vals     device, [nvals]; one value per position of the last level.  nvals < 2^31.
+ *   flags    COMET_BORROW | COMET_COPY, optionally | COMET_VALIDATE.
+ *
+ * Cheap consistency checks (lengths, root pos contents, D size == dims) always run.  With
+ * COMET_VALIDATE a device pass also checks: pos starts at 0, is non-decreasing and ends at
+ * crd_len; every coordinate lies in [0, dim); coordinates are strictly increasing inside each CU
+ * segment; a CN/S coordinate list is lexicographically sorted without duplicates.  Failures give
+ * COMET_ERR_BAD_FORMAT and no handle.  Explicit zeros in vals are legal stored entries.
+ *
+ * The call also builds the per-tensor schedule (nonzero-balanced tile tables used by the
+ * kernels; load imbalance is what Section 8.3 identifies as the main source of slowdown), which
+ * is why it synchronises.  Accepted tuples: [D,CU] (CSR), [CU,CU] (DCSR), [CN,S] and [CN,S,S]
+ * (COO), [CU,CU,CU] (CSF); results of TTV/TTM may additionally be [CU,CU,D].
+ */
+comet_status comet_tensor_create(comet_tensor **out, int order,
+                                 const int64_t *dims, const comet_level_t *levels,
+                                 const int32_t *const *pos, const int64_t *pos_len,
+                                 const int32_t *const *crd, const int64_t *crd_len,
+                                 const double *vals, int64_t nvals,
+                                 unsigned flags, void *stream);
+
+/* Release a handle and everything the library allocated for it (borrowed arrays are left
+ * alone).  Level arrays that a TTV/TTM result shares with its input stay valid until the last
+ * handle that uses them is destroyed.  NULL is accepted. */
+comet_status comet_tensor_destroy(comet_tensor *t);
+
+/* Fill *info (host) with the handle's description; pointers inside are device pointers that
+ * stay valid until the handle is destroyed. */
+comet_status comet_tensor_info(const comet_tensor *t, comet_tensor_info_t *info);
+
+/* SpMV, y = A x :  y_i = sum_j a_ij x_j   (Section 8.2, SpMV).
+ *   A   order-2 handle, [D,CU] or [CU,CU].
+ *   x   device, [dims[1]].          y   device, [dims[0]]; every entry is overwritten
+ *                                       (rows without stored nonzeros become 0). */
+comet_status comet_spmv(const comet_tensor *A, const double *x, double *y, void *stream);
+
+/* SpMM, C = A B :  c_ir = sum_j a_ij b_jr   (Section 8.2, SpMM; the paper's example program).
+ *   A   order-2 handle, [D,CU] or [CU,CU].
+ *   B   device, [dims[1] x R] row-major.   C   device, [dims[0] x R] row-major, overwritten.
+ *   R   number of dense columns, 1 <= R <= 1024. */
+comet_status comet_spmm(const comet_tensor *A, const double *B, int64_t R, double *C, void *stream);
+
+/* SpTTV, Y = X x_mode v :  y_ij = sum_k x_ijk v_k   (Section 8.2, SpTTV).
+ *   X     order-3 handle, [CU,CU,CU] or sorted [CN,S,S].
+ *   mode  contracted mode; must be 2 (the mode stored in the last level), else
+ *         COMET_ERR_UNSUPPORTED.
+ *   v     device, [dims[2]].
+ *   Y     host; *Y must be NULL or a handle returned earlier by this call for the same X.
+ *         On return *Y is an order-2 sparse result with the uncontracted levels of X:
+ *         [CU,CU] whose pos/crd are X's level-0/1 arrays (shared, not copied) for CSF input,
+ *         [CN,S] listing the distinct (i,j) in order for COO input.  One value per stored
+ *         (i,j), kept even when the sum is exactly 0.  Release with comet_tensor_destroy. */
+comet_status comet_ttv(const comet_tensor *X, int mode, const double *v, comet_tensor **Y, void *stream);
+
+/* SpTTM, Y = X x_mode U :  y_ijr = sum_k x_ijk u_kr   (Section 8.2, SpTTM; R takes the place
+ * of the contracted mode).
+ *   X     order-3 handle, [CU,CU,CU].      mode  must be 2.
+ *   U     device, [dims[2] x R] row-major, 1 <= R <= 1024.
+ *   Y     as for comet_ttv; the result is [CU,CU,D] with dims (I, J, R): levels 0/1 shared
+ *         with X, a dense last level of size R, vals of [#fibers x R] row-major. */
+comet_status comet_ttm(const comet_tensor *X, int mode, const double *U, int64_t R,
+                       comet_tensor **Y, void *stream);
+
+/* MTTKRP, M = X_(mode) (C (.) B) :  m_ir = sum_jk x_ijk b_jr c_kr.  The paper names the operation
+ * (Section 8.3) without defining it; this is the usual definition with the output indexed by
+ * the mode stored in the root level.
+ *   X        order-3 handle, [CU,CU,CU].   mode  must be 0.
+ *   factors  host array of 3 device pointers; factors[1] = B [dims[1] x R], factors[2] = C
+ *            [dims[2] x R], row-major; factors[mode] is ignored.
+ *   M        device, [dims[0] x R] row-major, overwritten (rows without a stored slice = 0). */
+comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *factors,
+                          int64_t R, double *M, void *stream);
+
+/* Human-readable name of a status (static string). */
+const char *comet_status_string(comet_status s);
+
+/* Choose the kernel family used by later operations on this handle: 0 = automatic,
+ * 1 = the simple one-lane-group-per-segment kernels, 2 = the nonzero-tiled streaming kernels.
+ * For testing and measurement; results are the same up to summation order. */
+comet_status comet_tensor_set_variant(comet_tensor *t, int variant);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COMET_H */

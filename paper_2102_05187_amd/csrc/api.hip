@@ -1,0 +1,463 @@
+// C ABI of the library: tensor construction from per-level pos/crd/vals, structure validation,
+// schedule building, and dispatch of the five contractions to the HIP kernels.
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "kernels.hpp"
+#include "stream_kernels.hpp"
+#include "tensor.hpp"
+
+using comet::DevRef;
+using comet::Format;
+
+#define HIP_TRY(expr)                                              \
+    do {                                                           \
+        hipError_t e_ = (expr);                                    \
+        if (e_ != hipSuccess) { (void)hipGetLastError(); return COMET_ERR_DEVICE; } \
+    } while (0)
+
+namespace {
+
+Format classify(int order, const int32_t *lv) {
+    if (order == 2) {
+        if (lv[0] == COMET_D && lv[1] == COMET_CU) return Format::CSR;
+        if (lv[0] == COMET_CU && lv[1] == COMET_CU) return Format::DCSR;
+        if (lv[0] == COMET_CN && lv[1] == COMET_S) return Format::COO2;
+    } else if (order == 3) {
+        if (lv[0] == COMET_CN && lv[1] == COMET_S && lv[2] == COMET_S) return Format::COO3;
+        if (lv[0] == COMET_CU && lv[1] == COMET_CU && lv[2] == COMET_CU) return Format::CSF3;
+        if (lv[0] == COMET_CU && lv[1] == COMET_CU && lv[2] == COMET_D) return Format::CSF3_DENSE_LEAF;
+    }
+    return Format::OTHER;
+}
+
+// number of positions of level l given the number of positions of its parent
+int64_t level_positions(const comet_tensor &t, int l, int64_t parent_positions) {
+    switch (t.levels[l]) {
+    case COMET_D:  return parent_positions * t.dims[l];
+    case COMET_CU: return t.crd_len[l];
+    case COMET_CN: return t.crd_len[l];
+    case COMET_S:  return parent_positions;
+    }
+    return -1;
+}
+
+comet_status read_i32(const int32_t *dev, int n, int32_t *host, hipStream_t st) {
+    HIP_TRY(hipMemcpyAsync(host, dev, sizeof(int32_t) * n, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    return COMET_OK;
+}
+
+// Builds the tile tables of the nonzero-tiled kernels for the formats that have them.
+comet_status build_schedule(comet_tensor &t, hipStream_t st) {
+    comet::Schedule &sc = t.sched;
+    const int tile = comet::kTile;
+    int leaf = -1;
+    if (t.fmt == Format::CSR || t.fmt == Format::DCSR) leaf = 1;
+    else if (t.fmt == Format::CSF3) leaf = 2;
+    if (leaf >= 0) {
+        sc.nnz = t.crd_len[leaf];
+        sc.nseg = t.pos_len[leaf] - 1;
+        sc.ntiles = (sc.nnz + tile - 1) / tile;
+        sc.seg_begin = comet::dev_alloc(sizeof(int32_t) * (sc.ntiles + 1));
+        if (!sc.seg_begin) return COMET_ERR_ALLOC;
+        HIP_TRY(comet::build_seg_begin(t.pos_i(leaf), sc.nseg, sc.nnz, tile, sc.ntiles,
+                                       (int32_t *)sc.seg_begin->ptr, st));
+        if (t.fmt == Format::CSF3) {
+            sc.slice_begin = comet::dev_alloc(sizeof(int32_t) * (sc.ntiles + 1));
+            if (!sc.slice_begin) return COMET_ERR_ALLOC;
+            HIP_TRY(comet::build_parent_begin(t.pos_i(1), t.pos_len[1] - 1, (const int32_t *)sc.seg_begin->ptr,
+                                              sc.ntiles, (int32_t *)sc.slice_begin->ptr, st));
+        }
+        DevRef mx = comet::dev_alloc(sizeof(int32_t));
+        if (!mx) return COMET_ERR_ALLOC;
+        HIP_TRY(hipMemsetAsync(mx->ptr, 0, sizeof(int32_t), st));
+        HIP_TRY(comet::max_segment_length(t.pos_i(leaf), sc.nseg, (int32_t *)mx->ptr, st));
+        int32_t h = 0;
+        comet_status rs = read_i32((const int32_t *)mx->ptr, 1, &h, st);
+        if (rs != COMET_OK) return rs;
+        sc.max_seg_len = h;
+    } else if (t.fmt == Format::COO3) {
+        sc.nnz = t.nvals;
+        sc.ntiles = (sc.nnz + tile - 1) / tile;
+        sc.run_base = comet::dev_alloc(sizeof(int32_t) * (sc.ntiles + 1));
+        if (!sc.run_base) return COMET_ERR_ALLOC;
+        HIP_TRY(comet::build_run_base(t.crd_i(0), t.crd_i(1), sc.nnz, tile, sc.ntiles,
+                                      (int32_t *)sc.run_base->ptr, st));
+        int32_t h = 0;
+        comet_status rs = read_i32((const int32_t *)sc.run_base->ptr + sc.ntiles, 1, &h, st);
+        if (rs != COMET_OK) return rs;
+        sc.nruns = h;
+        sc.nseg = h;
+    }
+    HIP_TRY(hipStreamSynchronize(st));
+    return COMET_OK;
+}
+
+comet_status validate_on_device(const comet_tensor &t, hipStream_t st) {
+    DevRef err = comet::dev_alloc(sizeof(int32_t));
+    if (!err) return COMET_ERR_ALLOC;
+    int32_t *e = (int32_t *)err->ptr;
+    HIP_TRY(hipMemsetAsync(e, 0, sizeof(int32_t), st));
+    for (int l = 0; l < t.order; ++l) {
+        if (t.levels[l] == COMET_CU) {
+            HIP_TRY(comet::check_pos(t.pos_i(l), t.pos_len[l], t.crd_len[l], e, st));
+            HIP_TRY(comet::check_crd_range(t.crd_i(l), t.crd_len[l], t.dims[l], e, st));
+        } else if (t.levels[l] == COMET_CN || t.levels[l] == COMET_S) {
+            HIP_TRY(comet::check_crd_range(t.crd_i(l), t.crd_len[l], t.dims[l], e, st));
+        }
+    }
+    int32_t h = 0;
+    comet_status rs = read_i32(e, 1, &h, st);
+    if (rs != COMET_OK) return rs;
+    if (h) return COMET_ERR_BAD_FORMAT;       // order checks below index through pos, so stop here
+    for (int l = 0; l < t.order; ++l)
+        if (t.levels[l] == COMET_CU)
+            HIP_TRY(comet::check_cu_sorted(t.pos_i(l), t.pos_len[l] - 1, t.crd_i(l), t.crd_len[l], e, st));
+    if (t.levels[0] == COMET_CN)
+        HIP_TRY(comet::check_coo_sorted(t.order, t.crd_i(0), t.crd_i(1), t.order > 2 ? t.crd_i(2) : nullptr,
+                                        t.nvals, e, st));
+    rs = read_i32(e, 1, &h, st);
+    if (rs != COMET_OK) return rs;
+    return h ? COMET_ERR_BAD_FORMAT : COMET_OK;
+}
+
+comet_status ensure_scratch(const comet_tensor *t, size_t bytes) {
+    comet_tensor *m = const_cast<comet_tensor *>(t);
+    if (m->scratch && m->scratch_bytes >= bytes) return COMET_OK;
+    m->scratch.reset();
+    m->scratch = comet::dev_alloc(bytes);
+    if (!m->scratch) { m->scratch_bytes = 0; return COMET_ERR_ALLOC; }
+    m->scratch_bytes = bytes;
+    return COMET_OK;
+}
+
+bool use_tiled(const comet_tensor *t, int64_t R) {
+    if (t->variant == 1) return false;
+    if (!comet::stream_supports_rank(R)) return false;
+    if (t->variant == 2) return true;
+    return true;
+}
+
+// A fresh result handle for TTV / TTM on `X`, or the caller's handle if it fits.
+comet_status result_handle(const comet_tensor *X, int kind, int64_t R, comet_tensor **Y, bool *fresh) {
+    *fresh = false;
+    if (*Y) {
+        comet_tensor *y = *Y;
+        if (y->result_of != X || y->result_kind != kind || y->result_R != R) return COMET_ERR_INVALID_ARG;
+        return COMET_OK;
+    }
+    comet_tensor *y = new (std::nothrow) comet_tensor();
+    if (!y) return COMET_ERR_ALLOC;
+    y->result_of = X; y->result_kind = kind; y->result_R = R;
+    *Y = y;
+    *fresh = true;
+    return COMET_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *comet_status_string(comet_status s) {
+    switch (s) {
+    case COMET_OK: return "ok";
+    case COMET_ERR_INVALID_ARG: return "invalid argument";
+    case COMET_ERR_BAD_FORMAT: return "arrays do not form a valid tensor of the stated level formats";
+    case COMET_ERR_SHAPE: return "operand shape mismatch";
+    case COMET_ERR_UNSUPPORTED: return "unsupported level tuple, mode or rank";
+    case COMET_ERR_ALLOC: return "allocation failed";
+    case COMET_ERR_DEVICE: return "HIP call failed";
+    }
+    return "unknown status";
+}
+
+comet_status comet_tensor_create(comet_tensor **out, int order, const int64_t *dims, const comet_level_t *levels,
+                                 const int32_t *const *pos, const int64_t *pos_len,
+                                 const int32_t *const *crd, const int64_t *crd_len,
+                                 const double *vals, int64_t nvals, unsigned flags, void *stream) {
+    if (!out) return COMET_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!dims || !levels || !pos || !pos_len || !crd || !crd_len) return COMET_ERR_INVALID_ARG;
+    if (order < 1 || order > COMET_MAX_ORDER) return COMET_ERR_UNSUPPORTED;
+    if (nvals < 0 || nvals >= (int64_t(1) << 31)) return COMET_ERR_INVALID_ARG;
+    if (nvals > 0 && !vals) return COMET_ERR_INVALID_ARG;
+    if (flags & ~(COMET_COPY | COMET_VALIDATE)) return COMET_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+
+    comet_tensor *t = new (std::nothrow) comet_tensor();
+    if (!t) return COMET_ERR_ALLOC;
+    std::unique_ptr<comet_tensor> guard(t);
+    t->order = order;
+    t->nvals = nvals;
+    for (int l = 0; l < order; ++l) {
+        if (dims[l] < 0 || dims[l] >= (int64_t(1) << 31)) return COMET_ERR_INVALID_ARG;
+        if ((int)levels[l] < 0 || (int)levels[l] > 3) return COMET_ERR_INVALID_ARG;
+        if (pos_len[l] < 0 || crd_len[l] < 0) return COMET_ERR_INVALID_ARG;
+        if (pos_len[l] >= (int64_t(1) << 31) || crd_len[l] >= (int64_t(1) << 31)) return COMET_ERR_INVALID_ARG;
+        if ((pos_len[l] > 0 && !pos[l]) || (crd_len[l] > 0 && !crd[l])) return COMET_ERR_INVALID_ARG;
+        t->dims[l] = dims[l];
+        t->levels[l] = (int32_t)levels[l];
+        t->pos_len[l] = pos_len[l];
+        t->crd_len[l] = crd_len[l];
+    }
+    t->fmt = classify(order, t->levels);
+    if (t->fmt == Format::OTHER) return COMET_ERR_UNSUPPORTED;
+
+    // -- cheap structural checks: array lengths per level, contents of the short pos arrays ------
+    int64_t parent = 1;
+    for (int l = 0; l < order; ++l) {
+        int32_t h[2] = {0, 0};
+        switch (t->levels[l]) {
+        case COMET_D:
+            if (pos_len[l] != 1 || crd_len[l] != 0) return COMET_ERR_BAD_FORMAT;
+            { comet_status rs = read_i32(pos[l], 1, h, st); if (rs != COMET_OK) return rs; }
+            if ((int64_t)h[0] != dims[l]) return COMET_ERR_BAD_FORMAT;
+            break;
+        case COMET_CU:
+            if (pos_len[l] != parent + 1) return COMET_ERR_BAD_FORMAT;
+            if (l == 0) {
+                comet_status rs = read_i32(pos[l], 2, h, st); if (rs != COMET_OK) return rs;
+                if (h[0] != 0 || (int64_t)h[1] != crd_len[l]) return COMET_ERR_BAD_FORMAT;
+            }
+            break;
+        case COMET_CN:
+            if (l != 0 || pos_len[l] != 2) return COMET_ERR_BAD_FORMAT;
+            { comet_status rs = read_i32(pos[l], 2, h, st); if (rs != COMET_OK) return rs; }
+            if (h[0] != 0 || (int64_t)h[1] != crd_len[l]) return COMET_ERR_BAD_FORMAT;
+            break;
+        case COMET_S:
+            if (l == 0 || pos_len[l] != 0 || crd_len[l] != parent) return COMET_ERR_BAD_FORMAT;
+            break;
+        }
+        parent = level_positions(*t, l, parent);
+        if (parent < 0 || parent >= (int64_t(1) << 31)) return COMET_ERR_BAD_FORMAT;
+    }
+    if (parent != nvals) return COMET_ERR_BAD_FORMAT;
+
+    // -- take (borrow or copy) the arrays -------------------------------------------------------
+    auto take = [&](const void *p, size_t bytes, DevRef &dst) -> comet_status {
+        if (!p || bytes == 0) { dst = (flags & COMET_COPY) ? comet::dev_alloc(16) : comet::borrow(p, 0); return dst ? COMET_OK : COMET_ERR_ALLOC; }
+        if (flags & COMET_COPY) {
+            dst = comet::dev_alloc(bytes);
+            if (!dst) return COMET_ERR_ALLOC;
+            HIP_TRY(hipMemcpyAsync(dst->ptr, p, bytes, hipMemcpyDeviceToDevice, st));
+        } else {
+            dst = comet::borrow(p, bytes);
+        }
+        return COMET_OK;
+    };
+    for (int l = 0; l < order; ++l) {
+        comet_status rs;
+        if (pos_len[l] > 0) { rs = take(pos[l], sizeof(int32_t) * pos_len[l], t->pos[l]); if (rs != COMET_OK) return rs; }
+        if (crd_len[l] > 0 || t->levels[l] != COMET_D) {
+            rs = take(crd[l], sizeof(int32_t) * crd_len[l], t->crd[l]); if (rs != COMET_OK) return rs;
+        }
+    }
+    { comet_status rs = take(vals, sizeof(double) * nvals, t->vals); if (rs != COMET_OK) return rs; }
+
+    // The tile tables index through pos, so pos arrays are always checked; the rest on request.
+    if (flags & COMET_VALIDATE) {
+        comet_status rs = validate_on_device(*t, st);
+        if (rs != COMET_OK) return rs;
+    } else {
+        DevRef err = comet::dev_alloc(sizeof(int32_t));
+        if (!err) return COMET_ERR_ALLOC;
+        HIP_TRY(hipMemsetAsync(err->ptr, 0, sizeof(int32_t), st));
+        for (int l = 0; l < order; ++l)
+            if (t->levels[l] == COMET_CU)
+                HIP_TRY(comet::check_pos(t->pos_i(l), t->pos_len[l], t->crd_len[l], (int32_t *)err->ptr, st));
+        int32_t h = 0;
+        comet_status rs = read_i32((const int32_t *)err->ptr, 1, &h, st);
+        if (rs != COMET_OK) return rs;
+        if (h) return COMET_ERR_BAD_FORMAT;
+    }
+    comet_status rs = build_schedule(*t, st);
+    if (rs != COMET_OK) return rs;
+    *out = guard.release();
+    return COMET_OK;
+}
+
+comet_status comet_tensor_destroy(comet_tensor *t) {
+    if (!t) return COMET_OK;
+    (void)hipDeviceSynchronize();
+    delete t;
+    return COMET_OK;
+}
+
+comet_status comet_tensor_info(const comet_tensor *t, comet_tensor_info_t *info) {
+    if (!t || !info) return COMET_ERR_INVALID_ARG;
+    std::memset(info, 0, sizeof(*info));
+    info->order = t->order;
+    for (int l = 0; l < t->order; ++l) {
+        info->dims[l] = t->dims[l];
+        info->levels[l] = t->levels[l];
+        info->pos[l] = t->pos_len[l] ? t->pos_i(l) : nullptr;
+        info->pos_len[l] = t->pos_len[l];
+        info->crd[l] = t->crd_len[l] ? t->crd_i(l) : nullptr;
+        info->crd_len[l] = t->crd_len[l];
+    }
+    info->vals = t->nvals ? t->vals_d() : nullptr;
+    info->nvals = t->nvals;
+    return COMET_OK;
+}
+
+comet_status comet_tensor_set_variant(comet_tensor *t, int variant) {
+    if (!t || variant < 0 || variant > 2) return COMET_ERR_INVALID_ARG;
+    t->variant = variant;
+    return COMET_OK;
+}
+
+// ---- SpMV / SpMM: the last level is compressed; rows come from a dense or compressed root -------
+static comet_status matrix_product(const comet_tensor *A, const double *Dn, int64_t R, double *out, hipStream_t st) {
+    if (!A || !Dn || !out) return COMET_ERR_INVALID_ARG;
+    if (A->fmt != Format::CSR && A->fmt != Format::DCSR) return COMET_ERR_UNSUPPORTED;
+    if (R < 1 || R > 1024) return COMET_ERR_UNSUPPORTED;
+    const int64_t nseg = A->pos_len[1] - 1, nnz = A->nvals;
+    const int32_t *rowmap = nullptr;
+    if (A->fmt == Format::DCSR) {
+        // rows absent from the root level hold no nonzeros: clear the result, then scatter rows
+        rowmap = A->crd_i(0);
+        HIP_TRY(comet::fill_zero_f64(out, A->dims[0] * R, st));
+    }
+    if (nnz == 0) {
+        if (A->fmt == Format::CSR) HIP_TRY(comet::fill_zero_f64(out, A->dims[0] * R, st));
+        return COMET_OK;
+    }
+    if (use_tiled(A, R)) {
+        size_t need = comet::stream_scratch_bytes(A->sched.ntiles, R);
+        comet_status rs = ensure_scratch(A, need);
+        if (rs != COMET_OK) return rs;
+        HIP_TRY(comet::stream_segreduce(A->sched, A->pos_i(1), A->crd_i(1), A->vals_d(), rowmap, Dn, R, out,
+                                        A->scratch->ptr, st));
+        return COMET_OK;
+    }
+    HIP_TRY(comet::simple_segreduce(A->pos_i(1), A->crd_i(1), A->vals_d(), nseg, nnz, rowmap, Dn, R, out, st));
+    return COMET_OK;
+}
+
+comet_status comet_spmv(const comet_tensor *A, const double *x, double *y, void *stream) {
+    return matrix_product(A, x, 1, y, (hipStream_t)stream);
+}
+
+comet_status comet_spmm(const comet_tensor *A, const double *B, int64_t R, double *C, void *stream) {
+    return matrix_product(A, B, R, C, (hipStream_t)stream);
+}
+
+// ---- TTV / TTM along the mode stored in the last level ------------------------------------------
+static comet_status leaf_contract(const comet_tensor *X, int mode, const double *Dn, int64_t R, int kind,
+                                  comet_tensor **Y, hipStream_t st) {
+    if (!X || !Dn || !Y) return COMET_ERR_INVALID_ARG;
+    if (X->order != 3) return COMET_ERR_UNSUPPORTED;
+    if (R < 1 || R > 1024) return COMET_ERR_UNSUPPORTED;
+    const bool csf = X->fmt == Format::CSF3, coo = X->fmt == Format::COO3;
+    if (!csf && !(coo && kind == 1)) return COMET_ERR_UNSUPPORTED;
+    if (mode != 2) return mode >= 0 && mode < 3 ? COMET_ERR_UNSUPPORTED : COMET_ERR_INVALID_ARG;
+    bool fresh = false;
+    comet_status rs = result_handle(X, kind, R, Y, &fresh);
+    if (rs != COMET_OK) return rs;
+    comet_tensor *y = *Y;
+    std::unique_ptr<comet_tensor> guard(fresh ? y : nullptr);
+    if (fresh) *Y = nullptr;
+    const int64_t nout = csf ? X->crd_len[1] : X->sched.nruns;    // stored (i,j) pairs
+    if (fresh) {
+        y->order = kind == 1 ? 2 : 3;
+        y->dims[0] = X->dims[0]; y->dims[1] = X->dims[1];
+        if (csf) {
+            y->levels[0] = COMET_CU; y->levels[1] = COMET_CU;
+            for (int l = 0; l < 2; ++l) {
+                y->pos[l] = X->pos[l]; y->crd[l] = X->crd[l];
+                y->pos_len[l] = X->pos_len[l]; y->crd_len[l] = X->crd_len[l];
+            }
+        } else {
+            y->levels[0] = COMET_CN; y->levels[1] = COMET_S;
+            y->pos[0] = comet::dev_alloc(2 * sizeof(int32_t));
+            y->crd[0] = comet::dev_alloc(sizeof(int32_t) * nout);
+            y->crd[1] = comet::dev_alloc(sizeof(int32_t) * nout);
+            if (!y->pos[0] || !y->crd[0] || !y->crd[1]) return COMET_ERR_ALLOC;
+            int32_t h[2] = {0, (int32_t)nout};
+            HIP_TRY(hipMemcpyAsync(y->pos[0]->ptr, h, sizeof h, hipMemcpyHostToDevice, st));
+            HIP_TRY(hipStreamSynchronize(st));
+            y->pos_len[0] = 2; y->crd_len[0] = nout; y->crd_len[1] = nout;
+        }
+        if (kind == 2) {
+            y->dims[2] = R; y->levels[2] = COMET_D;
+            y->pos[2] = comet::dev_alloc(sizeof(int32_t));
+            if (!y->pos[2]) return COMET_ERR_ALLOC;
+            int32_t h = (int32_t)R;
+            HIP_TRY(hipMemcpyAsync(y->pos[2]->ptr, &h, sizeof h, hipMemcpyHostToDevice, st));
+            HIP_TRY(hipStreamSynchronize(st));
+            y->pos_len[2] = 1;
+        }
+        if (nout * R >= (int64_t(1) << 31)) return COMET_ERR_UNSUPPORTED;
+        y->nvals = nout * R;
+        y->vals = comet::dev_alloc(sizeof(double) * y->nvals);
+        if (!y->vals) return COMET_ERR_ALLOC;
+        y->fmt = classify(y->order, y->levels);
+    }
+    double *yv = (double *)y->vals->ptr;
+    if (X->nvals > 0) {
+        if (csf) {
+            if (use_tiled(X, R)) {
+                rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.ntiles, R));
+                if (rs != COMET_OK) return rs;
+                HIP_TRY(comet::stream_segreduce(X->sched, X->pos_i(2), X->crd_i(2), X->vals_d(), nullptr, Dn, R, yv,
+                                                X->scratch->ptr, st));
+            } else {
+                HIP_TRY(comet::simple_segreduce(X->pos_i(2), X->crd_i(2), X->vals_d(), X->pos_len[2] - 1, X->nvals,
+                                                nullptr, Dn, R, yv, st));
+            }
+        } else {
+            if (use_tiled(X, 1)) {
+                rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.ntiles, 1));
+                if (rs != COMET_OK) return rs;
+                HIP_TRY(comet::stream_ttv_coo(X->sched, X->crd_i(0), X->crd_i(1), X->crd_i(2), X->vals_d(), Dn,
+                                              (int32_t *)y->crd[0]->ptr, (int32_t *)y->crd[1]->ptr, yv,
+                                              X->scratch->ptr, st));
+            } else {
+                HIP_TRY(comet::simple_ttv_coo(X->crd_i(0), X->crd_i(1), X->crd_i(2), X->vals_d(), X->nvals, comet::kTile,
+                                              X->sched.ntiles, (const int32_t *)X->sched.run_base->ptr, Dn,
+                                              (int32_t *)y->crd[0]->ptr, (int32_t *)y->crd[1]->ptr, yv, st));
+            }
+        }
+    } else if (y->nvals > 0) {
+        HIP_TRY(comet::fill_zero_f64(yv, y->nvals, st));   // stored fibers that hold no nonzero
+    }
+    if (fresh) *Y = guard.release();
+    return COMET_OK;
+}
+
+comet_status comet_ttv(const comet_tensor *X, int mode, const double *v, comet_tensor **Y, void *stream) {
+    return leaf_contract(X, mode, v, 1, 1, Y, (hipStream_t)stream);
+}
+
+comet_status comet_ttm(const comet_tensor *X, int mode, const double *U, int64_t R, comet_tensor **Y, void *stream) {
+    return leaf_contract(X, mode, U, R, 2, Y, (hipStream_t)stream);
+}
+
+comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *factors, int64_t R, double *M,
+                          void *stream) {
+    if (!X || !factors || !M) return COMET_ERR_INVALID_ARG;
+    if (X->fmt != Format::CSF3) return COMET_ERR_UNSUPPORTED;
+    if (mode != 0) return mode >= 0 && mode < 3 ? COMET_ERR_UNSUPPORTED : COMET_ERR_INVALID_ARG;
+    if (R < 1 || R > 1024) return COMET_ERR_UNSUPPORTED;
+    const double *B = factors[1], *C = factors[2];
+    if (!B || !C) return COMET_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    // rows of M whose index is not stored at the root level receive no contribution
+    HIP_TRY(comet::fill_zero_f64(M, X->dims[0] * R, st));
+    if (X->nvals == 0) return COMET_OK;
+    if (use_tiled(X, R) && comet::stream_mttkrp_supports_rank(R)) {
+        comet_status rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.ntiles, R));
+        if (rs != COMET_OK) return rs;
+        HIP_TRY(comet::stream_mttkrp(X->sched, X->pos_i(1), X->crd_i(0), X->pos_len[1] - 1, X->pos_i(2), X->crd_i(1),
+                                     X->crd_i(2), X->vals_d(), B, C, R, M, X->scratch->ptr, st));
+        return COMET_OK;
+    }
+    HIP_TRY(comet::simple_mttkrp(X->pos_i(1), X->crd_i(0), X->pos_len[1] - 1, X->pos_i(2), X->crd_i(1), X->crd_i(2),
+                                 X->vals_d(), B, C, R, M, st));
+    return COMET_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,46 @@
+// Launchers of the HIP kernels (host functions; definitions in the .hip files).
+// All pointers are device pointers; every launcher only enqueues work on `st`.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace comet {
+
+// ---- utilities (util.hip) -----------------------------------------------------------------------
+hipError_t fill_zero_f64(double *p, int64_t n, hipStream_t st);
+hipError_t fill_i32(int32_t *p, int64_t n, int32_t value, hipStream_t st);
+
+// Structure checks; each ORs a bit into *err (device int32, zeroed by the caller) on failure.
+hipError_t check_pos(const int32_t *pos, int64_t n, int64_t last, int32_t *err, hipStream_t st);
+hipError_t check_crd_range(const int32_t *crd, int64_t n, int64_t dim, int32_t *err, hipStream_t st);
+hipError_t check_cu_sorted(const int32_t *pos, int64_t nseg, const int32_t *crd, int64_t n, int32_t *err,
+                           hipStream_t st);
+hipError_t check_coo_sorted(int order, const int32_t *c0, const int32_t *c1, const int32_t *c2, int64_t n,
+                            int32_t *err, hipStream_t st);
+
+// Schedule tables (see Schedule in tensor.hpp).
+hipError_t build_seg_begin(const int32_t *pos, int64_t nseg, int64_t nnz, int tile, int64_t ntiles,
+                           int32_t *seg_begin, hipStream_t st);
+hipError_t build_parent_begin(const int32_t *parent_pos, int64_t nparent, const int32_t *seg_begin,
+                              int64_t ntiles, int32_t *parent_begin, hipStream_t st);
+hipError_t build_run_base(const int32_t *c0, const int32_t *c1, int64_t nnz, int tile, int64_t ntiles,
+                          int32_t *run_base /* [ntiles+1] */, hipStream_t st);
+hipError_t max_segment_length(const int32_t *pos, int64_t nseg, int32_t *out_max, hipStream_t st);
+
+// ---- simple family (kernels_simple.hip): one lane group / thread per output element -------------
+// out[row(s), :] = sum_{p in [pos[s], pos[s+1])} vals[p] * Dn[crd[p], :]   for s in [0, nseg)
+// row(s) = rowmap ? rowmap[s] : s.   R == 1 reads Dn as a vector.
+hipError_t simple_segreduce(const int32_t *pos, const int32_t *crd, const double *vals, int64_t nseg,
+                            int64_t nnz, const int32_t *rowmap, const double *Dn, int64_t R, double *out,
+                            hipStream_t st);
+// M[crd1[s], :] = sum_{f in slice s} B[crd2[f], :] * (sum_{p in fiber f} vals[p] * C[crd3[p], :])
+hipError_t simple_mttkrp(const int32_t *pos2, const int32_t *crd1, int64_t nslice, const int32_t *pos3,
+                         const int32_t *crd2, const int32_t *crd3, const double *vals, const double *B,
+                         const double *C, int64_t R, double *M, hipStream_t st);
+// Sorted COO [CN,S,S]: distinct (i,j) runs -> ycrd0/ycrd1/yvals (run_base from the schedule).
+hipError_t simple_ttv_coo(const int32_t *c0, const int32_t *c1, const int32_t *c2, const double *vals,
+                          int64_t nnz, int tile, int64_t ntiles, const int32_t *run_base, const double *v,
+                          int32_t *ycrd0, int32_t *ycrd1, double *yvals, hipStream_t st);
+
+}  // namespace comet

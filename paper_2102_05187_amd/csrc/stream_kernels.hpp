@@ -1,0 +1,38 @@
+// Launchers of the nonzero-tiled streaming kernels (definitions in kernels_stream.hip).
+//
+// The leaf level's nonzeros are processed in tiles of kTile consecutive positions regardless of
+// where segment (row / fiber / slice) boundaries fall, so a power-law head segment is spread
+// over many workgroups.  Partial sums of segments cut by a tile boundary go through a small
+// carry buffer in `scratch` and are completed by a fix-up kernel in a fixed order (no atomics,
+// results are reproducible run to run).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+#include "tensor.hpp"
+
+namespace comet {
+
+bool   stream_supports_rank(int64_t R);
+bool   stream_mttkrp_supports_rank(int64_t R);
+size_t stream_scratch_bytes(int64_t ntiles, int64_t R);
+
+// out[row(s), :] = sum_{p in segment s} vals[p] * Dn[crd[p], :],  row(s) = rowmap ? rowmap[s] : s.
+// Every segment of the level is written (empty ones with zeros).
+hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
+                            const int32_t *rowmap, const double *Dn, int64_t R, double *out, void *scratch,
+                            hipStream_t st);
+
+// Sorted COO [CN,S,S]: one output (i, j, value) per run of equal (c0, c1).
+hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *c1, const int32_t *c2,
+                          const double *vals, const double *v, int32_t *y0, int32_t *y1, double *yv,
+                          void *scratch, hipStream_t st);
+
+// M[crd1[s], :] = sum_{f in slice s} B[crd2[f], :] * (sum_{p in fiber f} vals[p] * C[crd3[p], :]).
+// M must have been cleared for rows that have no stored slice.
+hipError_t stream_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t *crd1, int64_t nslice,
+                         const int32_t *pos3, const int32_t *crd2, const int32_t *crd3, const double *vals,
+                         const double *B, const double *C, int64_t R, double *M, void *scratch, hipStream_t st);
+
+}  // namespace comet

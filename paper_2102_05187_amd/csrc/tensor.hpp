@@ -1,0 +1,87 @@
+// Level-format tensor descriptor (host side) shared by the API and the kernel launchers.
+//
+// A tensor is `order` levels, each tagged D / CU / CN / S and carrying int32 pos / crd arrays,
+// plus one fp64 value array (paper Section 4 and Section 6.1 "Sparse Tensor Data Type").  The
+// arrays live in device memory; the descriptor keeps them behind reference-counted holders so a
+// TTV / TTM result can share the uncontracted levels of its input without copying them.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include <memory>
+#include <vector>
+
+#include "../../include/comet.h"
+
+namespace comet {
+
+// One device array; frees its memory on destruction only if the library allocated it.
+struct DevArray {
+    void  *ptr   = nullptr;
+    size_t bytes = 0;
+    bool   owned = false;
+    DevArray() = default;
+    DevArray(void *p, size_t b, bool o) : ptr(p), bytes(b), owned(o) {}
+    DevArray(const DevArray &) = delete;
+    DevArray &operator=(const DevArray &) = delete;
+    ~DevArray() { if (owned && ptr) (void)hipFree(ptr); }
+};
+using DevRef = std::shared_ptr<DevArray>;
+
+inline DevRef borrow(const void *p, size_t bytes) {
+    return std::make_shared<DevArray>(const_cast<void *>(p), bytes, false);
+}
+// Allocates `bytes` of device memory (at least 16 so that empty arrays still have an address).
+inline DevRef dev_alloc(size_t bytes) {
+    void *p = nullptr;
+    if (hipMalloc(&p, bytes < 16 ? 16 : bytes) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+    return std::make_shared<DevArray>(p, bytes, true);
+}
+
+enum class Format { CSR, DCSR, COO2, COO3, CSF3, CSF3_DENSE_LEAF, OTHER };
+
+// Items per tile of the nonzero-tiled kernels (a multiple of every per-wave chunk they use).
+constexpr int kTile = 4096;
+
+// Per-tensor schedule for the nonzero-tiled kernels, built once at creation.
+//   The leaf level's nonzeros are cut into tiles of kTile consecutive positions; seg_begin[t] is
+//   the segment (row / fiber) that contains the first nonzero of tile t (seg_begin[0] = 0 and
+//   seg_begin[ntiles] = nseg, so leading and trailing empty segments belong to the first and
+//   last tile).  For CSF, slice_begin[t] is the slice that contains fiber seg_begin[t].
+//   For sorted COO, run_base[t] counts the distinct (i,j) runs that start before tile t.
+struct Schedule {
+    int64_t nnz = 0, nseg = 0, ntiles = 0;
+    DevRef  seg_begin;     // int32 [ntiles + 1]
+    DevRef  slice_begin;   // int32 [ntiles + 1]   (CSF3 only)
+    DevRef  run_base;      // int32 [ntiles + 1]   (COO3 only)
+    int64_t nruns = 0;     // COO3: number of distinct (i,j) pairs
+    int64_t max_seg_len = 0;
+};
+
+}  // namespace comet
+
+struct comet_tensor {
+    int32_t order = 0;
+    int64_t dims[COMET_MAX_ORDER] = {0, 0, 0, 0};
+    int32_t levels[COMET_MAX_ORDER] = {0, 0, 0, 0};
+    comet::DevRef pos[COMET_MAX_ORDER], crd[COMET_MAX_ORDER], vals;
+    int64_t pos_len[COMET_MAX_ORDER] = {0, 0, 0, 0};
+    int64_t crd_len[COMET_MAX_ORDER] = {0, 0, 0, 0};
+    int64_t nvals = 0;
+    comet::Format fmt = comet::Format::OTHER;
+    comet::Schedule sched;
+    int variant = 0;
+
+    // scratch owned by the handle (carry buffers of the tiled kernels), grown on demand
+    comet::DevRef scratch;
+    size_t scratch_bytes = 0;
+
+    // results of TTV / TTM remember what produced them so the handle can be reused
+    const comet_tensor *result_of = nullptr;
+    int     result_kind = 0;   // 1 = TTV, 2 = TTM
+    int64_t result_R = 0;
+
+    const int32_t *pos_i(int l) const { return pos[l] ? static_cast<const int32_t *>(pos[l]->ptr) : nullptr; }
+    const int32_t *crd_i(int l) const { return crd[l] ? static_cast<const int32_t *>(crd[l]->ptr) : nullptr; }
+    const double  *vals_d() const { return vals ? static_cast<const double *>(vals->ptr) : nullptr; }
+};

@@ -1,0 +1,61 @@
+"""The C-ABI library builds, loads and exports every symbol the public header declares (CPU only)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib_path():
+    from paper_2102_05187_amd import build
+    return build.build_if_missing()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "comet.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(comet_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_six_calls_of_the_boundary():
+    names = _declared_symbols()
+    for n in ("comet_tensor_create", "comet_spmv", "comet_spmm", "comet_ttv", "comet_ttm", "comet_mttkrp"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol(lib_path):
+    lib = ctypes.CDLL(lib_path)
+    for n in _declared_symbols():
+        assert hasattr(lib, n), n
+
+
+def test_binding_lists_the_same_symbols():
+    import paper_2102_05187_amd as comet
+    assert sorted(comet.EXPORTS) == _declared_symbols()
+
+
+def test_status_strings_without_a_gpu(lib_path):
+    lib = ctypes.CDLL(lib_path)
+    lib.comet_status_string.restype = ctypes.c_char_p
+    seen = {lib.comet_status_string(s) for s in range(7)}
+    assert len(seen) == 7 and all(seen)
+
+
+def test_product_package_does_not_reach_into_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2102_05187_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h", ".cpp")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src.lower(), "%s mentions the oracle" % f
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    import paper_2102_05187_amd as comet
+    with pytest.raises(TypeError):
+        comet.comet_tensor_create([2, 2], [0, 1], [torch.tensor([2], dtype=torch.int32), torch.tensor([0, 1, 2], dtype=torch.int32)],
+                                  [None, torch.tensor([0, 1], dtype=torch.int32)], torch.ones(2, dtype=torch.float64))

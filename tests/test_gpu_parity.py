@@ -1,0 +1,303 @@
+"""GPU parity: every operation through the C ABI against the CPU oracle, element by element.
+
+Sizes here are small enough for the oracle to finish in well under a second while still spanning
+several kernel tiles (4096 nonzeros each) and a ragged tail.  Index outputs must be bit-exact;
+values must satisfy |gpu - ref| <= 1e-10*|ref| + 1e-12*A with A = sum |term| from the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import formats as fmt
+from synth import generate as gen
+from util import assert_index_equal, assert_values_close, np_
+
+pytestmark = pytest.mark.gpu
+
+VARIANTS = [1, 0]          # 1 = simple kernels, 0 = automatic (tiled where specialised)
+
+
+@pytest.fixture(scope="module")
+def comet():
+    from paper_2102_05187_amd import build
+    build.build_if_missing()
+    import paper_2102_05187_amd as c
+    return c
+
+
+def dev(t):
+    return None if t is None else t.to("cuda")
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ----------------------------------------------------------------------------------------------
+# matrices
+# ----------------------------------------------------------------------------------------------
+def _matrix_cases():
+    cases = {}
+    c = gen.config_spmv(seed=0)
+    cases["config1"] = (c["dims"], c["coo"])
+    c = gen.config_spmm(seed=0, scale=0.004)
+    cases["zipf_rows"] = (c["dims"], c["coo"])
+    n = 3000
+    # one row holds every nonzero; all other rows empty (leading and trailing empties)
+    cols = torch.arange(n, dtype=torch.int64)
+    cases["one_full_row"] = ((9, n), (torch.full((n,), 4, dtype=torch.int64), cols,
+                                      gen.rng.uniform_pm1(5, 3, n)))
+    # rows of length 63 / 64 / 65 / 10000 / 1 and empty rows in between
+    lens = torch.tensor([63, 0, 64, 65, 0, 0, 10000, 1, 1, 0, 4097, 4095, 0], dtype=torch.int64)
+    cases["edge_lengths"] = ((len(lens), 20000), gen.matrix_from_row_lengths(len(lens), 20000, lens, 7))
+    cases["empty"] = ((5, 7), (torch.zeros(0, dtype=torch.int64), torch.zeros(0, dtype=torch.int64),
+                              torch.zeros(0, dtype=torch.float64)))
+    cases["single"] = ((5, 7), (torch.tensor([3]), torch.tensor([6]), torch.tensor([2.5], dtype=torch.float64)))
+    # hypersparse: far more rows than nonzeros
+    r, cc, v = gen.bernoulli_matrix(20000, 50, 0.001, 9)
+    cases["hypersparse"] = ((20000, 50), (r, cc, v))
+    return cases
+
+
+MATRIX_CASES = _matrix_cases()
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("layout", ["csr", "dcsr"])
+@pytest.mark.parametrize("name", list(MATRIX_CASES))
+def test_spmv(comet, name, layout, variant):
+    (I, J), (rows, cols, vals) = MATRIX_CASES[name]
+    say("spmv case=%s layout=%s variant=%d nnz=%d" % (name, layout, variant, vals.numel()))
+    pack = fmt.pack_csr if layout == "csr" else fmt.pack_dcsr
+    A = comet.from_levels(pack(I, J, rows, cols, vals).to("cuda")).set_variant(variant)
+    x = gen.dense_operand(1, 0, (J,))
+    y = torch.full((I,), float("nan"), dtype=torch.float64, device="cuda")
+    comet.comet_spmv(A, dev(x), y)
+    torch.cuda.synchronize()
+    ref, absum = oracle.spmv(np_(rows), np_(cols), np_(vals), (I, J), np_(x))
+    assert_values_close(np_(y), ref, absum, "spmv %s" % name)
+    y2 = comet.comet_spmv(A, dev(x))
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2), "two runs differ"
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("R", [1, 8, 16, 32, 64, 96])
+@pytest.mark.parametrize("name,layout", [("zipf_rows", "csr"), ("edge_lengths", "csr"), ("edge_lengths", "dcsr"),
+                                         ("empty", "csr"), ("hypersparse", "dcsr"), ("hypersparse", "csr")])
+def test_spmm(comet, name, layout, R, variant):
+    (I, J), (rows, cols, vals) = MATRIX_CASES[name]
+    say("spmm case=%s layout=%s R=%d variant=%d nnz=%d" % (name, layout, R, variant, vals.numel()))
+    pack = fmt.pack_csr if layout == "csr" else fmt.pack_dcsr
+    A = comet.from_levels(pack(I, J, rows, cols, vals).to("cuda")).set_variant(variant)
+    B = gen.dense_operand(2, 0, (J, R))
+    C = torch.full((I, R), float("nan"), dtype=torch.float64, device="cuda")
+    comet.comet_spmm(A, dev(B), C)
+    torch.cuda.synchronize()
+    ref, absum = oracle.spmm(np_(rows), np_(cols), np_(vals), (I, J), np_(B))
+    assert_values_close(np_(C), ref, absum, "spmm %s R=%d" % (name, R))
+
+
+def test_spmm_of_ones_gives_row_sums_in_every_column(comet):
+    """The paper's example program: B filled with 1.0."""
+    (I, J), (rows, cols, vals) = MATRIX_CASES["zipf_rows"]
+    A = comet.from_levels(fmt.pack_csr(I, J, rows, cols, vals).to("cuda"))
+    C = comet.comet_spmm(A, torch.ones((J, 32), dtype=torch.float64, device="cuda"))
+    y = comet.comet_spmv(A, torch.ones(J, dtype=torch.float64, device="cuda"))
+    torch.cuda.synchronize()
+    ref, absum = oracle.spmv(np_(rows), np_(cols), np_(vals), (I, J), np.ones(J))
+    assert_values_close(np_(y), ref, absum, "row sums")
+    for r in range(32):
+        assert_values_close(np_(C[:, r]), ref, absum, "column %d" % r)
+
+
+# ----------------------------------------------------------------------------------------------
+# order-3 tensors
+# ----------------------------------------------------------------------------------------------
+def _tensor_cases():
+    cases = {}
+    c = gen.config_ttv(seed=0, scale=4e-4, chunk=1 << 18)
+    cases["zipf_ttv"] = (c["dims"], c["coo"])
+    c = gen.config_ttm(seed=0, scale=3e-4, chunk=1 << 18)
+    cases["zipf_ttm"] = (c["dims"], c["coo"])
+    c = gen.config_mttkrp(seed=0, scale=2e-4, chunk=1 << 18)
+    cases["zipf_mttkrp"] = (c["dims"], c["coo"])
+    # a mode of size 2 (one of the paper's tensors has such a mode) and fibers of length 1 only
+    i, j, k, v = gen.bernoulli_tensor3((300, 40, 2), 0.3, 3)
+    cases["mode_of_two"] = ((300, 40, 2), (i, j, k, v))
+    i, j, k, v = gen.bernoulli_tensor3((64, 64, 1), 0.4, 4)
+    cases["unit_fibers"] = ((64, 64, 1), (i, j, k, v))
+    # one slice holds everything: a single slice cut over many tiles, with long and short fibers
+    i, j, k, v = gen.bernoulli_tensor3((1, 50, 700), 0.6, 5)
+    cases["single_slice"] = ((7, 50, 700), (i + 3, j, k, v))
+    # one fiber holds everything
+    n = 9000
+    cases["single_fiber"] = ((3, 3, n), (torch.ones(n, dtype=torch.int64), torch.full((n,), 2, dtype=torch.int64),
+                                         torch.arange(n, dtype=torch.int64), gen.rng.uniform_pm1(6, 3, n)))
+    z = torch.zeros(0, dtype=torch.int64)
+    cases["empty"] = ((4, 5, 6), (z, z, z, torch.zeros(0, dtype=torch.float64)))
+    cases["single"] = ((4, 5, 6), (torch.tensor([2]), torch.tensor([4]), torch.tensor([5]),
+                                   torch.tensor([-1.5], dtype=torch.float64)))
+    return cases
+
+
+TENSOR_CASES = _tensor_cases()
+
+
+def _check_sparse_result_structure(Y, X_levels, ref, layout):
+    """pos/crd of the result must be bit-identical to the expected structure."""
+    if layout == "csf":
+        want = oracle.compressed_pair_levels(ref["i"], ref["j"])
+        assert Y.levels()[:2] == [1, 1]
+        assert_index_equal(np_(Y.pos(0)), want["pos1"], "pos1")
+        assert_index_equal(np_(Y.crd(0)), want["crd1"], "crd1")
+        assert_index_equal(np_(Y.pos(1)), want["pos2"], "pos2")
+        assert_index_equal(np_(Y.crd(1)), want["crd2"], "crd2")
+        # and identical to the input's own level arrays
+        assert torch.equal(Y.pos(1).cpu(), X_levels.pos[1].cpu()) and torch.equal(Y.crd(1).cpu(), X_levels.crd[1].cpu())
+    else:
+        assert Y.levels() == [2, 3]
+        assert_index_equal(np_(Y.pos(0)), np.array([0, len(ref["i"])]), "pos")
+        assert_index_equal(np_(Y.crd(0)), ref["i"], "crd1")
+        assert_index_equal(np_(Y.crd(1)), ref["j"], "crd2")
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("layout", ["csf", "coo"])
+@pytest.mark.parametrize("name", list(TENSOR_CASES))
+def test_ttv(comet, name, layout, variant):
+    dims, (i, j, k, vals) = TENSOR_CASES[name]
+    say("ttv case=%s layout=%s variant=%d nnz=%d" % (name, layout, variant, vals.numel()))
+    L = (fmt.pack_csf3(dims, i, j, k, vals) if layout == "csf" else fmt.pack_coo(dims, (i, j, k), vals)).to("cuda")
+    X = comet.from_levels(L).set_variant(variant)
+    v = gen.dense_operand(3, 0, (dims[2],))
+    Y = comet.comet_ttv(X, 2, dev(v))
+    torch.cuda.synchronize()
+    ref = oracle.ttv(np_(i), np_(j), np_(k), np_(vals), dims, np_(v))
+    _check_sparse_result_structure(Y, L, ref, layout)
+    assert Y.dims() == list(dims[:2])
+    assert_values_close(np_(Y.vals()), ref["vals"], ref["abs"], "ttv %s" % name)
+    first = Y.vals()
+    comet.comet_ttv(X, 2, dev(v), Y)            # reuse of the result handle
+    torch.cuda.synchronize()
+    assert torch.equal(first, Y.vals())
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("R", [1, 8, 16, 32, 64])
+@pytest.mark.parametrize("name", ["zipf_ttm", "mode_of_two", "single_slice", "single_fiber", "empty", "single"])
+def test_ttm(comet, name, R, variant):
+    dims, (i, j, k, vals) = TENSOR_CASES[name]
+    say("ttm case=%s R=%d variant=%d nnz=%d" % (name, R, variant, vals.numel()))
+    L = fmt.pack_csf3(dims, i, j, k, vals).to("cuda")
+    X = comet.from_levels(L).set_variant(variant)
+    U = gen.dense_operand(4, 0, (dims[2], R))
+    Y = comet.comet_ttm(X, 2, dev(U))
+    torch.cuda.synchronize()
+    ref = oracle.ttm(np_(i), np_(j), np_(k), np_(vals), dims, np_(U))
+    _check_sparse_result_structure(Y, L, ref, "csf")
+    assert Y.levels() == [1, 1, 0] and Y.dims() == [dims[0], dims[1], R]
+    assert_index_equal(np_(Y.pos(2)), np.array([R]), "dense level size")
+    assert_values_close(np_(Y.vals()).reshape(-1, R), ref["vals"], ref["abs"], "ttm %s R=%d" % (name, R))
+
+
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("R", [1, 8, 16, 64])
+@pytest.mark.parametrize("name", ["zipf_mttkrp", "zipf_ttv", "mode_of_two", "single_slice", "single_fiber", "empty",
+                                  "single"])
+def test_mttkrp(comet, name, R, variant):
+    dims, (i, j, k, vals) = TENSOR_CASES[name]
+    say("mttkrp case=%s R=%d variant=%d nnz=%d" % (name, R, variant, vals.numel()))
+    X = comet.from_levels(fmt.pack_csf3(dims, i, j, k, vals).to("cuda")).set_variant(variant)
+    B, C = gen.dense_operand(5, 0, (dims[1], R)), gen.dense_operand(5, 1, (dims[2], R))
+    M = torch.full((dims[0], R), float("nan"), dtype=torch.float64, device="cuda")
+    comet.comet_mttkrp(X, 0, [None, dev(B), dev(C)], M)
+    torch.cuda.synchronize()
+    ref, absum = oracle.mttkrp(np_(i), np_(j), np_(k), np_(vals), dims, np_(B), np_(C))
+    assert_values_close(np_(M), ref, absum, "mttkrp %s R=%d" % (name, R))
+
+
+def test_mttkrp_rank_one_is_ttv_twice_on_the_gpu(comet):
+    """The sparse TTV result is itself a [CU,CU] matrix handle, so SpMV applies to it."""
+    dims, (i, j, k, vals) = TENSOR_CASES["zipf_mttkrp"]
+    X = comet.from_levels(fmt.pack_csf3(dims, i, j, k, vals).to("cuda"))
+    B, C = gen.dense_operand(5, 0, (dims[1], 1)), gen.dense_operand(5, 1, (dims[2], 1))
+    M = comet.comet_mttkrp(X, 0, [None, dev(B), dev(C)])
+    Y = comet.comet_ttv(X, 2, dev(C[:, 0].contiguous()))
+    Ym = comet.comet_tensor_create(Y.dims(), Y.levels(), [Y.pos(0), Y.pos(1)], [Y.crd(0), Y.crd(1)], Y.vals())
+    m2 = comet.comet_spmv(Ym, dev(B[:, 0].contiguous()))
+    torch.cuda.synchronize()
+    ref, absum = oracle.mttkrp(np_(i), np_(j), np_(k), np_(vals), dims, np_(B), np_(C))
+    assert_values_close(np_(M), ref, absum, "mttkrp")
+    assert_values_close(np_(m2), ref[:, 0], absum[:, 0], "ttv then spmv")
+
+
+# ----------------------------------------------------------------------------------------------
+# error paths (forced from the host; no kernel is launched on invalid data)
+# ----------------------------------------------------------------------------------------------
+def _i32(x):
+    return torch.tensor(x, dtype=torch.int32, device="cuda")
+
+
+def test_invalid_descriptors_are_rejected(comet):
+    vals = torch.ones(3, dtype=torch.float64, device="cuda")
+    good = dict(dims=[2, 4], levels=[0, 1], pos=[_i32([2]), _i32([0, 1, 3])], crd=[None, _i32([0, 1, 3])], vals=vals)
+    comet.comet_tensor_create(**good)
+
+    def bad(status, **kw):
+        with pytest.raises(comet.CometError) as e:
+            comet.comet_tensor_create(**{**good, **kw})
+        assert e.value.status == status, e.value
+
+    bad(2, pos=[_i32([3]), _i32([0, 1, 3])])                       # dense size != dim
+    bad(2, pos=[_i32([2]), _i32([0, 1])])                          # pos too short
+    bad(2, pos=[_i32([2]), _i32([0, 2, 1])])                       # pos not monotone / wrong end
+    bad(2, pos=[_i32([2]), _i32([1, 1, 3])])                       # pos does not start at 0
+    bad(2, crd=[None, _i32([0, 3, 1])])                            # unsorted inside a segment
+    bad(2, crd=[None, _i32([0, 1, 4])])                            # coordinate out of range
+    bad(2, crd=[None, _i32([0, 1, 1])])                            # duplicate inside a segment
+    bad(4, levels=[0, 0], pos=[_i32([2]), _i32([4])], crd=[None, None],
+        vals=torch.ones(8, dtype=torch.float64, device="cuda"))    # [D,D] is not a sparse tuple we take
+    bad(2, levels=[2, 3], pos=[_i32([1, 3]), None], crd=[_i32([0, 1, 1]), _i32([0, 1, 3])])   # CN pos[0] != 0
+    bad(2, levels=[2, 3], pos=[_i32([0, 3]), None], crd=[_i32([1, 0, 1]), _i32([0, 1, 3])])   # COO unsorted
+    bad(2, levels=[2, 3], pos=[_i32([0, 3]), None], crd=[_i32([0, 1, 1]), _i32([0, 3, 3])])   # COO duplicate
+
+
+def test_shape_mode_and_rank_errors(comet):
+    dims, (i, j, k, vals) = TENSOR_CASES["mode_of_two"]
+    X = comet.from_levels(fmt.pack_csf3(dims, i, j, k, vals).to("cuda"))
+    v = torch.ones(dims[2], dtype=torch.float64, device="cuda")
+    for mode in (0, 1):
+        with pytest.raises(comet.CometError) as e:
+            comet.comet_ttv(X, mode, torch.ones(dims[mode], dtype=torch.float64, device="cuda"))
+        assert e.value.status == 4
+    with pytest.raises(comet.CometError) as e:
+        comet.comet_ttv(X, 2, torch.ones(dims[2] + 1, dtype=torch.float64, device="cuda"))
+    assert e.value.status == 3
+    B = torch.ones((dims[1], 4), dtype=torch.float64, device="cuda")
+    C = torch.ones((dims[2], 4), dtype=torch.float64, device="cuda")
+    with pytest.raises(comet.CometError) as e:
+        comet.comet_mttkrp(X, 1, [torch.ones((dims[0], 4), dtype=torch.float64, device="cuda"), None, C])
+    assert e.value.status == 4
+    with pytest.raises(comet.CometError) as e:
+        comet.comet_spmv(X, v)
+    assert e.value.status in (3, 4)
+    Y = comet.comet_ttv(X, 2, v)
+    with pytest.raises(comet.CometError) as e:       # a TTV result handle cannot be reused for TTM
+        comet.comet_ttm(X, 2, C, Y)
+    assert e.value.status == 1
+    comet.comet_mttkrp(X, 0, [None, B, C])
+
+
+def test_copy_flag_detaches_from_caller_arrays(comet):
+    (I, J), (rows, cols, vals) = MATRIX_CASES["config1"]
+    L = fmt.pack_csr(I, J, rows, cols, vals).to("cuda")
+    A = comet.comet_tensor_create(L.dims, L.tags, L.pos, L.crd, L.vals, comet.COMET_COPY | comet.COMET_VALIDATE)
+    x = dev(gen.dense_operand(1, 0, (J,)))
+    y1 = comet.comet_spmv(A, x).clone()
+    L.vals.zero_()
+    L.crd[1].zero_()
+    y2 = comet.comet_spmv(A, x)
+    torch.cuda.synchronize()
+    assert torch.equal(y1, y2)
