@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse x dense contraction library on one MI355X.
+
+A "step" is one pass of the hot path over one batch of synthetic input: one call of an operation
+through the C ABI (main kernel + carry fix-up + any result clearing), inputs resident in HBM.
+The headline workload is the SpMM configuration (CSR 1e6 x 1e6, Zipf(1.8) row lengths capped at
+10,000, B dense 1e6 x 32, fp64); `value` is its GFLOP/s.  The other four configurations of the
+baseline (SpMV, TTV, TTM, MTTKRP at rank 16 and 64) are timed the same way and reported under
+"kernels" in the same JSON line.
+
+For every operation the line carries the algorithmic (compulsory) bytes of one launch, the
+achieved GB/s = those bytes / mean launch time, and the fraction of the 8 TB/s HBM peak.
+"cpu_baseline" is the CPU oracle timed on this host on a bounded sample of the headline workload.
+
+  python bench.py [--gpus 1] [--steps 25] [--warmup 5] [--ops spmv,spmm,ttv,ttv_coo,ttm,mttkrp16,mttkrp64]
+                  [--scale 1.0] [--variant 0] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+ALL_OPS = ["spmm", "spmv", "ttv", "ttv_coo", "ttm", "mttkrp16", "mttkrp64"]
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_steps(fn, steps, warmup):
+    """Mean and median milliseconds of `steps` calls of fn, bracketed by events on the current stream."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    per = sorted(a.elapsed_time(b) for a, b in evs)
+    total = evs[0][0].elapsed_time(evs[-1][1]) / steps
+    return {"mean_ms": total, "median_ms": per[len(per) // 2], "min_ms": per[0], "wall_ms": wall}
+
+
+def count_distinct(t):
+    import torch
+    return int(torch.unique(t).numel())
+
+
+def roofline(bytes_per_launch, ms):
+    gbs = bytes_per_launch / (ms * 1e-3) / 1e9
+    return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "bytes_per_launch": int(bytes_per_launch)}
+
+
+def run_op(op, args, comet, dev):
+    """Generate the op's configuration on the GPU, time it, return the report entry (+ inputs for the baseline)."""
+    import torch
+    from synth import formats as fmt
+    from synth import generate as gen
+    t_gen = time.perf_counter()
+    sc = args.scale
+    keep = {}
+    if op == "spmv":
+        c = gen.config_spmv(seed=0, device=dev)
+        rows, cols, vals = c["coo"]
+        n = c["dims"][0]
+        L = fmt.pack_csr(n, n, rows, cols, vals)
+        A = comet.from_levels(L).set_variant(args.variant)
+        x, y = c["x"], torch.empty(n, dtype=torch.float64, device=dev)
+        fn = lambda: comet.comet_spmv(A, x, y)
+        nnz = vals.numel()
+        flops = 2 * nnz
+        nbytes = 12 * nnz + 12 * n + 8 * n
+        desc = "SpMV CSR %dx%d, %d nnz (10 per row)" % (n, n, nnz)
+        extra = {"nnz": nnz, "rows": n}
+        keep = dict(A=A, L=L, x=x, y=y)
+    elif op == "spmm":
+        c = gen.config_spmm(seed=0, device=dev, scale=sc, R=32)
+        rows, cols, vals = c["coo"]
+        n = c["dims"][0]
+        R = 32
+        L = fmt.pack_csr(n, n, rows, cols, vals)
+        A = comet.from_levels(L).set_variant(args.variant)
+        B, C = c["B"], torch.empty((n, R), dtype=torch.float64, device=dev)
+        fn = lambda: comet.comet_spmm(A, B, C)
+        nnz = vals.numel()
+        touched = count_distinct(cols)
+        flops = 2 * R * nnz
+        nbytes = 12 * nnz + (4 + 8 * R) * n + 8 * R * touched
+        desc = "SpMM CSR %dx%d, %d nnz, Zipf(1.8) rows capped at 10000, B %dx%d" % (n, n, nnz, n, R)
+        extra = {"nnz": nnz, "rows": n, "R": R, "touched_B_rows": touched, "gather_bytes": 8 * R * nnz}
+        keep = dict(A=A, L=L, B=B, C=C, coo=(rows, cols, vals), n=n)
+    else:
+        R = {"ttv": 1, "ttv_coo": 1, "ttm": 16, "mttkrp16": 16, "mttkrp64": 64}[op]
+        if op.startswith("ttv"):
+            c = gen.config_ttv(seed=0, device=dev, scale=sc)
+        elif op == "ttm":
+            c = gen.config_ttm(seed=0, device=dev, scale=sc, R=R)
+        else:
+            c = gen.config_mttkrp(seed=0, device=dev, scale=sc, R=R)
+        i, j, k, vals = c["coo"]
+        dims = c["dims"]
+        nnz = vals.numel()
+        L = fmt.pack_coo(dims, (i, j, k), vals) if op == "ttv_coo" else fmt.pack_csf3(dims, i, j, k, vals)
+        touched_k = count_distinct(k)
+        if op == "ttv_coo":
+            nfib = count_distinct(i * dims[1] + j)
+            n1 = count_distinct(i)
+        else:
+            nfib, n1 = int(L.crd[1].numel()), int(L.crd[0].numel())
+        del i, j, k
+        X = comet.from_levels(L).set_variant(args.variant)
+        extra = {"nnz": nnz, "nfib": nfib, "n1": n1, "dims": list(dims), "R": R, "draws": c["info"]["draws"]}
+        if op in ("ttv", "ttv_coo"):
+            v = c["v"]
+            Y = comet.comet_ttv(X, 2, v)
+            fn = lambda: comet.comet_ttv(X, 2, v, Y)
+            flops = 2 * nnz
+            nbytes = (12 if op == "ttv" else 20) * nnz + 16 * nfib + 8 * touched_k
+            desc = "TTV %s %s, %d nnz, %d fibers, Zipf(1.3)" % ("CSF" if op == "ttv" else "COO", "x".join(map(str, dims)), nnz, nfib)
+            keep = dict(X=X, L=L, v=v, Y=Y)
+        elif op == "ttm":
+            U = c["U"]
+            Y = comet.comet_ttm(X, 2, U)
+            fn = lambda: comet.comet_ttm(X, 2, U, Y)
+            flops = 2 * R * nnz
+            nbytes = 12 * nnz + (8 + 8 * R) * nfib + 8 * R * touched_k
+            desc = "TTM CSF %s, %d nnz, %d fibers, U %dx%d" % ("x".join(map(str, dims)), nnz, nfib, dims[2], R)
+            extra["gather_bytes"] = 8 * R * nnz
+            keep = dict(X=X, L=L, U=U, Y=Y)
+        else:
+            Bf, Cf = c["B"], c["C"]
+            M = torch.empty((dims[0], R), dtype=torch.float64, device=dev)
+            fn = lambda: comet.comet_mttkrp(X, 0, [None, Bf, Cf], M)
+            touched_j = count_distinct(L.crd[1])
+            flops = 2 * R * (nnz + nfib)
+            nbytes = 12 * nnz + 8 * nfib + 8 * n1 + 8 * R * (touched_j + touched_k + dims[0])
+            desc = "MTTKRP mode-1 CSF %s, %d nnz, %d fibers, %d slices, R=%d" % ("x".join(map(str, dims)), nnz, nfib, n1, R)
+            extra["gather_bytes"] = 8 * R * (nnz + nfib)
+            keep = dict(X=X, L=L, B=Bf, C=Cf, M=M)
+    torch.cuda.synchronize()
+    gen_s = time.perf_counter() - t_gen
+    steps = args.steps
+    tm = time_steps(fn, steps, args.warmup)
+    ms = tm["mean_ms"]
+    entry = {"workload": desc, "ms": round(ms, 5), "median_ms": round(tm["median_ms"], 5),
+             "min_ms": round(tm["min_ms"], 5), "gflops": round(flops / (ms * 1e-3) / 1e9, 2), "flops": int(flops),
+             "roofline": roofline(nbytes, ms), "setup_s": round(gen_s, 2), **extra}
+    log("[bench] %-9s %s: %.4f ms/step  %.1f GFLOP/s  %.1f GB/s (%.1f%% of 8 TB/s)  [setup %.1fs]" % (
+        op, desc, ms, entry["gflops"], entry["roofline"]["achieved"], 100 * entry["roofline"]["frac"], gen_s))
+    return entry, keep
+
+
+def cpu_baseline_spmm(keep, budget_nnz=6_000_000):
+    """The CPU oracle (single thread, as it stands) on the leading rows of the headline matrix."""
+    import numpy as np
+    import torch
+    import oracle
+    rows, cols, vals = keep["coo"]
+    n = keep["n"]
+    nnz = int(vals.numel())
+    m = min(nnz, budget_nnz)
+    last_row = int(rows[m - 1]) if m else 0
+    nrows = last_row            # rows 0 .. last_row-1 are complete within the first m nonzeros
+    if nrows <= 0:
+        nrows, m = n, nnz
+    else:
+        m = int(torch.searchsorted(rows, torch.tensor([nrows], device=rows.device))[0])
+    r_h, c_h, v_h = rows[:m].cpu().numpy(), cols[:m].cpu().numpy(), vals[:m].cpu().numpy()
+    B_h = keep["B"].cpu().numpy()
+    R = B_h.shape[1]
+    t0 = time.perf_counter()
+    ref, absum = oracle.spmm(r_h, c_h, v_h, (nrows, n), B_h)
+    dt = time.perf_counter() - t0
+    got = keep["C"][:nrows].cpu().numpy()
+    ok = bool(np.all(np.abs(got - ref) <= 1e-10 * np.abs(ref) + 1e-12 * absum))
+    return {"value": round(2 * R * m / dt / 1e9, 3), "unit": "GFLOP/s", "cores": 1, "kind": "oracle",
+            "sample": "rows 0..%d of the SpMM matrix (%d of %d nnz), %.1f s" % (nrows - 1, m, nnz, dt),
+            "parity_on_sample": ok}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=25)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--ops", type=str, default=",".join(ALL_OPS))
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink every configuration (testing only)")
+    ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 simple kernels, 2 tiled kernels")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build runs on one GPU only (no sharding, no collectives); run it with --gpus 1.")
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(1)
+    from paper_2102_05187_amd import build as hipbuild
+    hipbuild.build_if_missing()
+    import paper_2102_05187_amd as comet
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    ops = [o for o in args.ops.split(",") if o]
+    if "spmm" in ops:                       # headline first
+        ops = ["spmm"] + [o for o in ops if o != "spmm"]
+    kernels, head_keep = {}, None
+    cpu = None
+    for op in ops:
+        entry, keep = run_op(op, args, comet, dev)
+        kernels[op] = entry
+        if op == "spmm":
+            head_keep = keep
+            if not args.no_cpu_baseline:
+                cpu = cpu_baseline_spmm(keep)
+                log("[bench] cpu oracle: %s GFLOP/s on %s (parity on sample: %s)" % (cpu["value"], cpu["sample"], cpu["parity_on_sample"]))
+        del keep
+        head_keep = None
+        torch.cuda.empty_cache()
+    head = kernels.get("spmm") or next(iter(kernels.values()))
+    line = {
+        "metric": "GFLOP/s + achieved HBM GB/s (% of peak) for SpMV, SpMM, TTM, MTTKRP",
+        "value": head["gflops"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": head["workload"], "index_dtype": "int32", "scale": args.scale, "variant": args.variant},
+        "roofline": head["roofline"], "cpu_baseline": cpu, "kernels": kernels,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -133,10 +133,15 @@ comet_status ensure_scratch(const comet_tensor *t, size_t bytes) {
     return COMET_OK;
 }
 
-bool use_tiled(const comet_tensor *t, int64_t R) {
+// The tiled kernels read crd / vals with 16-byte vector loads, so the arrays must be 16-byte aligned
+// (device allocations are; sub-views handed in by a caller may not be).
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool use_tiled(const comet_tensor *t, int64_t R, const void *dense) {
     if (t->variant == 1) return false;
     if (!comet::stream_supports_rank(R)) return false;
-    if (t->variant == 2) return true;
+    const int leaf = t->order - 1;
+    if (!aligned16(t->crd_i(leaf)) || !aligned16(t->vals_d()) || !aligned16(dense)) return false;
     return true;
 }
 
@@ -325,7 +330,7 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
         if (A->fmt == Format::CSR) HIP_TRY(comet::fill_zero_f64(out, A->dims[0] * R, st));
         return COMET_OK;
     }
-    if (use_tiled(A, R)) {
+    if (use_tiled(A, R, Dn)) {
         size_t need = comet::stream_scratch_bytes(A->sched.ntiles, R);
         comet_status rs = ensure_scratch(A, need);
         if (rs != COMET_OK) return rs;
@@ -399,7 +404,7 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
     double *yv = (double *)y->vals->ptr;
     if (X->nvals > 0) {
         if (csf) {
-            if (use_tiled(X, R)) {
+            if (use_tiled(X, R, Dn)) {
                 rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.ntiles, R));
                 if (rs != COMET_OK) return rs;
                 HIP_TRY(comet::stream_segreduce(X->sched, X->pos_i(2), X->crd_i(2), X->vals_d(), nullptr, Dn, R, yv,
@@ -409,7 +414,7 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
                                                 nullptr, Dn, R, yv, st));
             }
         } else {
-            if (use_tiled(X, 1)) {
+            if (use_tiled(X, 1, Dn) && comet::stream_supports_coo()) {
                 rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.ntiles, 1));
                 if (rs != COMET_OK) return rs;
                 HIP_TRY(comet::stream_ttv_coo(X->sched, X->crd_i(0), X->crd_i(1), X->crd_i(2), X->vals_d(), Dn,
@@ -448,7 +453,7 @@ comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *
     // rows of M whose index is not stored at the root level receive no contribution
     HIP_TRY(comet::fill_zero_f64(M, X->dims[0] * R, st));
     if (X->nvals == 0) return COMET_OK;
-    if (use_tiled(X, R) && comet::stream_mttkrp_supports_rank(R)) {
+    if (use_tiled(X, R, B) && aligned16(C) && comet::stream_mttkrp_supports_rank(R)) {
         comet_status rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.ntiles, R));
         if (rs != COMET_OK) return rs;
         HIP_TRY(comet::stream_mttkrp(X->sched, X->pos_i(1), X->crd_i(0), X->pos_len[1] - 1, X->pos_i(2), X->crd_i(1),

@@ -1,13 +1,265 @@
+// Nonzero-tiled streaming kernels for gfx950 (wave64).
+//
+// Work is cut by nonzeros, not by rows: tile t owns leaf positions [t*kTile, (t+1)*kTile), whatever
+// segments (rows / fibers / slices) they belong to, so a power-law head segment is spread over many
+// workgroups -- load imbalance across rows is what the paper names as the main source of slowdown
+// (Section 8.3).  Inside a tile each wavefront streams a contiguous quarter with wide coalesced
+// loads and reduces it with a segmented scan; the per-level access rule is the compressed-unique
+// one of Table "Generated code to access nonzeros coordinates" (segment s owns positions
+// pos[s]..pos[s+1]-1, coordinate crd[p], value vals[p]).
+//
+// Segment ends are marked in an LDS map: ts[i] = id of the segment whose LAST nonzero is tile item
+// i, else -1.  A unit of work (lane, wavefront, tile) summarises its item range as
+//     has_tail    a segment ends inside the range
+//     first       sum of the items up to and including the first segment end   (+ its segment id)
+//     open        sum of the items after the last segment end (all items if there is none)
+// and two adjacent summaries combine associatively; a segment that closes at the boundary of two
+// units is final once the left unit contains a segment end.  Tile summaries go to a carry buffer
+// and a second small kernel finishes the segments cut by tile boundaries in a fixed order, so the
+// results do not depend on scheduling (no atomics).
 #include "stream_kernels.hpp"
+
 namespace comet {
-bool stream_supports_rank(int64_t) { return false; }
+
+namespace {
+
+constexpr int kWaves = 4;                    // wavefronts per workgroup
+constexpr int kWaveItems = kTile / kWaves;   // 1024 consecutive items per wavefront
+
+// ---- DPP helpers (gfx9 controls: row_shr:n = 0x110+n, wave_shr:1 = 0x138, row_bcast:15 = 0x142,
+//      row_bcast:31 = 0x143, quad_perm = 8-bit selector) ------------------------------------------
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_i(int old, int v) {
+    return __builtin_amdgcn_update_dpp(old, v, CTRL, ROW_MASK, 0xf, false);
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_d(double old, double v) {
+    int lo = __builtin_amdgcn_update_dpp(__double2loint(old), __double2loint(v), CTRL, ROW_MASK, 0xf, false);
+    int hi = __builtin_amdgcn_update_dpp(__double2hiint(old), __double2hiint(v), CTRL, ROW_MASK, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double readlane_d(double v, int lane) {
+    int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+    int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+    return __hiloint2double(hi, lo);
+}
+
+// Inclusive segmented scan over the 64 lanes.  Element = (f, v); combine(left, right) =
+// (left.f | right.f, right.f ? right.v : left.v + right.v): a flagged element cuts the running sum.
+__device__ __forceinline__ void segscan_inclusive(int &f, double &v) {
+#define COMET_SCAN_STEP(CTRL, RM)                         \
+    {                                                     \
+        int nf = dpp_i<CTRL, RM>(0, f);                   \
+        double nv = dpp_d<CTRL, RM>(0.0, v);              \
+        v = f ? v : nv + v;                               \
+        f |= nf;                                          \
+    }
+    COMET_SCAN_STEP(0x111, 0xf)   // row_shr:1
+    COMET_SCAN_STEP(0x112, 0xf)   // row_shr:2
+    COMET_SCAN_STEP(0x114, 0xf)   // row_shr:4
+    COMET_SCAN_STEP(0x118, 0xf)   // row_shr:8
+    COMET_SCAN_STEP(0x142, 0xa)   // row_bcast:15 into rows 1 and 3
+    COMET_SCAN_STEP(0x143, 0xc)   // row_bcast:31 into rows 2 and 3
+#undef COMET_SCAN_STEP
+}
+
+// Carry-buffer layout inside the per-tensor scratch: per tile  first[R], open[R] (fp64), then
+// has_tail and first_id (int32).
+struct CarryView {
+    double  *first, *open;
+    int32_t *has_tail, *first_id;
+};
+__host__ __device__ inline CarryView carry_view(void *scratch, int64_t ntiles, int64_t R) {
+    CarryView c;
+    c.first = (double *)scratch;
+    c.open = c.first + ntiles * R;
+    c.has_tail = (int32_t *)(c.open + ntiles * R);
+    c.first_id = c.has_tail + ntiles;
+    return c;
+}
+
+// ---- phase A/B for compressed levels: fill the tail map from pos, zero-fill empty segments -------
+// Segments [seg_begin[t], seg_begin[t+1]) end inside tile t (the segment that contains the first
+// item of the next tile ends later), so each of them owns exactly one map entry.
+template <bool WIDE_OUT>
+__device__ __forceinline__ void build_tail_map_from_pos(int32_t *ts, const int32_t *__restrict__ pos,
+                                                        const int32_t *__restrict__ rowmap, int64_t tb, int32_t s0,
+                                                        int32_t s1, double *__restrict__ out, int R) {
+    for (int i = threadIdx.x; i < kTile; i += blockDim.x) ts[i] = -1;
+    __syncthreads();
+    for (int32_t s = s0 + threadIdx.x; s < s1; s += blockDim.x) {
+        int32_t b = pos[s], e = pos[s + 1];
+        if (e > b) {
+            ts[(int64_t)e - 1 - tb] = s;
+        } else {
+            int64_t row = rowmap ? (int64_t)rowmap[s] : (int64_t)s;
+            for (int r = 0; r < R; ++r) out[row * R + r] = 0.0;
+        }
+    }
+    __syncthreads();
+}
+
+// ---- rank-1 walk: each lane owns 2 consecutive items per 128-item block --------------------------
+// Returns through LDS: wsum_ht[w], wsum_open[w], wsum_first[w], wsum_first_id[w].
+__device__ __forceinline__ void walk_rank1(const int32_t *ts, const int32_t *__restrict__ crd,
+                                           const double *__restrict__ vals, const double *__restrict__ x,
+                                           const int32_t *__restrict__ rowmap, double *__restrict__ out, int64_t tb,
+                                           int64_t nnz, int *wsum_ht, double *wsum_open, double *wsum_first,
+                                           int *wsum_first_id) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t wb = tb + (int64_t)w * kWaveItems;
+    int cf = 0;          // carry of this wavefront over the blocks done so far: has_tail, open
+    double cv = 0.0;
+#pragma unroll 2
+    for (int blk = 0; blk < kWaveItems / 128; ++blk) {
+        const int64_t i0 = wb + blk * 128 + 2 * lane;
+        if (wb + blk * 128 >= nnz) break;                    // uniform: nothing left in this wavefront's range
+        int2 c;
+        double2 a;
+        if (i0 + 1 < nnz) {
+            c = *reinterpret_cast<const int2 *>(crd + i0);
+            a = *reinterpret_cast<const double2 *>(vals + i0);
+        } else {
+            c.x = i0 < nnz ? crd[i0] : 0;  c.y = 0;
+            a.x = i0 < nnz ? vals[i0] : 0.0;  a.y = 0.0;
+        }
+        const int2 t = *reinterpret_cast<const int2 *>(ts + (i0 - tb));
+        const double p0 = a.x * x[c.x];
+        const double p1 = i0 + 1 < nnz ? a.y * x[c.y] : 0.0;
+        // lane summary
+        int f = (t.x >= 0) | (t.y >= 0);
+        double first = t.x >= 0 ? p0 : p0 + p1;
+        int first_id = t.x >= 0 ? t.x : t.y;
+        double open = t.y >= 0 ? 0.0 : (t.x >= 0 ? p1 : p0 + p1);
+        if (t.x >= 0 && t.y >= 0) {                          // item i0+1 is a whole segment by itself
+            int64_t row = rowmap ? (int64_t)rowmap[t.y] : (int64_t)t.y;
+            out[row] = p1;
+        }
+        int sf = f;
+        double sv = open;
+        segscan_inclusive(sf, sv);
+        // exclusive value for this lane = carry (+) inclusive value of the previous lane
+        int pf = dpp_i<0x138, 0xf>(0, sf);                   // wave_shr:1, lane 0 keeps the identity
+        double pv = dpp_d<0x138, 0xf>(0.0, sv);
+        const int ef = cf | pf;
+        const double ev = pf ? pv : cv + pv;
+        if (f) {
+            const double value = ev + first;
+            if (ef) {
+                int64_t row = rowmap ? (int64_t)rowmap[first_id] : (int64_t)first_id;
+                out[row] = value;
+            } else {                                         // the first segment end of this wavefront's range
+                wsum_first[w] = value;
+                wsum_first_id[w] = first_id;
+            }
+        }
+        const int tf = __builtin_amdgcn_readlane(sf, 63);
+        const double tv = readlane_d(sv, 63);
+        cv = tf ? tv : cv + tv;
+        cf |= tf;
+    }
+    if (lane == 0) { wsum_ht[w] = cf; wsum_open[w] = cv; }
+}
+
+// Combine the wavefront summaries of one tile in order and publish the tile summary.
+__device__ __forceinline__ void finish_tile_rank1(const int *wsum_ht, const double *wsum_open, const double *wsum_first,
+                                                  const int *wsum_first_id, const int32_t *__restrict__ rowmap,
+                                                  double *__restrict__ out, CarryView cb, int64_t t) {
+    if (threadIdx.x != 0) return;
+    int rf = 0, fid = -1;
+    double rv = 0.0, tfirst = 0.0;
+    for (int w = 0; w < kWaves; ++w) {
+        if (wsum_ht[w]) {
+            const double value = rv + wsum_first[w];
+            if (rf) {
+                int64_t row = rowmap ? (int64_t)rowmap[wsum_first_id[w]] : (int64_t)wsum_first_id[w];
+                out[row] = value;
+            } else {
+                tfirst = value; fid = wsum_first_id[w]; rf = 1;
+            }
+            rv = wsum_open[w];
+        } else {
+            rv += wsum_open[w];
+        }
+    }
+    cb.has_tail[t] = rf;
+    cb.first_id[t] = fid;
+    cb.first[t] = tfirst;
+    cb.open[t] = rv;
+}
+
+__global__ void __launch_bounds__(256) k_stream_rank1(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
+                                                      const double *__restrict__ vals,
+                                                      const int32_t *__restrict__ seg_begin,
+                                                      const int32_t *__restrict__ rowmap, const double *__restrict__ x,
+                                                      double *__restrict__ out, int64_t nnz, int64_t ntiles,
+                                                      void *scratch) {
+    __shared__ __attribute__((aligned(16))) int32_t ts[kTile];
+    __shared__ int wsum_ht[kWaves], wsum_first_id[kWaves];
+    __shared__ double wsum_open[kWaves], wsum_first[kWaves];
+    const int64_t t = blockIdx.x;
+    const int64_t tb = t * (int64_t)kTile;
+    build_tail_map_from_pos<false>(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, 1);
+    walk_rank1(ts, crd, vals, x, rowmap, out, tb, nnz, wsum_ht, wsum_open, wsum_first, wsum_first_id);
+    __syncthreads();
+    finish_tile_rank1(wsum_ht, wsum_open, wsum_first, wsum_first_id, rowmap, out, carry_view(scratch, ntiles, 1), t);
+}
+
+// ---- fix-up: finish the first segment end of every tile -------------------------------------------
+// value = first[t] + open[t-1] + open[t-2] + ... up to and including the nearest tile that contains
+// a segment end.  One thread per (tile, r).
+__global__ void __launch_bounds__(256) k_stream_fixup(void *scratch, int64_t ntiles, int R,
+                                                      const int32_t *__restrict__ rowmap, double *__restrict__ out) {
+    const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= ntiles * R) return;
+    const int64_t t = g / R;
+    const int r = (int)(g - t * R);
+    CarryView cb = carry_view(scratch, ntiles, R);
+    if (!cb.has_tail[t]) return;
+    double v = cb.first[t * R + r];
+    for (int64_t u = t - 1; u >= 0; --u) {
+        v += cb.open[u * R + r];
+        if (cb.has_tail[u]) break;
+    }
+    const int32_t id = cb.first_id[t];
+    const int64_t row = rowmap ? (int64_t)rowmap[id] : (int64_t)id;
+    out[row * R + r] = v;
+}
+
+}  // namespace
+
+bool stream_supports_rank(int64_t R) { return R == 1; }
 bool stream_mttkrp_supports_rank(int64_t) { return false; }
-size_t stream_scratch_bytes(int64_t, int64_t) { return 16; }
-hipError_t stream_segreduce(const Schedule &, const int32_t *, const int32_t *, const double *, const int32_t *,
-                            const double *, int64_t, double *, void *, hipStream_t) { return hipErrorNotSupported; }
+bool stream_supports_coo() { return false; }
+
+size_t stream_scratch_bytes(int64_t ntiles, int64_t R) {
+    size_t n = (size_t)(ntiles < 1 ? 1 : ntiles);
+    return n * (size_t)R * 2 * sizeof(double) + n * 2 * sizeof(int32_t) + 64;
+}
+
+hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
+                            const int32_t *rowmap, const double *Dn, int64_t R, double *out, void *scratch,
+                            hipStream_t st) {
+    if (sc.ntiles <= 0) return hipSuccess;
+    if (R != 1) return hipErrorNotSupported;
+    const int32_t *sb = (const int32_t *)sc.seg_begin->ptr;
+    hipLaunchKernelGGL(k_stream_rank1, dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals, sb, rowmap, Dn, out,
+                       sc.nnz, sc.ntiles, scratch);
+    const int64_t n = sc.ntiles * R;
+    hipLaunchKernelGGL(k_stream_fixup, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, scratch, sc.ntiles, (int)R,
+                       rowmap, out);
+    return hipGetLastError();
+}
+
 hipError_t stream_ttv_coo(const Schedule &, const int32_t *, const int32_t *, const int32_t *, const double *,
-                          const double *, int32_t *, int32_t *, double *, void *, hipStream_t) { return hipErrorNotSupported; }
+                          const double *, int32_t *, int32_t *, double *, void *, hipStream_t) {
+    return hipErrorNotSupported;
+}
+
 hipError_t stream_mttkrp(const Schedule &, const int32_t *, const int32_t *, int64_t, const int32_t *, const int32_t *,
                          const int32_t *, const double *, const double *, const double *, int64_t, double *, void *,
-                         hipStream_t) { return hipErrorNotSupported; }
+                         hipStream_t) {
+    return hipErrorNotSupported;
 }
+
+}  // namespace comet

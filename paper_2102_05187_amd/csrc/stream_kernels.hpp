@@ -16,6 +16,7 @@ namespace comet {
 
 bool   stream_supports_rank(int64_t R);
 bool   stream_mttkrp_supports_rank(int64_t R);
+bool   stream_supports_coo();
 size_t stream_scratch_bytes(int64_t ntiles, int64_t R);
 
 // out[row(s), :] = sum_{p in segment s} vals[p] * Dn[crd[p], :],  row(s) = rowmap ? rowmap[s] : s.
