@@ -226,9 +226,176 @@ __global__ void __launch_bounds__(256) k_stream_fixup(void *scratch, int64_t nti
     out[row * R + r] = v;
 }
 
+
+// ---- rank-R walk: a quad (4 lanes) walks 64 consecutive items; lanes hold V = R/4 ranks each ------
+// Quad q of wavefront w owns items [tb + 1024 w + 64 q, +64).  Every 16 items each lane loads four
+// consecutive (crd, val, tail id) triples with 16-byte loads; the quad then takes the items one at
+// a time, fetching the current item's triple from the lane that holds it with a quad_perm DPP
+// broadcast.  For one item the quad reads the operand row Dn[crd, :] as contiguous 16-byte pieces
+// (WIDE, R a multiple of 8: lane j takes ranks 8q+2j, 8q+2j+1) or 8-byte pieces (lane j takes ranks
+// 4q+j), so each gathered row is one contiguous run of bytes across the quad.
+template <int BP>
+__device__ __forceinline__ int quad_bcast_i(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, BP * 0x55, 0xf, 0xf, false);
+}
+template <int BP>
+__device__ __forceinline__ double quad_bcast_d(double v) {
+    int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), BP * 0x55, 0xf, 0xf, false);
+    int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), BP * 0x55, 0xf, 0xf, false);
+    return __hiloint2double(hi, lo);
+}
+
+template <int V, bool WIDE>
+struct QuadState {
+    double acc[V];
+    double first[V];
+    int ht, first_id;
+};
+
+template <int V, bool WIDE>
+__device__ __forceinline__ void quad_store_row(double *__restrict__ out, int64_t row, int R, int j, const double *v) {
+    double *p = out + row * R;
+    if constexpr (WIDE) {
+#pragma unroll
+        for (int q = 0; q < V / 2; ++q) *reinterpret_cast<double2 *>(p + 8 * q + 2 * j) = make_double2(v[2 * q], v[2 * q + 1]);
+    } else {
+#pragma unroll
+        for (int q = 0; q < V; ++q) { int r = 4 * q + j; if (r < R) p[r] = v[q]; }
+    }
+}
+
+template <int V, bool WIDE>
+__device__ __forceinline__ void quad_item(QuadState<V, WIDE> &st, int c, double a, int t, const double *__restrict__ Dn,
+                                          const int32_t *__restrict__ rowmap, double *__restrict__ out, int R, int j) {
+    const double *rowp = Dn + (int64_t)c * R;
+    if constexpr (WIDE) {
+        double2 d[V / 2];
+#pragma unroll
+        for (int q = 0; q < V / 2; ++q) d[q] = *reinterpret_cast<const double2 *>(rowp + 8 * q + 2 * j);
+#pragma unroll
+        for (int q = 0; q < V / 2; ++q) { st.acc[2 * q] = fma(a, d[q].x, st.acc[2 * q]); st.acc[2 * q + 1] = fma(a, d[q].y, st.acc[2 * q + 1]); }
+    } else {
+        double d[V];
+#pragma unroll
+        for (int q = 0; q < V; ++q) { int r = 4 * q + j; d[q] = r < R ? rowp[r] : 0.0; }
+#pragma unroll
+        for (int q = 0; q < V; ++q) st.acc[q] = fma(a, d[q], st.acc[q]);
+    }
+    if (t >= 0) {                                   // the item ends segment t (same for the 4 lanes of the quad)
+        if (!st.ht) {
+#pragma unroll
+            for (int q = 0; q < V; ++q) st.first[q] = st.acc[q];
+            st.first_id = t;
+            st.ht = 1;
+        } else {
+            quad_store_row<V, WIDE>(out, rowmap ? (int64_t)rowmap[t] : (int64_t)t, R, j, st.acc);
+        }
+#pragma unroll
+        for (int q = 0; q < V; ++q) st.acc[q] = 0.0;
+    }
+}
+
+template <int V, bool WIDE>
+__global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
+                                                      const double *__restrict__ vals,
+                                                      const int32_t *__restrict__ seg_begin,
+                                                      const int32_t *__restrict__ rowmap, const double *__restrict__ Dn,
+                                                      double *__restrict__ out, int64_t nnz, int64_t ntiles, int R,
+                                                      void *scratch) {
+    __shared__ __attribute__((aligned(16))) int32_t ts[kTile];
+    __shared__ __attribute__((aligned(16))) double qopen[64 * 4 * V];    // [quad][lane j][V]
+    __shared__ int qht[64];
+    const int64_t t = blockIdx.x;
+    const int64_t tb = t * (int64_t)kTile;
+    build_tail_map_from_pos<true>(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, R);
+
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, qw = lane >> 2, j = lane & 3;
+    const int Q = w * 16 + qw;                                    // quad index inside the tile
+    const int64_t qb = tb + (int64_t)Q * 64;                      // first item of this quad
+    QuadState<V, WIDE> st;
+#pragma unroll
+    for (int q = 0; q < V; ++q) { st.acc[q] = 0.0; st.first[q] = 0.0; }
+    st.ht = 0; st.first_id = -1;
+
+    for (int sb = 0; sb < 4; ++sb) {
+        const int64_t i0 = qb + 16 * sb + 4 * j;                  // this lane's four items
+        int cr[4], tl[4];
+        double va[4];
+        if (i0 + 3 < nnz) {
+            const int4 c4 = *reinterpret_cast<const int4 *>(crd + i0);
+            const double2 a01 = *reinterpret_cast<const double2 *>(vals + i0);
+            const double2 a23 = *reinterpret_cast<const double2 *>(vals + i0 + 2);
+            cr[0] = c4.x; cr[1] = c4.y; cr[2] = c4.z; cr[3] = c4.w;
+            va[0] = a01.x; va[1] = a01.y; va[2] = a23.x; va[3] = a23.y;
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) { bool in = i0 + s < nnz; cr[s] = in ? crd[i0 + s] : 0; va[s] = in ? vals[i0 + s] : 0.0; }
+        }
+        {
+            const int4 t4 = *reinterpret_cast<const int4 *>(ts + (i0 - tb));
+            tl[0] = t4.x; tl[1] = t4.y; tl[2] = t4.z; tl[3] = t4.w;
+        }
+#define COMET_QUAD_STEPS(BP)                                                                          \
+        _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                  \
+            quad_item<V, WIDE>(st, quad_bcast_i<BP>(cr[s]), quad_bcast_d<BP>(va[s]), quad_bcast_i<BP>(tl[s]), Dn,  \
+                               rowmap, out, R, j);
+        COMET_QUAD_STEPS(0) COMET_QUAD_STEPS(1) COMET_QUAD_STEPS(2) COMET_QUAD_STEPS(3)
+#undef COMET_QUAD_STEPS
+    }
+
+    // publish this quad's open sum, then close the first segment end of every quad
+    {
+        double *qo = qopen + (Q * 4 + j) * V;
+#pragma unroll
+        for (int q = 0; q < V; ++q) qo[q] = st.acc[q];
+        if (j == 0) qht[Q] = st.ht;
+    }
+    __syncthreads();
+    const bool last = Q == 63;
+    if (st.ht || last) {
+        double sum[V];
+#pragma unroll
+        for (int q = 0; q < V; ++q) sum[q] = 0.0;
+        int found = 0;
+        for (int q2 = Q - 1; q2 >= 0; --q2) {
+            const double *qo = qopen + (q2 * 4 + j) * V;
+#pragma unroll
+            for (int q = 0; q < V; ++q) sum[q] += qo[q];
+            if (qht[q2]) { found = 1; break; }
+        }
+        CarryView cb = carry_view(scratch, ntiles, R);
+        if (st.ht) {
+            double value[V];
+#pragma unroll
+            for (int q = 0; q < V; ++q) value[q] = sum[q] + st.first[q];
+            if (found) {
+                quad_store_row<V, WIDE>(out, rowmap ? (int64_t)rowmap[st.first_id] : (int64_t)st.first_id, R, j, value);
+            } else {                                              // first segment end of the whole tile
+                quad_store_row<V, WIDE>(cb.first, t, R, j, value);
+                if (j == 0) cb.first_id[t] = st.first_id;
+            }
+        }
+        if (last) {
+            double topen[V];
+#pragma unroll
+            for (int q = 0; q < V; ++q) topen[q] = st.ht ? st.acc[q] : st.acc[q] + sum[q];
+            quad_store_row<V, WIDE>(cb.open, t, R, j, topen);
+            if (j == 0) cb.has_tail[t] = st.ht | found;
+        }
+    }
+}
+
+template <int V, bool WIDE>
+hipError_t launch_rankR(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
+                        const int32_t *rowmap, const double *Dn, int R, double *out, void *scratch, hipStream_t st) {
+    hipLaunchKernelGGL((k_stream_rankR<V, WIDE>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
+                       (const int32_t *)sc.seg_begin->ptr, rowmap, Dn, out, sc.nnz, sc.ntiles, R, scratch);
+    return hipGetLastError();
+}
+
 }  // namespace
 
-bool stream_supports_rank(int64_t R) { return R == 1; }
+bool stream_supports_rank(int64_t R) { return R >= 1 && R <= 64; }
 bool stream_mttkrp_supports_rank(int64_t) { return false; }
 bool stream_supports_coo() { return false; }
 
@@ -241,10 +408,23 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
                             const int32_t *rowmap, const double *Dn, int64_t R, double *out, void *scratch,
                             hipStream_t st) {
     if (sc.ntiles <= 0) return hipSuccess;
-    if (R != 1) return hipErrorNotSupported;
+    if (!stream_supports_rank(R)) return hipErrorNotSupported;
     const int32_t *sb = (const int32_t *)sc.seg_begin->ptr;
-    hipLaunchKernelGGL(k_stream_rank1, dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals, sb, rowmap, Dn, out,
-                       sc.nnz, sc.ntiles, scratch);
+    hipError_t e = hipSuccess;
+    if (R == 1) {
+        hipLaunchKernelGGL(k_stream_rank1, dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals, sb, rowmap, Dn,
+                           out, sc.nnz, sc.ntiles, scratch);
+        e = hipGetLastError();
+    } else if (R == 8)  e = launch_rankR<2, true>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
+    else if (R == 16)   e = launch_rankR<4, true>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
+    else if (R == 32)   e = launch_rankR<8, true>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
+    else if (R == 64)   e = launch_rankR<16, true>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
+    else if (R <= 4)    e = launch_rankR<1, false>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
+    else if (R <= 8)    e = launch_rankR<2, false>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
+    else if (R <= 16)   e = launch_rankR<4, false>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
+    else if (R <= 32)   e = launch_rankR<8, false>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
+    else                e = launch_rankR<16, false>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
+    if (e != hipSuccess) return e;
     const int64_t n = sc.ntiles * R;
     hipLaunchKernelGGL(k_stream_fixup, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, scratch, sc.ntiles, (int)R,
                        rowmap, out);
