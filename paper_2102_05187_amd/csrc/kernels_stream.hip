@@ -205,6 +205,62 @@ __global__ void __launch_bounds__(256) k_stream_rank1(const int32_t *__restrict_
     finish_tile_rank1(wsum_ht, wsum_open, wsum_first, wsum_first_id, rowmap, out, carry_view(scratch, ntiles, 1), t);
 }
 
+// ---- rank-1 kernel for sorted coordinate lists [CN,S,S] -------------------------------------------
+// A segment is a run of equal (c0, c1).  The root level keeps every coordinate and the lower levels
+// are singletons (one coordinate per position), so run ends are found by comparing neighbours.  The
+// result's own coordinate arrays are written here too: run number n (run_base[t] + runs started
+// earlier in the tile) gets y0[n], y1[n] from the run's first nonzero.
+__global__ void __launch_bounds__(256) k_stream_rank1_coo(const int32_t *__restrict__ c0, const int32_t *__restrict__ c1,
+                                                          const int32_t *__restrict__ c2, const double *__restrict__ vals,
+                                                          const int32_t *__restrict__ run_base,
+                                                          const double *__restrict__ v, int32_t *__restrict__ y0,
+                                                          int32_t *__restrict__ y1, double *__restrict__ yv, int64_t nnz,
+                                                          int64_t ntiles, void *scratch) {
+    __shared__ __attribute__((aligned(16))) int32_t ts[kTile];
+    __shared__ int wsum_ht[kWaves], wsum_first_id[kWaves], wcount[kWaves];
+    __shared__ double wsum_open[kWaves], wsum_first[kWaves];
+    const int64_t t = blockIdx.x;
+    const int64_t tb = t * (int64_t)kTile;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t wb = tb + (int64_t)w * kWaveItems;
+    constexpr int kRows = kWaveItems / 64;
+    unsigned long long hm[kRows];
+    int count = 0;
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        const int64_t i = wb + 64 * r + lane;
+        bool head = false;
+        if (i < nnz) head = i == 0 || c0[i] != c0[i - 1] || c1[i] != c1[i - 1];
+        hm[r] = __ballot(head);
+        count += __popcll(hm[r]);
+    }
+    // does the item right after this wavefront's range start a run (or lie past the end)?
+    const int64_t inext = wb + kWaveItems;
+    const bool next_head = inext >= nnz || c0[inext] != c0[inext - 1] || c1[inext] != c1[inext - 1];
+    if (lane == 0) wcount[w] = count;
+    __syncthreads();
+    int running = run_base[t];
+    for (int u = 0; u < w; ++u) running += wcount[u];
+    const unsigned long long le_mask = (2ull << lane) - 1ull;
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        const int64_t i = wb + 64 * r + lane;
+        const int id = running + __popcll(hm[r] & le_mask) - 1;
+        const bool head = (hm[r] >> lane) & 1ull;
+        bool tail;
+        if (lane < 63) tail = (hm[r] >> (lane + 1)) & 1ull;
+        else tail = r + 1 < kRows ? (hm[r + 1] & 1ull) != 0 : next_head;
+        if (i + 1 >= nnz) tail = true;
+        if (head) { y0[id] = c0[i]; y1[id] = c1[i]; }
+        ts[i - tb] = (i < nnz && tail) ? id : -1;
+        running += __popcll(hm[r]);
+    }
+    __syncthreads();
+    walk_rank1(ts, c2, vals, v, nullptr, yv, tb, nnz, wsum_ht, wsum_open, wsum_first, wsum_first_id);
+    __syncthreads();
+    finish_tile_rank1(wsum_ht, wsum_open, wsum_first, wsum_first_id, nullptr, yv, carry_view(scratch, ntiles, 1), t);
+}
+
 // ---- fix-up: finish the first segment end of every tile -------------------------------------------
 // value = first[t] + open[t-1] + open[t-2] + ... up to and including the nearest tile that contains
 // a segment end.  One thread per (tile, r).
@@ -393,11 +449,197 @@ hipError_t launch_rankR(const Schedule &sc, const int32_t *pos, const int32_t *c
     return hipGetLastError();
 }
 
+
+// ---- MTTKRP: the same quad walk, two nested segment levels ----------------------------------------
+// Inner level: fibers (segments of pos3); the per-fiber sum of vals * C[crd3, :] is scaled by the row
+// B[crd2[fiber], :] when the fiber ends and folded into the slice accumulator.  Scaling is linear,
+// so a fiber cut by a quad or tile boundary is folded piecewise (each piece times the same B row);
+// only the slice level needs carries.  Outer level: slices (segments of pos2); a slice end writes
+// row crd1[slice] of M.  Two LDS maps, both keyed by tile item: ts = fiber id at a fiber's last
+// nonzero, tm = output row at a slice's last nonzero (-1 elsewhere).
+template <int V, bool WIDE>
+__device__ __forceinline__ void quad_load_row(const double *__restrict__ Dn, int64_t row, int R, int j, double *d) {
+    const double *rowp = Dn + row * R;
+    if constexpr (WIDE) {
+#pragma unroll
+        for (int q = 0; q < V / 2; ++q) {
+            const double2 x = *reinterpret_cast<const double2 *>(rowp + 8 * q + 2 * j);
+            d[2 * q] = x.x; d[2 * q + 1] = x.y;
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < V; ++q) { int r = 4 * q + j; d[q] = r < R ? rowp[r] : 0.0; }
+    }
+}
+
+template <int V, bool WIDE>
+__global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict__ pos2, const int32_t *__restrict__ crd1,
+                                                       const int32_t *__restrict__ pos3, const int32_t *__restrict__ crd2,
+                                                       const int32_t *__restrict__ crd3, const double *__restrict__ vals,
+                                                       const int32_t *__restrict__ seg_begin,
+                                                       const int32_t *__restrict__ slice_begin,
+                                                       const double *__restrict__ Bm, const double *__restrict__ Cm,
+                                                       double *__restrict__ M, int64_t nnz, int64_t nfib, int64_t ntiles,
+                                                       int R, void *scratch) {
+    constexpr int kMapInts = 2 * kTile;
+    constexpr int kOpenInts = 64 * 4 * V * 2;
+    constexpr int kLdsInts = kMapInts > kOpenInts ? kMapInts : kOpenInts;
+    __shared__ __attribute__((aligned(16))) int32_t lds[kLdsInts];
+    __shared__ int qht[64], qfirst_fid[64];
+    int32_t *ts = lds, *tm = lds + kTile;
+    double *qopen = reinterpret_cast<double *>(lds);              // reused once the maps are dead
+    const int64_t t = blockIdx.x;
+    const int64_t tb = t * (int64_t)kTile, te = tb + kTile;
+
+    for (int i = threadIdx.x; i < 2 * kTile; i += blockDim.x) lds[i] = -1;
+    __syncthreads();
+    for (int32_t f = seg_begin[t] + threadIdx.x; f < seg_begin[t + 1]; f += blockDim.x) {
+        int32_t b = pos3[f], e = pos3[f + 1];
+        if (e > b) ts[(int64_t)e - 1 - tb] = f;
+    }
+    for (int32_t sl = slice_begin[t] + threadIdx.x; sl < slice_begin[t + 1]; sl += blockDim.x) {
+        int32_t fb = pos2[sl], fe = pos2[sl + 1];
+        int64_t il = -1;                                          // last nonzero of the slice
+        for (int32_t f = fe - 1; f >= fb; --f) {
+            int32_t b = pos3[f], e = pos3[f + 1];
+            if (e > b) { il = (int64_t)e - 1; break; }
+        }
+        if (il >= tb && il < te) tm[il - tb] = crd1[sl];
+    }
+    __syncthreads();
+
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, qw = lane >> 2, j = lane & 3;
+    const int Q = w * 16 + qw;
+    const int64_t qb = tb + (int64_t)Q * 64;
+    double facc[V], sacc[V], first[V];
+#pragma unroll
+    for (int q = 0; q < V; ++q) { facc[q] = 0.0; sacc[q] = 0.0; first[q] = 0.0; }
+    int ht = 0, first_row = -1, first_fid = -1, last_is_tail = 1;
+
+    for (int sb = 0; sb < 4; ++sb) {
+        const int64_t i0 = qb + 16 * sb + 4 * j;
+        int cr[4], tl[4], tr[4], jb[4];
+        double va[4];
+        if (i0 + 3 < nnz) {
+            const int4 c4 = *reinterpret_cast<const int4 *>(crd3 + i0);
+            const double2 a01 = *reinterpret_cast<const double2 *>(vals + i0);
+            const double2 a23 = *reinterpret_cast<const double2 *>(vals + i0 + 2);
+            cr[0] = c4.x; cr[1] = c4.y; cr[2] = c4.z; cr[3] = c4.w;
+            va[0] = a01.x; va[1] = a01.y; va[2] = a23.x; va[3] = a23.y;
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) { bool in = i0 + s < nnz; cr[s] = in ? crd3[i0 + s] : 0; va[s] = in ? vals[i0 + s] : 0.0; }
+        }
+        {
+            const int4 t4 = *reinterpret_cast<const int4 *>(ts + (i0 - tb));
+            const int4 m4 = *reinterpret_cast<const int4 *>(tm + (i0 - tb));
+            tl[0] = t4.x; tl[1] = t4.y; tl[2] = t4.z; tl[3] = t4.w;
+            tr[0] = m4.x; tr[1] = m4.y; tr[2] = m4.z; tr[3] = m4.w;
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) jb[s] = tl[s] >= 0 ? crd2[tl[s]] : 0;      // B row of a fiber that ends here
+        const bool any_item = qb + 16 * sb < nnz;
+#define COMET_MTTKRP_STEPS(BP)                                                                        \
+        _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                                \
+            const int c = quad_bcast_i<BP>(cr[s]);                                                     \
+            const double a = quad_bcast_d<BP>(va[s]);                                                  \
+            const int tf = quad_bcast_i<BP>(tl[s]);                                                    \
+            const int tmr = quad_bcast_i<BP>(tr[s]);                                                   \
+            const int jrow = quad_bcast_i<BP>(jb[s]);                                                  \
+            double d[V];                                                                               \
+            quad_load_row<V, WIDE>(Cm, c, R, j, d);                                                    \
+            _Pragma("unroll") for (int q = 0; q < V; ++q) facc[q] = fma(a, d[q], facc[q]);             \
+            if (any_item) last_is_tail = tf >= 0;                                                      \
+            if (tf >= 0) {                                                                             \
+                if (first_fid < 0) first_fid = tf;                                                     \
+                double bw[V];                                                                          \
+                quad_load_row<V, WIDE>(Bm, jrow, R, j, bw);                                            \
+                _Pragma("unroll") for (int q = 0; q < V; ++q) { sacc[q] = fma(bw[q], facc[q], sacc[q]); facc[q] = 0.0; } \
+                if (tmr >= 0) {                                                                        \
+                    if (!ht) {                                                                         \
+                        _Pragma("unroll") for (int q = 0; q < V; ++q) first[q] = sacc[q];              \
+                        first_row = tmr; ht = 1;                                                       \
+                    } else {                                                                           \
+                        quad_store_row<V, WIDE>(M, tmr, R, j, sacc);                                   \
+                    }                                                                                  \
+                    _Pragma("unroll") for (int q = 0; q < V; ++q) sacc[q] = 0.0;                       \
+                }                                                                                      \
+            }                                                                                          \
+        }
+        COMET_MTTKRP_STEPS(0) COMET_MTTKRP_STEPS(1) COMET_MTTKRP_STEPS(2) COMET_MTTKRP_STEPS(3)
+#undef COMET_MTTKRP_STEPS
+    }
+
+    // A fiber left open at the end of this quad's range ends at the next fiber end of the tile, or,
+    // if there is none, it is the fiber that contains the first nonzero of the next tile.
+    if (j == 0) qfirst_fid[Q] = first_fid;
+    __syncthreads();                                              // also: every walk is done, the maps are dead
+    if (!last_is_tail) {
+        int64_t fid = seg_begin[t + 1];
+        for (int q2 = Q + 1; q2 < 64; ++q2) { int f2 = qfirst_fid[q2]; if (f2 >= 0) { fid = f2; break; } }
+        if (fid < nfib) {
+            double bw[V];
+            quad_load_row<V, WIDE>(Bm, crd2[fid], R, j, bw);
+#pragma unroll
+            for (int q = 0; q < V; ++q) sacc[q] = fma(bw[q], facc[q], sacc[q]);
+        }
+    }
+    {
+        double *qo = qopen + (Q * 4 + j) * V;
+#pragma unroll
+        for (int q = 0; q < V; ++q) qo[q] = sacc[q];
+        if (j == 0) qht[Q] = ht;
+    }
+    __syncthreads();
+    const bool last = Q == 63;
+    if (ht || last) {
+        double sum[V];
+#pragma unroll
+        for (int q = 0; q < V; ++q) sum[q] = 0.0;
+        int found = 0;
+        for (int q2 = Q - 1; q2 >= 0; --q2) {
+            const double *qo = qopen + (q2 * 4 + j) * V;
+#pragma unroll
+            for (int q = 0; q < V; ++q) sum[q] += qo[q];
+            if (qht[q2]) { found = 1; break; }
+        }
+        CarryView cb = carry_view(scratch, ntiles, R);
+        if (ht) {
+            double value[V];
+#pragma unroll
+            for (int q = 0; q < V; ++q) value[q] = sum[q] + first[q];
+            if (found) {
+                quad_store_row<V, WIDE>(M, first_row, R, j, value);
+            } else {
+                quad_store_row<V, WIDE>(cb.first, t, R, j, value);
+                if (j == 0) cb.first_id[t] = first_row;
+            }
+        }
+        if (last) {
+            double topen[V];
+#pragma unroll
+            for (int q = 0; q < V; ++q) topen[q] = ht ? sacc[q] : sacc[q] + sum[q];
+            quad_store_row<V, WIDE>(cb.open, t, R, j, topen);
+            if (j == 0) cb.has_tail[t] = ht | found;
+        }
+    }
+}
+
+template <int V, bool WIDE>
+hipError_t launch_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t *crd1, const int32_t *pos3,
+                         const int32_t *crd2, const int32_t *crd3, const double *vals, const double *B, const double *C,
+                         int R, double *M, void *scratch, hipStream_t st) {
+    hipLaunchKernelGGL((k_stream_mttkrp<V, WIDE>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos2, crd1, pos3, crd2,
+                       crd3, vals, (const int32_t *)sc.seg_begin->ptr, (const int32_t *)sc.slice_begin->ptr, B, C, M,
+                       sc.nnz, sc.nseg, sc.ntiles, R, scratch);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 bool stream_supports_rank(int64_t R) { return R >= 1 && R <= 64; }
-bool stream_mttkrp_supports_rank(int64_t) { return false; }
-bool stream_supports_coo() { return false; }
+bool stream_mttkrp_supports_rank(int64_t R) { return R >= 1 && R <= 64; }
+bool stream_supports_coo() { return true; }
 
 size_t stream_scratch_bytes(int64_t ntiles, int64_t R) {
     size_t n = (size_t)(ntiles < 1 ? 1 : ntiles);
@@ -431,15 +673,39 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
     return hipGetLastError();
 }
 
-hipError_t stream_ttv_coo(const Schedule &, const int32_t *, const int32_t *, const int32_t *, const double *,
-                          const double *, int32_t *, int32_t *, double *, void *, hipStream_t) {
-    return hipErrorNotSupported;
+hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *c1, const int32_t *c2,
+                          const double *vals, const double *v, int32_t *y0, int32_t *y1, double *yv, void *scratch,
+                          hipStream_t st) {
+    if (sc.ntiles <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_stream_rank1_coo, dim3((unsigned)sc.ntiles), dim3(256), 0, st, c0, c1, c2, vals,
+                       (const int32_t *)sc.run_base->ptr, v, y0, y1, yv, sc.nnz, sc.ntiles, scratch);
+    hipLaunchKernelGGL(k_stream_fixup, dim3((unsigned)((sc.ntiles + 255) / 256)), dim3(256), 0, st, scratch, sc.ntiles, 1,
+                       (const int32_t *)nullptr, yv);
+    return hipGetLastError();
 }
 
-hipError_t stream_mttkrp(const Schedule &, const int32_t *, const int32_t *, int64_t, const int32_t *, const int32_t *,
-                         const int32_t *, const double *, const double *, const double *, int64_t, double *, void *,
-                         hipStream_t) {
-    return hipErrorNotSupported;
+hipError_t stream_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t *crd1, int64_t nslice,
+                         const int32_t *pos3, const int32_t *crd2, const int32_t *crd3, const double *vals,
+                         const double *B, const double *C, int64_t R, double *M, void *scratch, hipStream_t st) {
+    (void)nslice;
+    if (sc.ntiles <= 0) return hipSuccess;
+    if (!stream_mttkrp_supports_rank(R) || !sc.slice_begin) return hipErrorNotSupported;
+    hipError_t e;
+    const int r = (int)R;
+    if (R == 8)        e = launch_mttkrp<2, true>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
+    else if (R == 16)  e = launch_mttkrp<4, true>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
+    else if (R == 32)  e = launch_mttkrp<8, true>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
+    else if (R == 64)  e = launch_mttkrp<16, true>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
+    else if (R <= 4)   e = launch_mttkrp<1, false>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
+    else if (R <= 8)   e = launch_mttkrp<2, false>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
+    else if (R <= 16)  e = launch_mttkrp<4, false>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
+    else if (R <= 32)  e = launch_mttkrp<8, false>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
+    else               e = launch_mttkrp<16, false>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
+    if (e != hipSuccess) return e;
+    const int64_t n = sc.ntiles * R;
+    hipLaunchKernelGGL(k_stream_fixup, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, scratch, sc.ntiles, r,
+                       (const int32_t *)nullptr, M);
+    return hipGetLastError();
 }
 
 }  // namespace comet
