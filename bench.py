@@ -103,12 +103,13 @@ def run_op(op, args, comet, dev):
         keep = dict(A=A, L=L, B=B, C=C, coo=(rows, cols, vals), n=n)
     else:
         R = {"ttv": 1, "ttv_coo": 1, "ttm": 16, "mttkrp16": 16, "mttkrp64": 64}[op]
+        kw = {"permute": not args.identity_ranks}
         if op.startswith("ttv"):
-            c = gen.config_ttv(seed=0, device=dev, scale=sc)
+            c = gen.config_ttv(seed=0, device=dev, scale=sc, **kw)
         elif op == "ttm":
-            c = gen.config_ttm(seed=0, device=dev, scale=sc, R=R)
+            c = gen.config_ttm(seed=0, device=dev, scale=sc, R=R, **kw)
         else:
-            c = gen.config_mttkrp(seed=0, device=dev, scale=sc, R=R)
+            c = gen.config_mttkrp(seed=0, device=dev, scale=sc, R=R, **kw)
         i, j, k, vals = c["coo"]
         dims = c["dims"]
         nnz = vals.numel()
@@ -199,6 +200,8 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink every configuration (testing only)")
     ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 simple kernels, 2 tiled kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--identity-ranks", action="store_true",
+                    help="tensor configs: Zipf rank r maps to coordinate r (clusters the nonzeros) instead of a seeded permutation")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on one GPU only (no sharding, no collectives); run it with --gpus 1.")
@@ -234,7 +237,8 @@ def main():
         "value": head["gflops"], "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": head["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
-        "config": {"workload": head["workload"], "index_dtype": "int32", "scale": args.scale, "variant": args.variant},
+        "config": {"workload": head["workload"], "index_dtype": "int32", "scale": args.scale, "variant": args.variant,
+                   "zipf_rank_to_coordinate": "identity" if args.identity_ranks else "seeded permutation"},
         "roofline": head["roofline"], "cpu_baseline": cpu, "kernels": kernels,
     }
     print(json.dumps(line), flush=True)

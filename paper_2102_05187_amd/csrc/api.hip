@@ -78,6 +78,13 @@ comet_status build_schedule(comet_tensor &t, hipStream_t st) {
         comet_status rs = read_i32((const int32_t *)mx->ptr, 1, &h, st);
         if (rs != COMET_OK) return rs;
         sc.max_seg_len = h;
+        if (t.fmt == Format::CSF3) {
+            HIP_TRY(hipMemsetAsync(mx->ptr, 0, sizeof(int32_t), st));
+            HIP_TRY(comet::max_parent_span(t.pos_i(1), t.pos_len[1] - 1, t.pos_i(2), (int32_t *)mx->ptr, st));
+            rs = read_i32((const int32_t *)mx->ptr, 1, &h, st);
+            if (rs != COMET_OK) return rs;
+            sc.max_parent_len = h;
+        }
     } else if (t.fmt == Format::COO3) {
         sc.nnz = t.nvals;
         sc.ntiles = (sc.nnz + tile - 1) / tile;

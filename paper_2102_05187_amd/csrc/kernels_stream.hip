@@ -63,29 +63,36 @@ __device__ __forceinline__ void segscan_inclusive(int &f, double &v) {
 #undef COMET_SCAN_STEP
 }
 
-// Carry-buffer layout inside the per-tensor scratch: per tile  first[R], open[R] (fp64), then
-// has_tail and first_id (int32).
+// Carry-buffer layout inside the per-tensor scratch.  Level 0 holds one summary per tile: first[R],
+// open[R] (fp64), has_tail and first_id (int32).  Level l+1 holds one summary per group of
+// kFixGroup consecutive level-l summaries (same layout), so that a segment cut over thousands of
+// tiles is finished in a few short passes instead of one long serial walk.
+constexpr int kFixGroup = 64;
 struct CarryView {
     double  *first, *open;
     int32_t *has_tail, *first_id;
 };
-__host__ __device__ inline CarryView carry_view(void *scratch, int64_t ntiles, int64_t R) {
+__host__ __device__ inline size_t carry_level_bytes(int64_t n, int64_t R) {
+    size_t b = (size_t)n * (size_t)R * 2 * sizeof(double) + (size_t)n * 2 * sizeof(int32_t);
+    return (b + 255) & ~(size_t)255;
+}
+__host__ __device__ inline CarryView carry_view(void *scratch, int64_t n, int64_t R) {
     CarryView c;
     c.first = (double *)scratch;
-    c.open = c.first + ntiles * R;
-    c.has_tail = (int32_t *)(c.open + ntiles * R);
-    c.first_id = c.has_tail + ntiles;
+    c.open = c.first + n * R;
+    c.has_tail = (int32_t *)(c.open + n * R);
+    c.first_id = c.has_tail + n;
     return c;
 }
 
 // ---- phase A/B for compressed levels: fill the tail map from pos, zero-fill empty segments -------
 // Segments [seg_begin[t], seg_begin[t+1]) end inside tile t (the segment that contains the first
 // item of the next tile ends later), so each of them owns exactly one map entry.
-template <bool WIDE_OUT>
 __device__ __forceinline__ void build_tail_map_from_pos(int32_t *ts, const int32_t *__restrict__ pos,
                                                         const int32_t *__restrict__ rowmap, int64_t tb, int32_t s0,
                                                         int32_t s1, double *__restrict__ out, int R) {
-    for (int i = threadIdx.x; i < kTile; i += blockDim.x) ts[i] = -1;
+    for (int i = threadIdx.x * 4; i < kTile; i += blockDim.x * 4)
+        *reinterpret_cast<int4 *>(ts + i) = make_int4(-1, -1, -1, -1);
     __syncthreads();
     for (int32_t s = s0 + threadIdx.x; s < s1; s += blockDim.x) {
         int32_t b = pos[s], e = pos[s + 1];
@@ -99,54 +106,70 @@ __device__ __forceinline__ void build_tail_map_from_pos(int32_t *ts, const int32
     __syncthreads();
 }
 
-// ---- rank-1 walk: each lane owns 2 consecutive items per 128-item block --------------------------
-// Returns through LDS: wsum_ht[w], wsum_open[w], wsum_first[w], wsum_first_id[w].
-__device__ __forceinline__ void walk_rank1(const int32_t *ts, const int32_t *__restrict__ crd,
-                                           const double *__restrict__ vals, const double *__restrict__ x,
-                                           const int32_t *__restrict__ rowmap, double *__restrict__ out, int64_t tb,
-                                           int64_t nnz, int *wsum_ht, double *wsum_open, double *wsum_first,
-                                           int *wsum_first_id) {
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int64_t wb = tb + (int64_t)w * kWaveItems;
-    int cf = 0;          // carry of this wavefront over the blocks done so far: has_tail, open
-    double cv = 0.0;
-#pragma unroll 2
-    for (int blk = 0; blk < kWaveItems / 128; ++blk) {
-        const int64_t i0 = wb + blk * 128 + 2 * lane;
-        if (wb + blk * 128 >= nnz) break;                    // uniform: nothing left in this wavefront's range
-        int2 c;
-        double2 a;
+// ---- rank-1 walk ---------------------------------------------------------------------------------
+// A wavefront owns 1024 consecutive items = 8 blocks of 128; in a block lane l holds items 2l, 2l+1
+// (one 8-byte crd load and one 16-byte vals load per lane, consecutive lanes on consecutive bytes).
+// The loads of four blocks are issued together, and the first four before the tail map is built, so
+// the HBM latency overlaps the map construction and the scans of the preceding blocks.
+struct Rank1Half {
+    int2    c[4];
+    double2 a[4];
+};
+
+__device__ __forceinline__ void rank1_load_half(Rank1Half &h, const int32_t *__restrict__ crd,
+                                                const double *__restrict__ vals, int64_t base, int lane, int64_t nnz) {
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const int64_t i0 = base + b * 128 + 2 * lane;
         if (i0 + 1 < nnz) {
-            c = *reinterpret_cast<const int2 *>(crd + i0);
-            a = *reinterpret_cast<const double2 *>(vals + i0);
+            // streamed once: non-temporal, so the lines do not displace the gathered operand in L1/L2
+            const long long cc = __builtin_nontemporal_load(reinterpret_cast<const long long *>(crd + i0));
+            h.c[b].x = (int)(cc & 0xffffffffll); h.c[b].y = (int)(cc >> 32);
+            h.a[b].x = __builtin_nontemporal_load(vals + i0);
+            h.a[b].y = __builtin_nontemporal_load(vals + i0 + 1);
         } else {
-            c.x = i0 < nnz ? crd[i0] : 0;  c.y = 0;
-            a.x = i0 < nnz ? vals[i0] : 0.0;  a.y = 0.0;
+            h.c[b].x = i0 < nnz ? crd[i0] : 0;   h.c[b].y = 0;
+            h.a[b].x = i0 < nnz ? vals[i0] : 0.0; h.a[b].y = 0.0;
         }
+    }
+}
+
+struct Rank1Carry {
+    int    cf;     // a segment end was seen in the blocks done so far
+    double cv;     // sum of the items after the last segment end
+};
+
+template <bool ROWMAP>
+__device__ __forceinline__ void rank1_process_half(const Rank1Half &h, const double2 *xv, const int32_t *ts,
+                                                   int64_t base, int64_t tb, int64_t nnz, int lane, int w,
+                                                   const int32_t *__restrict__ rowmap, double *__restrict__ out,
+                                                   Rank1Carry &cy, double *wsum_first, int *wsum_first_id) {
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+        const int64_t i0 = base + b * 128 + 2 * lane;
         const int2 t = *reinterpret_cast<const int2 *>(ts + (i0 - tb));
-        const double p0 = a.x * x[c.x];
-        const double p1 = i0 + 1 < nnz ? a.y * x[c.y] : 0.0;
-        // lane summary
-        int f = (t.x >= 0) | (t.y >= 0);
-        double first = t.x >= 0 ? p0 : p0 + p1;
-        int first_id = t.x >= 0 ? t.x : t.y;
-        double open = t.y >= 0 ? 0.0 : (t.x >= 0 ? p1 : p0 + p1);
+        const double p0 = i0 < nnz ? h.a[b].x * xv[b].x : 0.0;
+        const double p1 = i0 + 1 < nnz ? h.a[b].y * xv[b].y : 0.0;
+        const int f = (t.x >= 0) | (t.y >= 0);
+        const double first = t.x >= 0 ? p0 : p0 + p1;
+        const int first_id = t.x >= 0 ? t.x : t.y;
+        const double open = t.y >= 0 ? 0.0 : (t.x >= 0 ? p1 : p0 + p1);
         if (t.x >= 0 && t.y >= 0) {                          // item i0+1 is a whole segment by itself
-            int64_t row = rowmap ? (int64_t)rowmap[t.y] : (int64_t)t.y;
+            const int64_t row = ROWMAP ? (int64_t)rowmap[t.y] : (int64_t)t.y;
             out[row] = p1;
         }
         int sf = f;
         double sv = open;
         segscan_inclusive(sf, sv);
         // exclusive value for this lane = carry (+) inclusive value of the previous lane
-        int pf = dpp_i<0x138, 0xf>(0, sf);                   // wave_shr:1, lane 0 keeps the identity
-        double pv = dpp_d<0x138, 0xf>(0.0, sv);
-        const int ef = cf | pf;
-        const double ev = pf ? pv : cv + pv;
+        const int pf = dpp_i<0x138, 0xf>(0, sf);             // wave_shr:1, lane 0 keeps the identity
+        const double pv = dpp_d<0x138, 0xf>(0.0, sv);
+        const int ef = cy.cf | pf;
+        const double ev = pf ? pv : cy.cv + pv;
         if (f) {
             const double value = ev + first;
             if (ef) {
-                int64_t row = rowmap ? (int64_t)rowmap[first_id] : (int64_t)first_id;
+                const int64_t row = ROWMAP ? (int64_t)rowmap[first_id] : (int64_t)first_id;
                 out[row] = value;
             } else {                                         // the first segment end of this wavefront's range
                 wsum_first[w] = value;
@@ -155,13 +178,38 @@ __device__ __forceinline__ void walk_rank1(const int32_t *ts, const int32_t *__r
         }
         const int tf = __builtin_amdgcn_readlane(sf, 63);
         const double tv = readlane_d(sv, 63);
-        cv = tf ? tv : cv + tv;
-        cf |= tf;
+        cy.cv = tf ? tv : cy.cv + tv;
+        cy.cf |= tf;
     }
-    if (lane == 0) { wsum_ht[w] = cf; wsum_open[w] = cv; }
+}
+
+__device__ __forceinline__ void rank1_gather(const Rank1Half &h, const double *__restrict__ x, double2 *xv) {
+#pragma unroll
+    for (int b = 0; b < 4; ++b) { xv[b].x = x[h.c[b].x]; xv[b].y = x[h.c[b].y]; }
+}
+
+// Second part of the walk (after the map is complete); h0 holds the already issued first half.
+template <bool ROWMAP>
+__device__ __forceinline__ void walk_rank1(Rank1Half &h0, const int32_t *ts, const int32_t *__restrict__ crd,
+                                           const double *__restrict__ vals, const double *__restrict__ x,
+                                           const int32_t *__restrict__ rowmap, double *__restrict__ out, int64_t tb,
+                                           int64_t nnz, int *wsum_ht, double *wsum_open, double *wsum_first,
+                                           int *wsum_first_id) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t wb = tb + (int64_t)w * kWaveItems;
+    Rank1Carry cy{0, 0.0};
+    double2 xv[4];
+    rank1_gather(h0, x, xv);
+    Rank1Half h1;
+    rank1_load_half(h1, crd, vals, wb + 512, lane, nnz);
+    rank1_process_half<ROWMAP>(h0, xv, ts, wb, tb, nnz, lane, w, rowmap, out, cy, wsum_first, wsum_first_id);
+    rank1_gather(h1, x, xv);
+    rank1_process_half<ROWMAP>(h1, xv, ts, wb + 512, tb, nnz, lane, w, rowmap, out, cy, wsum_first, wsum_first_id);
+    if (lane == 0) { wsum_ht[w] = cy.cf; wsum_open[w] = cy.cv; }
 }
 
 // Combine the wavefront summaries of one tile in order and publish the tile summary.
+template <bool ROWMAP>
 __device__ __forceinline__ void finish_tile_rank1(const int *wsum_ht, const double *wsum_open, const double *wsum_first,
                                                   const int *wsum_first_id, const int32_t *__restrict__ rowmap,
                                                   double *__restrict__ out, CarryView cb, int64_t t) {
@@ -172,7 +220,7 @@ __device__ __forceinline__ void finish_tile_rank1(const int *wsum_ht, const doub
         if (wsum_ht[w]) {
             const double value = rv + wsum_first[w];
             if (rf) {
-                int64_t row = rowmap ? (int64_t)rowmap[wsum_first_id[w]] : (int64_t)wsum_first_id[w];
+                const int64_t row = ROWMAP ? (int64_t)rowmap[wsum_first_id[w]] : (int64_t)wsum_first_id[w];
                 out[row] = value;
             } else {
                 tfirst = value; fid = wsum_first_id[w]; rf = 1;
@@ -188,6 +236,7 @@ __device__ __forceinline__ void finish_tile_rank1(const int *wsum_ht, const doub
     cb.open[t] = rv;
 }
 
+template <bool ROWMAP>
 __global__ void __launch_bounds__(256) k_stream_rank1(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
                                                       const double *__restrict__ vals,
                                                       const int32_t *__restrict__ seg_begin,
@@ -199,10 +248,12 @@ __global__ void __launch_bounds__(256) k_stream_rank1(const int32_t *__restrict_
     __shared__ double wsum_open[kWaves], wsum_first[kWaves];
     const int64_t t = blockIdx.x;
     const int64_t tb = t * (int64_t)kTile;
-    build_tail_map_from_pos<false>(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, 1);
-    walk_rank1(ts, crd, vals, x, rowmap, out, tb, nnz, wsum_ht, wsum_open, wsum_first, wsum_first_id);
+    Rank1Half h0;
+    rank1_load_half(h0, crd, vals, tb + (int64_t)(threadIdx.x >> 6) * kWaveItems, threadIdx.x & 63, nnz);
+    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, 1);
+    walk_rank1<ROWMAP>(h0, ts, crd, vals, x, rowmap, out, tb, nnz, wsum_ht, wsum_open, wsum_first, wsum_first_id);
     __syncthreads();
-    finish_tile_rank1(wsum_ht, wsum_open, wsum_first, wsum_first_id, rowmap, out, carry_view(scratch, ntiles, 1), t);
+    finish_tile_rank1<ROWMAP>(wsum_ht, wsum_open, wsum_first, wsum_first_id, rowmap, out, carry_view(scratch, ntiles, 1), t);
 }
 
 // ---- rank-1 kernel for sorted coordinate lists [CN,S,S] -------------------------------------------
@@ -223,6 +274,8 @@ __global__ void __launch_bounds__(256) k_stream_rank1_coo(const int32_t *__restr
     const int64_t tb = t * (int64_t)kTile;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int64_t wb = tb + (int64_t)w * kWaveItems;
+    Rank1Half h0;
+    rank1_load_half(h0, c2, vals, wb, lane, nnz);
     constexpr int kRows = kWaveItems / 64;
     unsigned long long hm[kRows];
     int count = 0;
@@ -256,9 +309,9 @@ __global__ void __launch_bounds__(256) k_stream_rank1_coo(const int32_t *__restr
         running += __popcll(hm[r]);
     }
     __syncthreads();
-    walk_rank1(ts, c2, vals, v, nullptr, yv, tb, nnz, wsum_ht, wsum_open, wsum_first, wsum_first_id);
+    walk_rank1<false>(h0, ts, c2, vals, v, nullptr, yv, tb, nnz, wsum_ht, wsum_open, wsum_first, wsum_first_id);
     __syncthreads();
-    finish_tile_rank1(wsum_ht, wsum_open, wsum_first, wsum_first_id, nullptr, yv, carry_view(scratch, ntiles, 1), t);
+    finish_tile_rank1<false>(wsum_ht, wsum_open, wsum_first, wsum_first_id, nullptr, yv, carry_view(scratch, ntiles, 1), t);
 }
 
 // ---- fix-up: finish the first segment end of every tile -------------------------------------------
@@ -363,7 +416,7 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
     __shared__ int qht[64];
     const int64_t t = blockIdx.x;
     const int64_t tb = t * (int64_t)kTile;
-    build_tail_map_from_pos<true>(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, R);
+    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, R);
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, qw = lane >> 2, j = lane & 3;
     const int Q = w * 16 + qw;                                    // quad index inside the tile
@@ -635,6 +688,72 @@ hipError_t launch_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t 
     return hipGetLastError();
 }
 
+
+// One pass of the hierarchical fix-up: thread (g, r) folds the kFixGroup summaries of group g in
+// order.  A segment end whose carry chain starts inside the group is final and is written to out;
+// the group's own summary (first segment end, trailing open sum) goes one level up.
+__global__ void __launch_bounds__(256) k_fixup_level(const double *__restrict__ lo_first, const double *__restrict__ lo_open,
+                                                     const int32_t *__restrict__ lo_ht, const int32_t *__restrict__ lo_id,
+                                                     int64_t n_lo, double *__restrict__ up_first,
+                                                     double *__restrict__ up_open, int32_t *__restrict__ up_ht,
+                                                     int32_t *__restrict__ up_id, int64_t n_up, int R,
+                                                     const int32_t *__restrict__ rowmap, double *__restrict__ out) {
+    const int64_t gidx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gidx >= n_up * R) return;
+    const int64_t g = gidx / R;
+    const int r = (int)(gidx - g * R);
+    const int64_t u0 = g * kFixGroup;
+    const int64_t u1 = u0 + kFixGroup < n_lo ? u0 + kFixGroup : n_lo;
+    int rf = 0, gid = -1;
+    double rv = 0.0, gfirst = 0.0;
+#pragma unroll 8
+    for (int64_t u = u0; u < u1; ++u) {
+        const int ht = lo_ht[u];
+        const double op = lo_open[u * R + r];
+        if (ht) {
+            const double value = rv + lo_first[u * R + r];
+            const int32_t id = lo_id[u];
+            if (rf) {
+                const int64_t row = rowmap ? (int64_t)rowmap[id] : (int64_t)id;
+                out[row * R + r] = value;
+            } else {
+                gfirst = value; gid = id; rf = 1;
+            }
+            rv = op;
+        } else {
+            rv += op;
+        }
+    }
+    up_first[g * R + r] = gfirst;
+    up_open[g * R + r] = rv;
+    if (r == 0) { up_ht[g] = rf; up_id[g] = gid; }
+}
+
+// Finish every segment that a tile boundary cut: fold the tile summaries level by level, then
+// walk the few top-level summaries serially.  `max_chain` bounds the number of consecutive tiles
+// one segment can span (0 = unknown); short chains go straight to the serial walk.
+hipError_t run_fixup(void *scratch, int64_t ntiles, int R, const int32_t *rowmap, double *out, int64_t max_chain,
+                     hipStream_t st) {
+    char *base = (char *)scratch;
+    int64_t n = ntiles;
+    const bool direct = max_chain > 0 && max_chain <= 24;
+    while (!direct && n > kFixGroup) {
+        const int64_t n_up = (n + kFixGroup - 1) / kFixGroup;
+        CarryView lo = carry_view(base, n, R);
+        char *up_base = base + carry_level_bytes(n, R);
+        CarryView up = carry_view(up_base, n_up, R);
+        const int64_t threads = n_up * R;
+        hipLaunchKernelGGL(k_fixup_level, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, lo.first, lo.open,
+                           lo.has_tail, lo.first_id, n, up.first, up.open, up.has_tail, up.first_id, n_up, R, rowmap, out);
+        base = up_base;
+        n = n_up;
+    }
+    const int64_t threads = n * R;
+    hipLaunchKernelGGL(k_stream_fixup, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, (void *)base, n, R,
+                       rowmap, out);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 bool stream_supports_rank(int64_t R) { return R >= 1 && R <= 64; }
@@ -642,8 +761,14 @@ bool stream_mttkrp_supports_rank(int64_t R) { return R >= 1 && R <= 64; }
 bool stream_supports_coo() { return true; }
 
 size_t stream_scratch_bytes(int64_t ntiles, int64_t R) {
-    size_t n = (size_t)(ntiles < 1 ? 1 : ntiles);
-    return n * (size_t)R * 2 * sizeof(double) + n * 2 * sizeof(int32_t) + 64;
+    int64_t n = ntiles < 1 ? 1 : ntiles;
+    size_t total = 0;
+    for (;;) {
+        total += carry_level_bytes(n, R);
+        if (n <= kFixGroup) break;
+        n = (n + kFixGroup - 1) / kFixGroup;
+    }
+    return total + 256;
 }
 
 hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
@@ -654,8 +779,12 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
     const int32_t *sb = (const int32_t *)sc.seg_begin->ptr;
     hipError_t e = hipSuccess;
     if (R == 1) {
-        hipLaunchKernelGGL(k_stream_rank1, dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals, sb, rowmap, Dn,
-                           out, sc.nnz, sc.ntiles, scratch);
+        if (rowmap)
+            hipLaunchKernelGGL(k_stream_rank1<true>, dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals, sb,
+                               rowmap, Dn, out, sc.nnz, sc.ntiles, scratch);
+        else
+            hipLaunchKernelGGL(k_stream_rank1<false>, dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals, sb,
+                               rowmap, Dn, out, sc.nnz, sc.ntiles, scratch);
         e = hipGetLastError();
     } else if (R == 8)  e = launch_rankR<2, true>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
     else if (R == 16)   e = launch_rankR<4, true>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
@@ -667,10 +796,7 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
     else if (R <= 32)   e = launch_rankR<8, false>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
     else                e = launch_rankR<16, false>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
     if (e != hipSuccess) return e;
-    const int64_t n = sc.ntiles * R;
-    hipLaunchKernelGGL(k_stream_fixup, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, scratch, sc.ntiles, (int)R,
-                       rowmap, out);
-    return hipGetLastError();
+    return run_fixup(scratch, sc.ntiles, (int)R, rowmap, out, sc.max_seg_len / kTile + 2, st);
 }
 
 hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *c1, const int32_t *c2,
@@ -679,9 +805,7 @@ hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *
     if (sc.ntiles <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_stream_rank1_coo, dim3((unsigned)sc.ntiles), dim3(256), 0, st, c0, c1, c2, vals,
                        (const int32_t *)sc.run_base->ptr, v, y0, y1, yv, sc.nnz, sc.ntiles, scratch);
-    hipLaunchKernelGGL(k_stream_fixup, dim3((unsigned)((sc.ntiles + 255) / 256)), dim3(256), 0, st, scratch, sc.ntiles, 1,
-                       (const int32_t *)nullptr, yv);
-    return hipGetLastError();
+    return run_fixup(scratch, sc.ntiles, 1, nullptr, yv, sc.max_seg_len > 0 ? sc.max_seg_len / kTile + 2 : 0, st);
 }
 
 hipError_t stream_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t *crd1, int64_t nslice,
@@ -702,10 +826,7 @@ hipError_t stream_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t 
     else if (R <= 32)  e = launch_mttkrp<8, false>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
     else               e = launch_mttkrp<16, false>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
     if (e != hipSuccess) return e;
-    const int64_t n = sc.ntiles * R;
-    hipLaunchKernelGGL(k_stream_fixup, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, scratch, sc.ntiles, r,
-                       (const int32_t *)nullptr, M);
-    return hipGetLastError();
+    return run_fixup(scratch, sc.ntiles, r, nullptr, M, sc.max_parent_len > 0 ? sc.max_parent_len / kTile + 2 : 0, st);
 }
 
 }  // namespace comet

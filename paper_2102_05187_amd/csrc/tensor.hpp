@@ -55,7 +55,8 @@ struct Schedule {
     DevRef  slice_begin;   // int32 [ntiles + 1]   (CSF3 only)
     DevRef  run_base;      // int32 [ntiles + 1]   (COO3 only)
     int64_t nruns = 0;     // COO3: number of distinct (i,j) pairs
-    int64_t max_seg_len = 0;
+    int64_t max_seg_len = 0;      // longest leaf segment, in nonzeros (0 = unknown)
+    int64_t max_parent_len = 0;   // CSF3: most nonzeros under one slice (0 = unknown)
 };
 
 }  // namespace comet

@@ -233,4 +233,25 @@ hipError_t max_segment_length(const int32_t *pos, int64_t nseg, int32_t *out_max
     return hipGetLastError();
 }
 
+// most leaf positions under one parent segment: max over s of pos_leaf[pos_par[s+1]] - pos_leaf[pos_par[s]]
+__global__ void __launch_bounds__(256) k_max_parent_span(const int32_t *__restrict__ ppos, int64_t nparent,
+                                                         const int32_t *__restrict__ lpos, int32_t *__restrict__ out) {
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int32_t m = 0;
+    for (int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; s < nparent; s += stride) {
+        int32_t l = lpos[ppos[s + 1]] - lpos[ppos[s]];
+        m = l > m ? l : m;
+    }
+    if (m > 0) atomicMax(out, m);
+}
+
+hipError_t max_parent_span(const int32_t *parent_pos, int64_t nparent, const int32_t *leaf_pos, int32_t *out_max,
+                           hipStream_t st) {
+    if (nparent <= 0) return hipSuccess;
+    int64_t want = (nparent + 255) / 256;
+    unsigned grid = (unsigned)(want > 2048 ? 2048 : want);
+    hipLaunchKernelGGL(k_max_parent_span, dim3(grid), dim3(256), 0, st, parent_pos, nparent, leaf_pos, out_max);
+    return hipGetLastError();
+}
+
 }  // namespace comet

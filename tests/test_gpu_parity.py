@@ -54,6 +54,9 @@ def _matrix_cases():
     cases["empty"] = ((5, 7), (torch.zeros(0, dtype=torch.int64), torch.zeros(0, dtype=torch.int64),
                               torch.zeros(0, dtype=torch.float64)))
     cases["single"] = ((5, 7), (torch.tensor([3]), torch.tensor([6]), torch.tensor([2.5], dtype=torch.float64)))
+    # one row cut over ~150 tiles (more than one group of the hierarchical carry fix-up), then a short one
+    lens = torch.tensor([3, 600000, 0, 70000, 5], dtype=torch.int64)
+    cases["long_row"] = ((len(lens), 700000), gen.matrix_from_row_lengths(len(lens), 700000, lens, 8))
     # hypersparse: far more rows than nonzeros
     r, cc, v = gen.bernoulli_matrix(20000, 50, 0.001, 9)
     cases["hypersparse"] = ((20000, 50), (r, cc, v))
@@ -85,7 +88,8 @@ def test_spmv(comet, name, layout, variant):
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("R", [1, 8, 16, 32, 64, 96])
 @pytest.mark.parametrize("name,layout", [("zipf_rows", "csr"), ("edge_lengths", "csr"), ("edge_lengths", "dcsr"),
-                                         ("empty", "csr"), ("hypersparse", "dcsr"), ("hypersparse", "csr")])
+                                         ("empty", "csr"), ("hypersparse", "dcsr"), ("hypersparse", "csr"),
+                                         ("long_row", "csr")])
 def test_spmm(comet, name, layout, R, variant):
     (I, J), (rows, cols, vals) = MATRIX_CASES[name]
     say("spmm case=%s layout=%s R=%d variant=%d nnz=%d" % (name, layout, R, variant, vals.numel()))
@@ -135,6 +139,12 @@ def _tensor_cases():
     n = 9000
     cases["single_fiber"] = ((3, 3, n), (torch.ones(n, dtype=torch.int64), torch.full((n,), 2, dtype=torch.int64),
                                          torch.arange(n, dtype=torch.int64), gen.rng.uniform_pm1(6, 3, n)))
+    # one slice / one fiber cut over far more than 64 tiles
+    i, j, k, v = gen.bernoulli_tensor3((1, 600, 1000), 0.6, 7)
+    cases["long_slice"] = ((5, 600, 1000), (i + 2, j, k, v))
+    n = 300000
+    cases["long_fiber"] = ((2, 2, n), (torch.zeros(n, dtype=torch.int64), torch.ones(n, dtype=torch.int64),
+                                       torch.arange(n, dtype=torch.int64), gen.rng.uniform_pm1(8, 3, n)))
     z = torch.zeros(0, dtype=torch.int64)
     cases["empty"] = ((4, 5, 6), (z, z, z, torch.zeros(0, dtype=torch.float64)))
     cases["single"] = ((4, 5, 6), (torch.tensor([2]), torch.tensor([4]), torch.tensor([5]),
@@ -186,7 +196,8 @@ def test_ttv(comet, name, layout, variant):
 
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("R", [1, 8, 16, 32, 64])
-@pytest.mark.parametrize("name", ["zipf_ttm", "mode_of_two", "single_slice", "single_fiber", "empty", "single"])
+@pytest.mark.parametrize("name", ["zipf_ttm", "mode_of_two", "single_slice", "single_fiber", "long_fiber", "empty",
+                                  "single"])
 def test_ttm(comet, name, R, variant):
     dims, (i, j, k, vals) = TENSOR_CASES[name]
     say("ttm case=%s R=%d variant=%d nnz=%d" % (name, R, variant, vals.numel()))
@@ -204,8 +215,8 @@ def test_ttm(comet, name, R, variant):
 
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("R", [1, 8, 16, 64])
-@pytest.mark.parametrize("name", ["zipf_mttkrp", "zipf_ttv", "mode_of_two", "single_slice", "single_fiber", "empty",
-                                  "single"])
+@pytest.mark.parametrize("name", ["zipf_mttkrp", "zipf_ttv", "mode_of_two", "single_slice", "single_fiber", "long_slice",
+                                  "long_fiber", "empty", "single"])
 def test_mttkrp(comet, name, R, variant):
     dims, (i, j, k, vals) = TENSOR_CASES[name]
     say("mttkrp case=%s R=%d variant=%d nnz=%d" % (name, R, variant, vals.numel()))
