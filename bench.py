@@ -71,7 +71,17 @@ def run_op(op, args, comet, dev):
     t_gen = time.perf_counter()
     sc = args.scale
     keep = {}
-    if op == "spmv":
+    if op == "copy":
+        # calibration only: a plain 1 GiB device-to-device copy, to scale the rocprofv3 HBM byte counters
+        n = 1 << 27
+        src = torch.ones(n, dtype=torch.float64, device=dev)
+        dst = torch.empty_like(src)
+        fn = lambda: dst.copy_(src)
+        nnz, flops, nbytes = n, 0, 16 * n
+        desc = "plain copy of %d bytes (counter calibration)" % (8 * n)
+        extra = {}
+        keep = dict(src=src, dst=dst)
+    elif op == "spmv":
         c = gen.config_spmv(seed=0, device=dev)
         rows, cols, vals = c["coo"]
         n = c["dims"][0]

@@ -373,23 +373,58 @@ __device__ __forceinline__ void quad_store_row(double *__restrict__ out, int64_t
     }
 }
 
+// This lane's share of operand row `row`: V values (see the rank layout above).
 template <int V, bool WIDE>
-__device__ __forceinline__ void quad_item(QuadState<V, WIDE> &st, int c, double a, int t, const double *__restrict__ Dn,
-                                          const int32_t *__restrict__ rowmap, double *__restrict__ out, int R, int j) {
-    const double *rowp = Dn + (int64_t)c * R;
+__device__ __forceinline__ void quad_load_row(const double *__restrict__ Dn, int64_t row, int R, int j, double *d) {
+    const double *rowp = Dn + row * R;
     if constexpr (WIDE) {
-        double2 d[V / 2];
 #pragma unroll
-        for (int q = 0; q < V / 2; ++q) d[q] = *reinterpret_cast<const double2 *>(rowp + 8 * q + 2 * j);
-#pragma unroll
-        for (int q = 0; q < V / 2; ++q) { st.acc[2 * q] = fma(a, d[q].x, st.acc[2 * q]); st.acc[2 * q + 1] = fma(a, d[q].y, st.acc[2 * q + 1]); }
+        for (int q = 0; q < V / 2; ++q) {
+            const double2 x = *reinterpret_cast<const double2 *>(rowp + 8 * q + 2 * j);
+            d[2 * q] = x.x; d[2 * q + 1] = x.y;
+        }
     } else {
-        double d[V];
 #pragma unroll
         for (int q = 0; q < V; ++q) { int r = 4 * q + j; d[q] = r < R ? rowp[r] : 0.0; }
-#pragma unroll
-        for (int q = 0; q < V; ++q) st.acc[q] = fma(a, d[q], st.acc[q]);
     }
+}
+
+// compile-time loop: f(std::integral_constant<int, B>{}), ..., f(integral_constant<int, E-1>{})
+template <int N> struct IntC { static constexpr int value = N; constexpr operator int() const { return N; } };
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (B < E) { f(IntC<B>{}); static_for<B + 1, E>(f); }
+}
+
+// Four consecutive items of one lane (16 of the quad): the streamed part of a 16-item super-block.
+struct QuadItems {
+    int    cr[4];
+    double va[4];
+};
+__device__ __forceinline__ void quad_load_items(QuadItems &it, const int32_t *__restrict__ crd,
+                                                const double *__restrict__ vals, int64_t i0, int64_t nnz) {
+    if (i0 + 3 < nnz) {
+        const int4 c4 = *reinterpret_cast<const int4 *>(crd + i0);
+        const double2 a01 = *reinterpret_cast<const double2 *>(vals + i0);
+        const double2 a23 = *reinterpret_cast<const double2 *>(vals + i0 + 2);
+        it.cr[0] = c4.x; it.cr[1] = c4.y; it.cr[2] = c4.z; it.cr[3] = c4.w;
+        it.va[0] = a01.x; it.va[1] = a01.y; it.va[2] = a23.x; it.va[3] = a23.y;
+    } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) { bool in = i0 + s < nnz; it.cr[s] = in ? crd[i0 + s] : 0; it.va[s] = in ? vals[i0 + s] : 0.0; }
+    }
+}
+
+template <int V> struct RowBuf { double d[V]; };
+
+// Steps per pipeline group: the gathers of group g+1 are in flight while group g is consumed.
+template <int V> struct QuadGroup { static constexpr int value = V <= 4 ? 4 : (V <= 8 ? 2 : 1); };
+
+template <int V, bool WIDE, bool ROWMAP>
+__device__ __forceinline__ void quad_consume(QuadState<V, WIDE> &st, double a, int t, const RowBuf<V> &b,
+                                             const int32_t *__restrict__ rowmap, double *__restrict__ out, int R, int j) {
+#pragma unroll
+    for (int q = 0; q < V; ++q) st.acc[q] = fma(a, b.d[q], st.acc[q]);
     if (t >= 0) {                                   // the item ends segment t (same for the 4 lanes of the quad)
         if (!st.ht) {
 #pragma unroll
@@ -397,14 +432,14 @@ __device__ __forceinline__ void quad_item(QuadState<V, WIDE> &st, int c, double 
             st.first_id = t;
             st.ht = 1;
         } else {
-            quad_store_row<V, WIDE>(out, rowmap ? (int64_t)rowmap[t] : (int64_t)t, R, j, st.acc);
+            quad_store_row<V, WIDE>(out, ROWMAP ? (int64_t)rowmap[t] : (int64_t)t, R, j, st.acc);
         }
 #pragma unroll
         for (int q = 0; q < V; ++q) st.acc[q] = 0.0;
     }
 }
 
-template <int V, bool WIDE>
+template <int V, bool WIDE, bool ROWMAP>
 __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
                                                       const double *__restrict__ vals,
                                                       const int32_t *__restrict__ seg_begin,
@@ -416,40 +451,51 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
     __shared__ int qht[64];
     const int64_t t = blockIdx.x;
     const int64_t tb = t * (int64_t)kTile;
-    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, R);
-
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, qw = lane >> 2, j = lane & 3;
     const int Q = w * 16 + qw;                                    // quad index inside the tile
     const int64_t qb = tb + (int64_t)Q * 64;                      // first item of this quad
+    QuadItems cur;
+    quad_load_items(cur, crd, vals, qb + 4 * j, nnz);             // in flight while the map is built
+    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, R);
+
     QuadState<V, WIDE> st;
 #pragma unroll
     for (int q = 0; q < V; ++q) { st.acc[q] = 0.0; st.first[q] = 0.0; }
     st.ht = 0; st.first_id = -1;
 
+    constexpr int G = QuadGroup<V>::value, NG = 16 / G;
     for (int sb = 0; sb < 4; ++sb) {
         const int64_t i0 = qb + 16 * sb + 4 * j;                  // this lane's four items
-        int cr[4], tl[4];
-        double va[4];
-        if (i0 + 3 < nnz) {
-            const int4 c4 = *reinterpret_cast<const int4 *>(crd + i0);
-            const double2 a01 = *reinterpret_cast<const double2 *>(vals + i0);
-            const double2 a23 = *reinterpret_cast<const double2 *>(vals + i0 + 2);
-            cr[0] = c4.x; cr[1] = c4.y; cr[2] = c4.z; cr[3] = c4.w;
-            va[0] = a01.x; va[1] = a01.y; va[2] = a23.x; va[3] = a23.y;
-        } else {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) { bool in = i0 + s < nnz; cr[s] = in ? crd[i0 + s] : 0; va[s] = in ? vals[i0 + s] : 0.0; }
-        }
+        QuadItems nxt;
+        if (sb < 3) quad_load_items(nxt, crd, vals, i0 + 16, nnz);
+        int tl[4];
         {
             const int4 t4 = *reinterpret_cast<const int4 *>(ts + (i0 - tb));
             tl[0] = t4.x; tl[1] = t4.y; tl[2] = t4.z; tl[3] = t4.w;
         }
-#define COMET_QUAD_STEPS(BP)                                                                          \
-        _Pragma("unroll") for (int s = 0; s < 4; ++s)                                                  \
-            quad_item<V, WIDE>(st, quad_bcast_i<BP>(cr[s]), quad_bcast_d<BP>(va[s]), quad_bcast_i<BP>(tl[s]), Dn,  \
-                               rowmap, out, R, j);
-        COMET_QUAD_STEPS(0) COMET_QUAD_STEPS(1) COMET_QUAD_STEPS(2) COMET_QUAD_STEPS(3)
-#undef COMET_QUAD_STEPS
+        RowBuf<V> buf[2][G];
+        auto issue = [&](auto gc, RowBuf<V> *bb) {
+            static_for<0, G>([&](auto sc) {
+                constexpr int k = decltype(gc)::value * G + decltype(sc)::value;      // step 0..15 of the super-block
+                const int c = quad_bcast_i<k / 4>(cur.cr[k % 4]);
+                quad_load_row<V, WIDE>(Dn, c, R, j, bb[decltype(sc)::value].d);
+            });
+        };
+        auto consume = [&](auto gc, const RowBuf<V> *bb) {
+            static_for<0, G>([&](auto sc) {
+                constexpr int k = decltype(gc)::value * G + decltype(sc)::value;
+                const double a = quad_bcast_d<k / 4>(cur.va[k % 4]);
+                const int tt = quad_bcast_i<k / 4>(tl[k % 4]);
+                quad_consume<V, WIDE, ROWMAP>(st, a, tt, bb[decltype(sc)::value], rowmap, out, R, j);
+            });
+        };
+        issue(IntC<0>{}, buf[0]);
+        static_for<0, NG>([&](auto gc) {
+            constexpr int g = decltype(gc)::value;
+            if constexpr (g + 1 < NG) issue(IntC<g + 1>{}, buf[(g + 1) & 1]);
+            consume(gc, buf[g & 1]);
+        });
+        if (sb < 3) cur = nxt;
     }
 
     // publish this quad's open sum, then close the first segment end of every quad
@@ -478,7 +524,7 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
 #pragma unroll
             for (int q = 0; q < V; ++q) value[q] = sum[q] + st.first[q];
             if (found) {
-                quad_store_row<V, WIDE>(out, rowmap ? (int64_t)rowmap[st.first_id] : (int64_t)st.first_id, R, j, value);
+                quad_store_row<V, WIDE>(out, ROWMAP ? (int64_t)rowmap[st.first_id] : (int64_t)st.first_id, R, j, value);
             } else {                                              // first segment end of the whole tile
                 quad_store_row<V, WIDE>(cb.first, t, R, j, value);
                 if (j == 0) cb.first_id[t] = st.first_id;
@@ -497,8 +543,12 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
 template <int V, bool WIDE>
 hipError_t launch_rankR(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                         const int32_t *rowmap, const double *Dn, int R, double *out, void *scratch, hipStream_t st) {
-    hipLaunchKernelGGL((k_stream_rankR<V, WIDE>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
-                       (const int32_t *)sc.seg_begin->ptr, rowmap, Dn, out, sc.nnz, sc.ntiles, R, scratch);
+    if (rowmap)
+        hipLaunchKernelGGL((k_stream_rankR<V, WIDE, true>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
+                           (const int32_t *)sc.seg_begin->ptr, rowmap, Dn, out, sc.nnz, sc.ntiles, R, scratch);
+    else
+        hipLaunchKernelGGL((k_stream_rankR<V, WIDE, false>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
+                           (const int32_t *)sc.seg_begin->ptr, rowmap, Dn, out, sc.nnz, sc.ntiles, R, scratch);
     return hipGetLastError();
 }
 
@@ -510,21 +560,6 @@ hipError_t launch_rankR(const Schedule &sc, const int32_t *pos, const int32_t *c
 // only the slice level needs carries.  Outer level: slices (segments of pos2); a slice end writes
 // row crd1[slice] of M.  Two LDS maps, both keyed by tile item: ts = fiber id at a fiber's last
 // nonzero, tm = output row at a slice's last nonzero (-1 elsewhere).
-template <int V, bool WIDE>
-__device__ __forceinline__ void quad_load_row(const double *__restrict__ Dn, int64_t row, int R, int j, double *d) {
-    const double *rowp = Dn + row * R;
-    if constexpr (WIDE) {
-#pragma unroll
-        for (int q = 0; q < V / 2; ++q) {
-            const double2 x = *reinterpret_cast<const double2 *>(rowp + 8 * q + 2 * j);
-            d[2 * q] = x.x; d[2 * q + 1] = x.y;
-        }
-    } else {
-#pragma unroll
-        for (int q = 0; q < V; ++q) { int r = 4 * q + j; d[q] = r < R ? rowp[r] : 0.0; }
-    }
-}
-
 template <int V, bool WIDE>
 __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict__ pos2, const int32_t *__restrict__ crd1,
                                                        const int32_t *__restrict__ pos3, const int32_t *__restrict__ crd2,

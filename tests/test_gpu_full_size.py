@@ -1,0 +1,161 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The oracle cannot evaluate 10^8-nonzero tensors element by element within the test budget, so each
+case checks (a) sampled output rows / fibers / slices -- random ones plus the heaviest one, which is
+cut over the most kernel tiles -- against the oracle run on exactly the nonzeros that feed them, and
+(b) properties that hold at any size: index outputs bit-identical to the expected structure, rows
+without stored nonzeros exactly zero.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import formats as fmt
+from synth import generate as gen
+from util import assert_values_close, np_
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+@pytest.fixture(scope="module")
+def comet():
+    from paper_2102_05187_amd import build
+    build.build_if_missing()
+    import paper_2102_05187_amd as c
+    return c
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def ranges_to_index(starts: torch.Tensor, ends: torch.Tensor):
+    """Concatenated positions of the half-open ranges, plus the range number of every position."""
+    lens = (ends - starts).to(torch.int64)
+    which = torch.repeat_interleave(torch.arange(lens.numel(), device=starts.device), lens)
+    offs = torch.cumsum(lens, 0) - lens
+    idx = starts.to(torch.int64)[which] + (torch.arange(int(lens.sum()), device=starts.device) - offs[which])
+    return idx, which
+
+
+def sample_ids(n, count, must, seed):
+    g = torch.Generator().manual_seed(seed)
+    ids = torch.randint(0, n, (count,), generator=g)
+    ids = torch.unique(torch.cat([ids, torch.as_tensor(must, dtype=torch.int64)]))
+    return ids.to(DEV)
+
+
+def test_spmm_config(comet):
+    c = gen.config_spmm(seed=0, device=DEV, R=32)
+    rows, cols, vals = c["coo"]
+    n = c["dims"][0]
+    say("spmm full size nnz=%d" % vals.numel())
+    L = fmt.pack_csr(n, n, rows, cols, vals)
+    A = comet.from_levels(L)
+    C = comet.comet_spmm(A, c["B"])
+    torch.cuda.synchronize()
+    pos = L.pos[1].to(torch.int64)
+    lens = pos[1:] - pos[:-1]
+    heavy = torch.topk(lens, 4).indices.cpu()
+    ids = sample_ids(n, 3000, heavy, 1)
+    idx, which = ranges_to_index(pos[ids], pos[ids + 1])
+    ref, absum = oracle.spmm(np_(which), np_(cols[idx]), np_(vals[idx]), (ids.numel(), n), np_(c["B"]))
+    assert_values_close(np_(C[ids]), ref, absum, "spmm sampled rows")
+
+
+@pytest.fixture(scope="module")
+def ttv_config():
+    return gen.config_ttv(seed=0, device=DEV)
+
+
+def _fiber_sample(L, count, seed):
+    pos3 = L.pos[2].to(torch.int64)
+    lens = pos3[1:] - pos3[:-1]
+    heavy = torch.topk(lens, 4).indices.cpu()
+    fids = sample_ids(lens.numel(), count, heavy, seed)
+    idx, which = ranges_to_index(pos3[fids], pos3[fids + 1])
+    return fids, idx, which
+
+
+def test_ttv_csf_config(comet, ttv_config):
+    c = ttv_config
+    i, j, k, vals = c["coo"]
+    L = fmt.pack_csf3(c["dims"], i, j, k, vals)
+    say("ttv csf full size nnz=%d fibers=%d" % (vals.numel(), L.crd[1].numel()))
+    X = comet.from_levels(L)
+    Y = comet.comet_ttv(X, 2, c["v"])
+    torch.cuda.synchronize()
+    for l in range(2):                    # structure: the result's levels are the input's, bit for bit
+        assert torch.equal(Y.pos(l), L.pos[l]) and torch.equal(Y.crd(l), L.crd[l])
+    fids, idx, which = _fiber_sample(L, 4000, 2)
+    # the sampled fibers have distinct (i,j) in increasing order, so the oracle's pair list is `fids`
+    ref = oracle.ttv(np_(i[idx]), np_(j[idx]), np_(k[idx]), np_(vals[idx]), c["dims"], np_(c["v"]))
+    assert len(ref["vals"]) == fids.numel()
+    assert_values_close(np_(Y.vals()[fids]), ref["vals"], ref["abs"], "ttv sampled fibers")
+
+
+def test_ttv_coo_config(comet, ttv_config):
+    c = ttv_config
+    i, j, k, vals = c["coo"]
+    Lc = fmt.pack_coo(c["dims"], (i, j, k), vals)
+    Ls = fmt.pack_csf3(c["dims"], i, j, k, vals)
+    say("ttv coo full size nnz=%d" % vals.numel())
+    X = comet.from_levels(Lc)
+    Y = comet.comet_ttv(X, 2, c["v"])
+    torch.cuda.synchronize()
+    # structure: the distinct (i,j) pairs in order = run heads of the sorted coordinate list
+    head = torch.ones(i.numel(), dtype=torch.bool, device=DEV)
+    head[1:] = (i[1:] != i[:-1]) | (j[1:] != j[:-1])
+    assert torch.equal(Y.crd(0), i[head].to(torch.int32)) and torch.equal(Y.crd(1), j[head].to(torch.int32))
+    assert Y.pos(0).tolist() == [0, int(head.sum())]
+    fids, idx, which = _fiber_sample(Ls, 4000, 3)
+    ref = oracle.ttv(np_(i[idx]), np_(j[idx]), np_(k[idx]), np_(vals[idx]), c["dims"], np_(c["v"]))
+    assert_values_close(np_(Y.vals()[fids]), ref["vals"], ref["abs"], "ttv coo sampled runs")
+
+
+def test_ttm_config(comet):
+    c = gen.config_ttm(seed=0, device=DEV, R=16)
+    i, j, k, vals = c["coo"]
+    L = fmt.pack_csf3(c["dims"], i, j, k, vals)
+    say("ttm full size nnz=%d fibers=%d" % (vals.numel(), L.crd[1].numel()))
+    X = comet.from_levels(L)
+    Y = comet.comet_ttm(X, 2, c["U"])
+    torch.cuda.synchronize()
+    for l in range(2):
+        assert torch.equal(Y.pos(l), L.pos[l]) and torch.equal(Y.crd(l), L.crd[l])
+    assert Y.pos(2).tolist() == [16] and Y.levels() == [1, 1, 0]
+    fids, idx, which = _fiber_sample(L, 3000, 4)
+    ref = oracle.ttm(np_(i[idx]), np_(j[idx]), np_(k[idx]), np_(vals[idx]), c["dims"], np_(c["U"]))
+    got = Y.vals().reshape(-1, 16)[fids]
+    assert_values_close(np_(got), ref["vals"], ref["abs"], "ttm sampled fibers")
+
+
+@pytest.mark.parametrize("R", [16, 64])
+def test_mttkrp_config(comet, R):
+    c = gen.config_mttkrp(seed=0, device=DEV, R=R)
+    i, j, k, vals = c["coo"]
+    dims = c["dims"]
+    L = fmt.pack_csf3(dims, i, j, k, vals)
+    say("mttkrp full size R=%d nnz=%d fibers=%d slices=%d" % (R, vals.numel(), L.crd[1].numel(), L.crd[0].numel()))
+    X = comet.from_levels(L)
+    M = torch.full((dims[0], R), float("nan"), dtype=torch.float64, device=DEV)
+    comet.comet_mttkrp(X, 0, [None, c["B"], c["C"]], M)
+    torch.cuda.synchronize()
+    pos2, pos3 = L.pos[1].to(torch.int64), L.pos[2].to(torch.int64)
+    first = pos3[pos2[:-1]]
+    last = pos3[pos2[1:]]
+    heavy = torch.topk(last - first, 2).indices.cpu()       # the Zipf head slices: cut over thousands of tiles
+    sids = sample_ids(first.numel(), 600, heavy, 5)
+    idx, which = ranges_to_index(first[sids], last[sids])
+    say("  oracle on %d nonzeros of %d sampled slices" % (idx.numel(), sids.numel()))
+    ref, absum = oracle.mttkrp(np_(which), np_(j[idx]), np_(k[idx]), np_(vals[idx]), (sids.numel(), dims[1], dims[2]),
+                               np_(c["B"]), np_(c["C"]))
+    rows = L.crd[0].to(torch.int64)[sids]
+    assert_values_close(np_(M[rows]), ref, absum, "mttkrp sampled slices R=%d" % R)
+    # rows whose index is not stored at the root level receive nothing
+    stored = torch.zeros(dims[0], dtype=torch.bool, device=DEV)
+    stored[L.crd[0].to(torch.int64)] = True
+    assert bool((M[~stored] == 0.0).all())
+    assert not bool(torch.isnan(M).any())
