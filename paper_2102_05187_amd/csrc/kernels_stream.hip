@@ -17,6 +17,8 @@
 // units is final once the left unit contains a segment end.  Tile summaries go to a carry buffer
 // and a second small kernel finishes the segments cut by tile boundaries in a fixed order, so the
 // results do not depend on scheduling (no atomics).
+#include <cstdlib>
+
 #include "stream_kernels.hpp"
 
 namespace comet {
@@ -336,72 +338,70 @@ __global__ void __launch_bounds__(256) k_stream_fixup(void *scratch, int64_t nti
 }
 
 
-// ---- rank-R walk: a quad (4 lanes) walks 64 consecutive items; lanes hold V = R/4 ranks each ------
-// Quad q of wavefront w owns items [tb + 1024 w + 64 q, +64).  Every 16 items each lane loads four
-// consecutive (crd, val, tail id) triples with 16-byte loads; the quad then takes the items one at
-// a time, fetching the current item's triple from the lane that holds it with a quad_perm DPP
-// broadcast.  For one item the quad reads the operand row Dn[crd, :] as contiguous 16-byte pieces
-// (WIDE, R a multiple of 8: lane j takes ranks 8q+2j, 8q+2j+1) or 8-byte pieces (lane j takes ranks
-// 4q+j), so each gathered row is one contiguous run of bytes across the quad.
-template <int BP>
-__device__ __forceinline__ int quad_bcast_i(int v) {
-    return __builtin_amdgcn_update_dpp(0, v, BP * 0x55, 0xf, 0xf, false);
+// ---- rank-R walk: a group of L lanes (4 or 8) walks a run of consecutive items --------------------
+// The 256 threads of a tile form 256/L lane groups ("walkers"); walker g owns the 16*L consecutive
+// items [tb + 16*L*g, +16*L).  Every 4*L items each lane loads four consecutive (crd, val, tail id)
+// triples with 16-byte loads; the group then takes the items one at a time, fetching the current
+// item's triple from the lane that holds it with DPP broadcasts (quad_perm inside a quad, plus one
+// row_shr:4 / row_shl:4 with a bank mask to cross the two quads of an 8-lane group).  For one item
+// the group reads the operand row Dn[crd, :] as contiguous 16-byte pieces (WIDE, R a multiple of
+// 2L: lane j takes ranks 2L*q+2j, 2L*q+2j+1) or 8-byte pieces (lane j takes ranks L*q+j), so a load
+// instruction touches each gathered row as one contiguous run of 16*L bytes: with L = 8 that is a
+// whole 128-byte cache line per instruction, which halves the number of L1 accesses per nonzero
+// against L = 4 (the texture-address / L1 tag path is what bounds these kernels).
+template <int L, int BP>
+__device__ __forceinline__ int grp_bcast_i(int v) {
+    static_assert(L == 4 || L == 8, "lane groups of 4 or 8");
+    const int x1 = __builtin_amdgcn_update_dpp(0, v, (BP % 4) * 0x55, 0xf, 0xf, false);     // quad_perm broadcast
+    if constexpr (L == 4) return x1;
+    else if constexpr (BP < 4) return __builtin_amdgcn_update_dpp(x1, x1, 0x114, 0xf, 0xa, false);   // row_shr:4 into the odd quads
+    else return __builtin_amdgcn_update_dpp(x1, x1, 0x104, 0xf, 0x5, false);                          // row_shl:4 into the even quads
 }
-template <int BP>
-__device__ __forceinline__ double quad_bcast_d(double v) {
-    int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), BP * 0x55, 0xf, 0xf, false);
-    int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), BP * 0x55, 0xf, 0xf, false);
-    return __hiloint2double(hi, lo);
-}
-
-template <int V, bool WIDE>
-struct QuadState {
-    double acc[V];
-    double first[V];
-    int ht, first_id;
-};
-
-template <int V, bool WIDE>
-__device__ __forceinline__ void quad_store_row(double *__restrict__ out, int64_t row, int R, int j, const double *v) {
-    double *p = out + row * R;
-    if constexpr (WIDE) {
-#pragma unroll
-        for (int q = 0; q < V / 2; ++q) *reinterpret_cast<double2 *>(p + 8 * q + 2 * j) = make_double2(v[2 * q], v[2 * q + 1]);
-    } else {
-#pragma unroll
-        for (int q = 0; q < V; ++q) { int r = 4 * q + j; if (r < R) p[r] = v[q]; }
-    }
+template <int L, int BP>
+__device__ __forceinline__ double grp_bcast_d(double v) {
+    return __hiloint2double(grp_bcast_i<L, BP>(__double2hiint(v)), grp_bcast_i<L, BP>(__double2loint(v)));
 }
 
-// This lane's share of operand row `row`: V values (see the rank layout above).
-template <int V, bool WIDE>
-__device__ __forceinline__ void quad_load_row(const double *__restrict__ Dn, int64_t row, int R, int j, double *d) {
+// This lane's share of a dense row: V values.
+template <int L, int V, bool WIDE>
+__device__ __forceinline__ void grp_load_row(const double *__restrict__ Dn, int64_t row, int R, int j, double *d) {
     const double *rowp = Dn + row * R;
     if constexpr (WIDE) {
 #pragma unroll
         for (int q = 0; q < V / 2; ++q) {
-            const double2 x = *reinterpret_cast<const double2 *>(rowp + 8 * q + 2 * j);
+            const double2 x = *reinterpret_cast<const double2 *>(rowp + 2 * L * q + 2 * j);
             d[2 * q] = x.x; d[2 * q + 1] = x.y;
         }
     } else {
 #pragma unroll
-        for (int q = 0; q < V; ++q) { int r = 4 * q + j; d[q] = r < R ? rowp[r] : 0.0; }
+        for (int q = 0; q < V; ++q) { int r = L * q + j; d[q] = r < R ? rowp[r] : 0.0; }
+    }
+}
+template <int L, int V, bool WIDE>
+__device__ __forceinline__ void grp_store_row(double *__restrict__ out, int64_t row, int R, int j, const double *v) {
+    double *p = out + row * R;
+    if constexpr (WIDE) {
+#pragma unroll
+        for (int q = 0; q < V / 2; ++q) *reinterpret_cast<double2 *>(p + 2 * L * q + 2 * j) = make_double2(v[2 * q], v[2 * q + 1]);
+    } else {
+#pragma unroll
+        for (int q = 0; q < V; ++q) { int r = L * q + j; if (r < R) p[r] = v[q]; }
     }
 }
 
-// compile-time loop: f(std::integral_constant<int, B>{}), ..., f(integral_constant<int, E-1>{})
-template <int N> struct IntC { static constexpr int value = N; constexpr operator int() const { return N; } };
+// compile-time loop: f(IntC<B>{}), ..., f(IntC<E-1>{})
+template <int N> struct IntC { static constexpr int value = N; };
 template <int B, int E, class F>
 __device__ __forceinline__ void static_for(F &&f) {
     if constexpr (B < E) { f(IntC<B>{}); static_for<B + 1, E>(f); }
 }
 
-// Four consecutive items of one lane (16 of the quad): the streamed part of a 16-item super-block.
-struct QuadItems {
+// Four consecutive items of one lane: the streamed part of a 4*L-item super-block.
+struct LaneItems {
     int    cr[4];
     double va[4];
 };
-__device__ __forceinline__ void quad_load_items(QuadItems &it, const int32_t *__restrict__ crd,
+__device__ __forceinline__ void lane_load_items(LaneItems &it, const int32_t *__restrict__ crd,
                                                 const double *__restrict__ vals, int64_t i0, int64_t nnz) {
     if (i0 + 3 < nnz) {
         const int4 c4 = *reinterpret_cast<const int4 *>(crd + i0);
@@ -418,56 +418,107 @@ __device__ __forceinline__ void quad_load_items(QuadItems &it, const int32_t *__
 template <int V> struct RowBuf { double d[V]; };
 
 // Steps per pipeline group: the gathers of group g+1 are in flight while group g is consumed.
-template <int V> struct QuadGroup { static constexpr int value = V <= 4 ? 4 : (V <= 8 ? 2 : 1); };
+template <int V> struct StepGroup { static constexpr int value = V <= 4 ? 4 : (V <= 8 ? 2 : 1); };
 
-template <int V, bool WIDE, bool ROWMAP>
-__device__ __forceinline__ void quad_consume(QuadState<V, WIDE> &st, double a, int t, const RowBuf<V> &b,
-                                             const int32_t *__restrict__ rowmap, double *__restrict__ out, int R, int j) {
+template <int V>
+struct WalkState {
+    double acc[V];
+    double first[V];
+    int ht, first_id;
+};
+
+template <int L, int V, bool WIDE, bool ROWMAP>
+__device__ __forceinline__ void grp_consume(WalkState<V> &st, double a, int t, const RowBuf<V> &b,
+                                            const int32_t *__restrict__ rowmap, double *__restrict__ out, int R, int j) {
 #pragma unroll
     for (int q = 0; q < V; ++q) st.acc[q] = fma(a, b.d[q], st.acc[q]);
-    if (t >= 0) {                                   // the item ends segment t (same for the 4 lanes of the quad)
+    if (t >= 0) {                                   // the item ends segment t (same for every lane of the group)
         if (!st.ht) {
 #pragma unroll
             for (int q = 0; q < V; ++q) st.first[q] = st.acc[q];
             st.first_id = t;
             st.ht = 1;
         } else {
-            quad_store_row<V, WIDE>(out, ROWMAP ? (int64_t)rowmap[t] : (int64_t)t, R, j, st.acc);
+            grp_store_row<L, V, WIDE>(out, ROWMAP ? (int64_t)rowmap[t] : (int64_t)t, R, j, st.acc);
         }
 #pragma unroll
         for (int q = 0; q < V; ++q) st.acc[q] = 0.0;
     }
 }
 
-template <int V, bool WIDE, bool ROWMAP>
+// Close the first segment end of every walker of the tile and publish the tile summary.
+// wopen[(g*L + j)*V + q] holds walker g's open sum, wht[g] its has_tail flag (both already written
+// and separated from this call by a barrier).  `first_row` is the output row of the walker's first
+// segment end; `open` its trailing sum.
+template <int L, int V, bool WIDE>
+__device__ __forceinline__ void finish_tile_walkers(const double *wopen, const int *wht, int g, int j, int ht,
+                                                    const double *first, int64_t first_row, int32_t first_id,
+                                                    const double *open, double *__restrict__ out, int R,
+                                                    CarryView cb, int64_t t) {
+    constexpr int NW = 256 / L;
+    const bool last = g == NW - 1;
+    if (!(ht || last)) return;
+    double sum[V];
+#pragma unroll
+    for (int q = 0; q < V; ++q) sum[q] = 0.0;
+    int found = 0;
+    for (int g2 = g - 1; g2 >= 0; --g2) {
+        const double *wo = wopen + (g2 * L + j) * V;
+#pragma unroll
+        for (int q = 0; q < V; ++q) sum[q] += wo[q];
+        if (wht[g2]) { found = 1; break; }
+    }
+    if (ht) {
+        double value[V];
+#pragma unroll
+        for (int q = 0; q < V; ++q) value[q] = sum[q] + first[q];
+        if (found) {
+            grp_store_row<L, V, WIDE>(out, first_row, R, j, value);
+        } else {                                              // first segment end of the whole tile
+            grp_store_row<L, V, WIDE>(cb.first, t, R, j, value);
+            if (j == 0) cb.first_id[t] = first_id;
+        }
+    }
+    if (last) {
+        double topen[V];
+#pragma unroll
+        for (int q = 0; q < V; ++q) topen[q] = ht ? open[q] : open[q] + sum[q];
+        grp_store_row<L, V, WIDE>(cb.open, t, R, j, topen);
+        if (j == 0) cb.has_tail[t] = ht | found;
+    }
+}
+
+template <int L, int V, bool WIDE, bool ROWMAP>
 __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
                                                       const double *__restrict__ vals,
                                                       const int32_t *__restrict__ seg_begin,
                                                       const int32_t *__restrict__ rowmap, const double *__restrict__ Dn,
                                                       double *__restrict__ out, int64_t nnz, int64_t ntiles, int R,
                                                       void *scratch) {
+    constexpr int NW = 256 / L;                // walkers per tile
+    constexpr int WI = kTile / NW;             // items per walker
+    constexpr int SB = 4 * L;                  // items per super-block (4 per lane)
     __shared__ __attribute__((aligned(16))) int32_t ts[kTile];
-    __shared__ __attribute__((aligned(16))) double qopen[64 * 4 * V];    // [quad][lane j][V]
-    __shared__ int qht[64];
+    __shared__ __attribute__((aligned(16))) double wopen[256 * V];       // [walker][lane j][V]
+    __shared__ int wht[NW];
     const int64_t t = blockIdx.x;
     const int64_t tb = t * (int64_t)kTile;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, qw = lane >> 2, j = lane & 3;
-    const int Q = w * 16 + qw;                                    // quad index inside the tile
-    const int64_t qb = tb + (int64_t)Q * 64;                      // first item of this quad
-    QuadItems cur;
-    quad_load_items(cur, crd, vals, qb + 4 * j, nnz);             // in flight while the map is built
+    const int g = threadIdx.x / L, j = threadIdx.x % L;
+    const int64_t gb = tb + (int64_t)g * WI;                      // first item of this walker
+    LaneItems cur;
+    lane_load_items(cur, crd, vals, gb + 4 * j, nnz);             // in flight while the map is built
     build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, R);
 
-    QuadState<V, WIDE> st;
+    WalkState<V> st;
 #pragma unroll
     for (int q = 0; q < V; ++q) { st.acc[q] = 0.0; st.first[q] = 0.0; }
     st.ht = 0; st.first_id = -1;
 
-    constexpr int G = QuadGroup<V>::value, NG = 16 / G;
-    for (int sb = 0; sb < 4; ++sb) {
-        const int64_t i0 = qb + 16 * sb + 4 * j;                  // this lane's four items
-        QuadItems nxt;
-        if (sb < 3) quad_load_items(nxt, crd, vals, i0 + 16, nnz);
+    constexpr int G = StepGroup<V>::value, NG = SB / G;
+    for (int sb = 0; sb < WI / SB; ++sb) {
+        const int64_t i0 = gb + SB * sb + 4 * j;                  // this lane's four items
+        LaneItems nxt;
+        if (sb + 1 < WI / SB) lane_load_items(nxt, crd, vals, i0 + SB, nnz);
         int tl[4];
         {
             const int4 t4 = *reinterpret_cast<const int4 *>(ts + (i0 - tb));
@@ -476,91 +527,60 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
         RowBuf<V> buf[2][G];
         auto issue = [&](auto gc, RowBuf<V> *bb) {
             static_for<0, G>([&](auto sc) {
-                constexpr int k = decltype(gc)::value * G + decltype(sc)::value;      // step 0..15 of the super-block
-                const int c = quad_bcast_i<k / 4>(cur.cr[k % 4]);
-                quad_load_row<V, WIDE>(Dn, c, R, j, bb[decltype(sc)::value].d);
+                constexpr int k = decltype(gc)::value * G + decltype(sc)::value;      // step inside the super-block
+                const int c = grp_bcast_i<L, k / 4>(cur.cr[k % 4]);
+                grp_load_row<L, V, WIDE>(Dn, c, R, j, bb[decltype(sc)::value].d);
             });
         };
         auto consume = [&](auto gc, const RowBuf<V> *bb) {
             static_for<0, G>([&](auto sc) {
                 constexpr int k = decltype(gc)::value * G + decltype(sc)::value;
-                const double a = quad_bcast_d<k / 4>(cur.va[k % 4]);
-                const int tt = quad_bcast_i<k / 4>(tl[k % 4]);
-                quad_consume<V, WIDE, ROWMAP>(st, a, tt, bb[decltype(sc)::value], rowmap, out, R, j);
+                const double a = grp_bcast_d<L, k / 4>(cur.va[k % 4]);
+                const int tt = grp_bcast_i<L, k / 4>(tl[k % 4]);
+                grp_consume<L, V, WIDE, ROWMAP>(st, a, tt, bb[decltype(sc)::value], rowmap, out, R, j);
             });
         };
         issue(IntC<0>{}, buf[0]);
         static_for<0, NG>([&](auto gc) {
-            constexpr int g = decltype(gc)::value;
-            if constexpr (g + 1 < NG) issue(IntC<g + 1>{}, buf[(g + 1) & 1]);
-            consume(gc, buf[g & 1]);
+            constexpr int gi = decltype(gc)::value;
+            if constexpr (gi + 1 < NG) issue(IntC<gi + 1>{}, buf[(gi + 1) & 1]);
+            consume(gc, buf[gi & 1]);
         });
-        if (sb < 3) cur = nxt;
+        if (sb + 1 < WI / SB) cur = nxt;
     }
 
-    // publish this quad's open sum, then close the first segment end of every quad
     {
-        double *qo = qopen + (Q * 4 + j) * V;
+        double *wo = wopen + (g * L + j) * V;
 #pragma unroll
-        for (int q = 0; q < V; ++q) qo[q] = st.acc[q];
-        if (j == 0) qht[Q] = st.ht;
+        for (int q = 0; q < V; ++q) wo[q] = st.acc[q];
+        if (j == 0) wht[g] = st.ht;
     }
     __syncthreads();
-    const bool last = Q == 63;
-    if (st.ht || last) {
-        double sum[V];
-#pragma unroll
-        for (int q = 0; q < V; ++q) sum[q] = 0.0;
-        int found = 0;
-        for (int q2 = Q - 1; q2 >= 0; --q2) {
-            const double *qo = qopen + (q2 * 4 + j) * V;
-#pragma unroll
-            for (int q = 0; q < V; ++q) sum[q] += qo[q];
-            if (qht[q2]) { found = 1; break; }
-        }
-        CarryView cb = carry_view(scratch, ntiles, R);
-        if (st.ht) {
-            double value[V];
-#pragma unroll
-            for (int q = 0; q < V; ++q) value[q] = sum[q] + st.first[q];
-            if (found) {
-                quad_store_row<V, WIDE>(out, ROWMAP ? (int64_t)rowmap[st.first_id] : (int64_t)st.first_id, R, j, value);
-            } else {                                              // first segment end of the whole tile
-                quad_store_row<V, WIDE>(cb.first, t, R, j, value);
-                if (j == 0) cb.first_id[t] = st.first_id;
-            }
-        }
-        if (last) {
-            double topen[V];
-#pragma unroll
-            for (int q = 0; q < V; ++q) topen[q] = st.ht ? st.acc[q] : st.acc[q] + sum[q];
-            quad_store_row<V, WIDE>(cb.open, t, R, j, topen);
-            if (j == 0) cb.has_tail[t] = st.ht | found;
-        }
-    }
+    const int64_t first_row = st.ht ? (ROWMAP ? (int64_t)rowmap[st.first_id] : (int64_t)st.first_id) : 0;
+    finish_tile_walkers<L, V, WIDE>(wopen, wht, g, j, st.ht, st.first, first_row, st.first_id, st.acc, out, R,
+                                    carry_view(scratch, ntiles, R), t);
 }
 
-template <int V, bool WIDE>
+template <int L, int V, bool WIDE>
 hipError_t launch_rankR(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                         const int32_t *rowmap, const double *Dn, int R, double *out, void *scratch, hipStream_t st) {
     if (rowmap)
-        hipLaunchKernelGGL((k_stream_rankR<V, WIDE, true>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
+        hipLaunchKernelGGL((k_stream_rankR<L, V, WIDE, true>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
                            (const int32_t *)sc.seg_begin->ptr, rowmap, Dn, out, sc.nnz, sc.ntiles, R, scratch);
     else
-        hipLaunchKernelGGL((k_stream_rankR<V, WIDE, false>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
+        hipLaunchKernelGGL((k_stream_rankR<L, V, WIDE, false>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
                            (const int32_t *)sc.seg_begin->ptr, rowmap, Dn, out, sc.nnz, sc.ntiles, R, scratch);
     return hipGetLastError();
 }
 
-
-// ---- MTTKRP: the same quad walk, two nested segment levels ----------------------------------------
+// ---- MTTKRP: the same walk, two nested segment levels ---------------------------------------------
 // Inner level: fibers (segments of pos3); the per-fiber sum of vals * C[crd3, :] is scaled by the row
 // B[crd2[fiber], :] when the fiber ends and folded into the slice accumulator.  Scaling is linear,
-// so a fiber cut by a quad or tile boundary is folded piecewise (each piece times the same B row);
+// so a fiber cut by a walker or tile boundary is folded piecewise (each piece times the same B row);
 // only the slice level needs carries.  Outer level: slices (segments of pos2); a slice end writes
 // row crd1[slice] of M.  Two LDS maps, both keyed by tile item: ts = fiber id at a fiber's last
 // nonzero, tm = output row at a slice's last nonzero (-1 elsewhere).
-template <int V, bool WIDE>
+template <int L, int V, bool WIDE>
 __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict__ pos2, const int32_t *__restrict__ crd1,
                                                        const int32_t *__restrict__ pos3, const int32_t *__restrict__ crd2,
                                                        const int32_t *__restrict__ crd3, const double *__restrict__ vals,
@@ -569,17 +589,23 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
                                                        const double *__restrict__ Bm, const double *__restrict__ Cm,
                                                        double *__restrict__ M, int64_t nnz, int64_t nfib, int64_t ntiles,
                                                        int R, void *scratch) {
+    constexpr int NW = 256 / L, WI = kTile / NW, SB = 4 * L;
     constexpr int kMapInts = 2 * kTile;
-    constexpr int kOpenInts = 64 * 4 * V * 2;
+    constexpr int kOpenInts = 256 * V * 2;
     constexpr int kLdsInts = kMapInts > kOpenInts ? kMapInts : kOpenInts;
     __shared__ __attribute__((aligned(16))) int32_t lds[kLdsInts];
-    __shared__ int qht[64], qfirst_fid[64];
+    __shared__ int wht[NW], wfirst_fid[NW];
     int32_t *ts = lds, *tm = lds + kTile;
-    double *qopen = reinterpret_cast<double *>(lds);              // reused once the maps are dead
+    double *wopen = reinterpret_cast<double *>(lds);              // reused once the maps are dead
     const int64_t t = blockIdx.x;
     const int64_t tb = t * (int64_t)kTile, te = tb + kTile;
+    const int g = threadIdx.x / L, j = threadIdx.x % L;
+    const int64_t gb = tb + (int64_t)g * WI;
+    LaneItems cur;
+    lane_load_items(cur, crd3, vals, gb + 4 * j, nnz);            // in flight while the maps are built
 
-    for (int i = threadIdx.x; i < 2 * kTile; i += blockDim.x) lds[i] = -1;
+    for (int i = threadIdx.x * 4; i < 2 * kTile; i += blockDim.x * 4)
+        *reinterpret_cast<int4 *>(lds + i) = make_int4(-1, -1, -1, -1);
     __syncthreads();
     for (int32_t f = seg_begin[t] + threadIdx.x; f < seg_begin[t + 1]; f += blockDim.x) {
         int32_t b = pos3[f], e = pos3[f + 1];
@@ -596,28 +622,17 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
     }
     __syncthreads();
 
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, qw = lane >> 2, j = lane & 3;
-    const int Q = w * 16 + qw;
-    const int64_t qb = tb + (int64_t)Q * 64;
     double facc[V], sacc[V], first[V];
 #pragma unroll
     for (int q = 0; q < V; ++q) { facc[q] = 0.0; sacc[q] = 0.0; first[q] = 0.0; }
     int ht = 0, first_row = -1, first_fid = -1, last_is_tail = 1;
 
-    for (int sb = 0; sb < 4; ++sb) {
-        const int64_t i0 = qb + 16 * sb + 4 * j;
-        int cr[4], tl[4], tr[4], jb[4];
-        double va[4];
-        if (i0 + 3 < nnz) {
-            const int4 c4 = *reinterpret_cast<const int4 *>(crd3 + i0);
-            const double2 a01 = *reinterpret_cast<const double2 *>(vals + i0);
-            const double2 a23 = *reinterpret_cast<const double2 *>(vals + i0 + 2);
-            cr[0] = c4.x; cr[1] = c4.y; cr[2] = c4.z; cr[3] = c4.w;
-            va[0] = a01.x; va[1] = a01.y; va[2] = a23.x; va[3] = a23.y;
-        } else {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) { bool in = i0 + s < nnz; cr[s] = in ? crd3[i0 + s] : 0; va[s] = in ? vals[i0 + s] : 0.0; }
-        }
+    constexpr int G = StepGroup<V>::value, NG = SB / G;
+    for (int sb = 0; sb < WI / SB; ++sb) {
+        const int64_t i0 = gb + SB * sb + 4 * j;
+        LaneItems nxt;
+        if (sb + 1 < WI / SB) lane_load_items(nxt, crd3, vals, i0 + SB, nnz);
+        int tl[4], tr[4], jb[4];
         {
             const int4 t4 = *reinterpret_cast<const int4 *>(ts + (i0 - tb));
             const int4 m4 = *reinterpret_cast<const int4 *>(tm + (i0 - tb));
@@ -626,103 +641,92 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
         }
 #pragma unroll
         for (int s = 0; s < 4; ++s) jb[s] = tl[s] >= 0 ? crd2[tl[s]] : 0;      // B row of a fiber that ends here
-        const bool any_item = qb + 16 * sb < nnz;
-#define COMET_MTTKRP_STEPS(BP)                                                                        \
-        _Pragma("unroll") for (int s = 0; s < 4; ++s) {                                                \
-            const int c = quad_bcast_i<BP>(cr[s]);                                                     \
-            const double a = quad_bcast_d<BP>(va[s]);                                                  \
-            const int tf = quad_bcast_i<BP>(tl[s]);                                                    \
-            const int tmr = quad_bcast_i<BP>(tr[s]);                                                   \
-            const int jrow = quad_bcast_i<BP>(jb[s]);                                                  \
-            double d[V];                                                                               \
-            quad_load_row<V, WIDE>(Cm, c, R, j, d);                                                    \
-            _Pragma("unroll") for (int q = 0; q < V; ++q) facc[q] = fma(a, d[q], facc[q]);             \
-            if (any_item) last_is_tail = tf >= 0;                                                      \
-            if (tf >= 0) {                                                                             \
-                if (first_fid < 0) first_fid = tf;                                                     \
-                double bw[V];                                                                          \
-                quad_load_row<V, WIDE>(Bm, jrow, R, j, bw);                                            \
-                _Pragma("unroll") for (int q = 0; q < V; ++q) { sacc[q] = fma(bw[q], facc[q], sacc[q]); facc[q] = 0.0; } \
-                if (tmr >= 0) {                                                                        \
-                    if (!ht) {                                                                         \
-                        _Pragma("unroll") for (int q = 0; q < V; ++q) first[q] = sacc[q];              \
-                        first_row = tmr; ht = 1;                                                       \
-                    } else {                                                                           \
-                        quad_store_row<V, WIDE>(M, tmr, R, j, sacc);                                   \
-                    }                                                                                  \
-                    _Pragma("unroll") for (int q = 0; q < V; ++q) sacc[q] = 0.0;                       \
-                }                                                                                      \
-            }                                                                                          \
-        }
-        COMET_MTTKRP_STEPS(0) COMET_MTTKRP_STEPS(1) COMET_MTTKRP_STEPS(2) COMET_MTTKRP_STEPS(3)
-#undef COMET_MTTKRP_STEPS
+        const bool any_item = gb + SB * sb < nnz;
+        RowBuf<V> cbuf[2][G], bbuf[2][G];
+        auto issue = [&](auto gc, RowBuf<V> *cb_, RowBuf<V> *bb_) {
+            static_for<0, G>([&](auto sc) {
+                constexpr int k = decltype(gc)::value * G + decltype(sc)::value;
+                constexpr int s_ = decltype(sc)::value;
+                const int c = grp_bcast_i<L, k / 4>(cur.cr[k % 4]);
+                grp_load_row<L, V, WIDE>(Cm, c, R, j, cb_[s_].d);
+                const int tf = grp_bcast_i<L, k / 4>(tl[k % 4]);
+                if (tf >= 0) {                                    // the fiber ends here: its B row is needed too
+                    const int jrow = grp_bcast_i<L, k / 4>(jb[k % 4]);
+                    grp_load_row<L, V, WIDE>(Bm, jrow, R, j, bb_[s_].d);
+                }
+            });
+        };
+        auto consume = [&](auto gc, const RowBuf<V> *cb_, const RowBuf<V> *bb_) {
+            static_for<0, G>([&](auto sc) {
+                constexpr int k = decltype(gc)::value * G + decltype(sc)::value;
+                constexpr int s_ = decltype(sc)::value;
+                const double a = grp_bcast_d<L, k / 4>(cur.va[k % 4]);
+                const int tf = grp_bcast_i<L, k / 4>(tl[k % 4]);
+                const int tmr = grp_bcast_i<L, k / 4>(tr[k % 4]);
+#pragma unroll
+                for (int q = 0; q < V; ++q) facc[q] = fma(a, cb_[s_].d[q], facc[q]);
+                if (any_item) last_is_tail = tf >= 0;
+                if (tf >= 0) {
+                    if (first_fid < 0) first_fid = tf;
+#pragma unroll
+                    for (int q = 0; q < V; ++q) { sacc[q] = fma(bb_[s_].d[q], facc[q], sacc[q]); facc[q] = 0.0; }
+                    if (tmr >= 0) {
+                        if (!ht) {
+#pragma unroll
+                            for (int q = 0; q < V; ++q) first[q] = sacc[q];
+                            first_row = tmr; ht = 1;
+                        } else {
+                            grp_store_row<L, V, WIDE>(M, tmr, R, j, sacc);
+                        }
+#pragma unroll
+                        for (int q = 0; q < V; ++q) sacc[q] = 0.0;
+                    }
+                }
+            });
+        };
+        issue(IntC<0>{}, cbuf[0], bbuf[0]);
+        static_for<0, NG>([&](auto gc) {
+            constexpr int gi = decltype(gc)::value;
+            if constexpr (gi + 1 < NG) issue(IntC<gi + 1>{}, cbuf[(gi + 1) & 1], bbuf[(gi + 1) & 1]);
+            consume(gc, cbuf[gi & 1], bbuf[gi & 1]);
+        });
+        if (sb + 1 < WI / SB) cur = nxt;
     }
 
-    // A fiber left open at the end of this quad's range ends at the next fiber end of the tile, or,
+    // A fiber left open at the end of this walker's range ends at the next fiber end of the tile, or,
     // if there is none, it is the fiber that contains the first nonzero of the next tile.
-    if (j == 0) qfirst_fid[Q] = first_fid;
+    if (j == 0) wfirst_fid[g] = first_fid;
     __syncthreads();                                              // also: every walk is done, the maps are dead
     if (!last_is_tail) {
         int64_t fid = seg_begin[t + 1];
-        for (int q2 = Q + 1; q2 < 64; ++q2) { int f2 = qfirst_fid[q2]; if (f2 >= 0) { fid = f2; break; } }
+        for (int g2 = g + 1; g2 < NW; ++g2) { int f2 = wfirst_fid[g2]; if (f2 >= 0) { fid = f2; break; } }
         if (fid < nfib) {
             double bw[V];
-            quad_load_row<V, WIDE>(Bm, crd2[fid], R, j, bw);
+            grp_load_row<L, V, WIDE>(Bm, crd2[fid], R, j, bw);
 #pragma unroll
             for (int q = 0; q < V; ++q) sacc[q] = fma(bw[q], facc[q], sacc[q]);
         }
     }
     {
-        double *qo = qopen + (Q * 4 + j) * V;
+        double *wo = wopen + (g * L + j) * V;
 #pragma unroll
-        for (int q = 0; q < V; ++q) qo[q] = sacc[q];
-        if (j == 0) qht[Q] = ht;
+        for (int q = 0; q < V; ++q) wo[q] = sacc[q];
+        if (j == 0) wht[g] = ht;
     }
     __syncthreads();
-    const bool last = Q == 63;
-    if (ht || last) {
-        double sum[V];
-#pragma unroll
-        for (int q = 0; q < V; ++q) sum[q] = 0.0;
-        int found = 0;
-        for (int q2 = Q - 1; q2 >= 0; --q2) {
-            const double *qo = qopen + (q2 * 4 + j) * V;
-#pragma unroll
-            for (int q = 0; q < V; ++q) sum[q] += qo[q];
-            if (qht[q2]) { found = 1; break; }
-        }
-        CarryView cb = carry_view(scratch, ntiles, R);
-        if (ht) {
-            double value[V];
-#pragma unroll
-            for (int q = 0; q < V; ++q) value[q] = sum[q] + first[q];
-            if (found) {
-                quad_store_row<V, WIDE>(M, first_row, R, j, value);
-            } else {
-                quad_store_row<V, WIDE>(cb.first, t, R, j, value);
-                if (j == 0) cb.first_id[t] = first_row;
-            }
-        }
-        if (last) {
-            double topen[V];
-#pragma unroll
-            for (int q = 0; q < V; ++q) topen[q] = ht ? sacc[q] : sacc[q] + sum[q];
-            quad_store_row<V, WIDE>(cb.open, t, R, j, topen);
-            if (j == 0) cb.has_tail[t] = ht | found;
-        }
-    }
+    finish_tile_walkers<L, V, WIDE>(wopen, wht, g, j, ht, first, first_row, first_row, sacc, M, R,
+                                    carry_view(scratch, ntiles, R), t);
 }
 
-template <int V, bool WIDE>
+template <int L, int V, bool WIDE>
 hipError_t launch_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t *crd1, const int32_t *pos3,
                          const int32_t *crd2, const int32_t *crd3, const double *vals, const double *B, const double *C,
                          int R, double *M, void *scratch, hipStream_t st) {
-    hipLaunchKernelGGL((k_stream_mttkrp<V, WIDE>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos2, crd1, pos3, crd2,
+    hipLaunchKernelGGL((k_stream_mttkrp<L, V, WIDE>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos2, crd1, pos3, crd2,
                        crd3, vals, (const int32_t *)sc.seg_begin->ptr, (const int32_t *)sc.slice_begin->ptr, B, C, M,
                        sc.nnz, sc.nseg, sc.ntiles, R, scratch);
     return hipGetLastError();
 }
-
 
 // One pass of the hierarchical fix-up: thread (g, r) folds the kFixGroup summaries of group g in
 // order.  A segment end whose carry chain starts inside the group is final and is written to out;
@@ -791,8 +795,17 @@ hipError_t run_fixup(void *scratch, int64_t ntiles, int R, const int32_t *rowmap
 
 }  // namespace
 
-bool stream_supports_rank(int64_t R) { return R >= 1 && R <= 64; }
-bool stream_mttkrp_supports_rank(int64_t R) { return R >= 1 && R <= 64; }
+// Lane-group width of the rank-R kernels: 8 by default; COMET_LANES=4 selects the quad mapping
+// (for measurements).  Ranks up to 8 always use quads.
+static int lanes_per_item(int64_t R) {
+    static int forced = [] { const char *e = getenv("COMET_LANES"); return e ? atoi(e) : 0; }();
+    if (R <= 8) return 4;
+    if (forced == 4 && R <= 64) return 4;
+    return 8;
+}
+
+bool stream_supports_rank(int64_t R) { return R >= 1 && R <= 128; }
+bool stream_mttkrp_supports_rank(int64_t R) { return R >= 1 && R <= 128; }
 bool stream_supports_coo() { return true; }
 
 size_t stream_scratch_bytes(int64_t ntiles, int64_t R) {
@@ -805,6 +818,33 @@ size_t stream_scratch_bytes(int64_t ntiles, int64_t R) {
     }
     return total + 256;
 }
+
+// Calls F<L, V, WIDE>(args...) for the specialisation that covers rank R.
+#define COMET_DISPATCH_RANK(F, R, ...)                                                     \
+    [&]() -> hipError_t {                                                                  \
+        const int r_ = (int)(R);                                                           \
+        if (lanes_per_item(r_) == 4) {                                                     \
+            if (r_ == 8)  return F<4, 2, true>(__VA_ARGS__);                               \
+            if (r_ == 16) return F<4, 4, true>(__VA_ARGS__);                               \
+            if (r_ == 32) return F<4, 8, true>(__VA_ARGS__);                               \
+            if (r_ == 64) return F<4, 16, true>(__VA_ARGS__);                              \
+            if (r_ <= 4)  return F<4, 1, false>(__VA_ARGS__);                              \
+            if (r_ <= 8)  return F<4, 2, false>(__VA_ARGS__);                              \
+            if (r_ <= 16) return F<4, 4, false>(__VA_ARGS__);                              \
+            if (r_ <= 32) return F<4, 8, false>(__VA_ARGS__);                              \
+            return F<4, 16, false>(__VA_ARGS__);                                           \
+        }                                                                                  \
+        if (r_ == 16)  return F<8, 2, true>(__VA_ARGS__);                                  \
+        if (r_ == 32)  return F<8, 4, true>(__VA_ARGS__);                                  \
+        if (r_ == 48)  return F<8, 6, true>(__VA_ARGS__);                                  \
+        if (r_ == 64)  return F<8, 8, true>(__VA_ARGS__);                                  \
+        if (r_ == 96)  return F<8, 12, true>(__VA_ARGS__);                                 \
+        if (r_ == 128) return F<8, 16, true>(__VA_ARGS__);                                 \
+        if (r_ <= 16)  return F<8, 2, false>(__VA_ARGS__);                                 \
+        if (r_ <= 32)  return F<8, 4, false>(__VA_ARGS__);                                 \
+        if (r_ <= 64)  return F<8, 8, false>(__VA_ARGS__);                                 \
+        return F<8, 16, false>(__VA_ARGS__);                                               \
+    }()
 
 hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                             const int32_t *rowmap, const double *Dn, int64_t R, double *out, void *scratch,
@@ -821,15 +861,9 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
             hipLaunchKernelGGL(k_stream_rank1<false>, dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals, sb,
                                rowmap, Dn, out, sc.nnz, sc.ntiles, scratch);
         e = hipGetLastError();
-    } else if (R == 8)  e = launch_rankR<2, true>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
-    else if (R == 16)   e = launch_rankR<4, true>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
-    else if (R == 32)   e = launch_rankR<8, true>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
-    else if (R == 64)   e = launch_rankR<16, true>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
-    else if (R <= 4)    e = launch_rankR<1, false>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
-    else if (R <= 8)    e = launch_rankR<2, false>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
-    else if (R <= 16)   e = launch_rankR<4, false>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
-    else if (R <= 32)   e = launch_rankR<8, false>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
-    else                e = launch_rankR<16, false>(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
+    } else {
+        e = COMET_DISPATCH_RANK(launch_rankR, R, sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
+    }
     if (e != hipSuccess) return e;
     return run_fixup(scratch, sc.ntiles, (int)R, rowmap, out, sc.max_seg_len / kTile + 2, st);
 }
@@ -849,17 +883,8 @@ hipError_t stream_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t 
     (void)nslice;
     if (sc.ntiles <= 0) return hipSuccess;
     if (!stream_mttkrp_supports_rank(R) || !sc.slice_begin) return hipErrorNotSupported;
-    hipError_t e;
     const int r = (int)R;
-    if (R == 8)        e = launch_mttkrp<2, true>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
-    else if (R == 16)  e = launch_mttkrp<4, true>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
-    else if (R == 32)  e = launch_mttkrp<8, true>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
-    else if (R == 64)  e = launch_mttkrp<16, true>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
-    else if (R <= 4)   e = launch_mttkrp<1, false>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
-    else if (R <= 8)   e = launch_mttkrp<2, false>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
-    else if (R <= 16)  e = launch_mttkrp<4, false>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
-    else if (R <= 32)  e = launch_mttkrp<8, false>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
-    else               e = launch_mttkrp<16, false>(sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
+    hipError_t e = COMET_DISPATCH_RANK(launch_mttkrp, R, sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
     if (e != hipSuccess) return e;
     return run_fixup(scratch, sc.ntiles, r, nullptr, M, sc.max_parent_len > 0 ? sc.max_parent_len / kTile + 2 : 0, st);
 }
