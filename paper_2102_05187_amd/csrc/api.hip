@@ -144,9 +144,11 @@ comet_status ensure_scratch(const comet_tensor *t, size_t bytes) {
 // (device allocations are; sub-views handed in by a caller may not be).
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-bool use_tiled(const comet_tensor *t, int64_t R, const void *dense) {
+// Rank-R tiled kernels address operand rows with 32-bit byte offsets: the operand must be < 4 GiB.
+bool use_tiled(const comet_tensor *t, int64_t R, const void *dense, int64_t dense_rows = 0) {
     if (t->variant == 1) return false;
     if (!comet::stream_supports_rank(R)) return false;
+    if (R > 1 && dense_rows * R * 8 >= (int64_t(1) << 32) - 4096) return false;
     const int leaf = t->order - 1;
     if (!aligned16(t->crd_i(leaf)) || !aligned16(t->vals_d()) || !aligned16(dense)) return false;
     return true;
@@ -337,7 +339,7 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
         if (A->fmt == Format::CSR) HIP_TRY(comet::fill_zero_f64(out, A->dims[0] * R, st));
         return COMET_OK;
     }
-    if (use_tiled(A, R, Dn)) {
+    if (use_tiled(A, R, Dn, A->dims[1])) {
         size_t need = comet::stream_scratch_bytes(A->sched.ntiles, R);
         comet_status rs = ensure_scratch(A, need);
         if (rs != COMET_OK) return rs;
@@ -411,7 +413,7 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
     double *yv = (double *)y->vals->ptr;
     if (X->nvals > 0) {
         if (csf) {
-            if (use_tiled(X, R, Dn)) {
+            if (use_tiled(X, R, Dn, X->dims[2])) {
                 rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.ntiles, R));
                 if (rs != COMET_OK) return rs;
                 HIP_TRY(comet::stream_segreduce(X->sched, X->pos_i(2), X->crd_i(2), X->vals_d(), nullptr, Dn, R, yv,
@@ -460,7 +462,8 @@ comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *
     // rows of M whose index is not stored at the root level receive no contribution
     HIP_TRY(comet::fill_zero_f64(M, X->dims[0] * R, st));
     if (X->nvals == 0) return COMET_OK;
-    if (use_tiled(X, R, B) && aligned16(C) && comet::stream_mttkrp_supports_rank(R)) {
+    if (use_tiled(X, R, B, X->dims[1] > X->dims[2] ? X->dims[1] : X->dims[2]) && aligned16(C) &&
+        comet::stream_mttkrp_supports_rank(R)) {
         comet_status rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.ntiles, R));
         if (rs != COMET_OK) return rs;
         HIP_TRY(comet::stream_mttkrp(X->sched, X->pos_i(1), X->crd_i(0), X->pos_len[1] - 1, X->pos_i(2), X->crd_i(1),

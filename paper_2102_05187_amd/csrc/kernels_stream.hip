@@ -340,27 +340,21 @@ __global__ void __launch_bounds__(256) k_stream_fixup(void *scratch, int64_t nti
 
 // ---- rank-R walk: a group of L lanes (4 or 8) walks a run of consecutive items --------------------
 // The 256 threads of a tile form 256/L lane groups ("walkers"); walker g owns the 16*L consecutive
-// items [tb + 16*L*g, +16*L).  Every 4*L items each lane loads four consecutive (crd, val, tail id)
-// triples with 16-byte loads; the group then takes the items one at a time, fetching the current
-// item's triple from the lane that holds it with DPP broadcasts (quad_perm inside a quad, plus one
-// row_shr:4 / row_shl:4 with a bank mask to cross the two quads of an 8-lane group).  For one item
-// the group reads the operand row Dn[crd, :] as contiguous 16-byte pieces (WIDE, R a multiple of
-// 2L: lane j takes ranks 2L*q+2j, 2L*q+2j+1) or 8-byte pieces (lane j takes ranks L*q+j), so a load
-// instruction touches each gathered row as one contiguous run of 16*L bytes: with L = 8 that is a
-// whole 128-byte cache line per instruction, which halves the number of L1 accesses per nonzero
-// against L = 4 (the texture-address / L1 tag path is what bounds these kernels).
-template <int L, int BP>
-__device__ __forceinline__ int grp_bcast_i(int v) {
-    static_assert(L == 4 || L == 8, "lane groups of 4 or 8");
-    const int x1 = __builtin_amdgcn_update_dpp(0, v, (BP % 4) * 0x55, 0xf, 0xf, false);     // quad_perm broadcast
-    if constexpr (L == 4) return x1;
-    else if constexpr (BP < 4) return __builtin_amdgcn_update_dpp(x1, x1, 0x114, 0xf, 0xa, false);   // row_shr:4 into the odd quads
-    else return __builtin_amdgcn_update_dpp(x1, x1, 0x104, 0xf, 0x5, false);                          // row_shl:4 into the even quads
-}
-template <int L, int BP>
-__device__ __forceinline__ double grp_bcast_d(double v) {
-    return __hiloint2double(grp_bcast_i<L, BP>(__double2hiint(v)), grp_bcast_i<L, BP>(__double2loint(v)));
-}
+// items [tb + 16*L*g, +16*L).  Every 4*L items (a super-block) each lane loads four consecutive
+// (crd, val) pairs with 16-byte loads, looks up their tail ids, turns crd into the byte offset of
+// the operand row, and writes one small record per item into the walker's private LDS area.  The
+// group then takes the items one at a time: every lane reads the current item's record with a
+// broadcast LDS read (no cross-lane VALU work), adds its own 16-byte slot, and gathers its share of
+// the operand row Dn[crd, :] -- contiguous 16-byte pieces (WIDE, R a multiple of 2L: lane j takes
+// ranks 2L*q+2j, 2L*q+2j+1) or 8-byte pieces (lane j takes ranks L*q+j) -- so a load instruction
+// reads each gathered row as one contiguous run of 16*L bytes.  Gathers run G steps ahead of the
+// FMAs (double-buffered in registers).  Row offsets are 32-bit, so an operand must be < 4 GiB.
+template <int L, int NI>
+struct RecLayout {                                     // per-walker record area, in 4-byte words
+    static constexpr int SB = 4 * L;                   // items per super-block
+    static constexpr int kVal = NI * SB;               // values start after the integer records
+    static constexpr int kStride = NI * SB + 2 * SB + 4;   // + 16 bytes so that walkers start on different banks
+};
 
 // This lane's share of a dense row: V values.
 template <int L, int V, bool WIDE>
@@ -415,7 +409,7 @@ __device__ __forceinline__ void lane_load_items(LaneItems &it, const int32_t *__
     }
 }
 
-template <int V> struct RowBuf { double d[V]; };
+template <int V> struct RowBuf { double d[V]; int tail; double a; int boff, mrow; };
 
 // Steps per pipeline group: the gathers of group g+1 are in flight while group g is consumed.
 template <int V> struct StepGroup { static constexpr int value = V <= 4 ? 4 : (V <= 8 ? 2 : 1); };
@@ -427,24 +421,26 @@ struct WalkState {
     int ht, first_id;
 };
 
-template <int L, int V, bool WIDE, bool ROWMAP>
-__device__ __forceinline__ void grp_consume(WalkState<V> &st, double a, int t, const RowBuf<V> &b,
-                                            const int32_t *__restrict__ rowmap, double *__restrict__ out, int R, int j) {
+// This lane's share of the dense row that starts `off` bytes into Dn (off already includes the
+// lane's own slot).
+template <int L, int V, bool WIDE>
+__device__ __forceinline__ void grp_load_row_off(const double *__restrict__ Dn, unsigned off, int R, int j, double *d) {
+    const char *base = reinterpret_cast<const char *>(Dn);
+    if constexpr (WIDE) {
 #pragma unroll
-    for (int q = 0; q < V; ++q) st.acc[q] = fma(a, b.d[q], st.acc[q]);
-    if (t >= 0) {                                   // the item ends segment t (same for every lane of the group)
-        if (!st.ht) {
-#pragma unroll
-            for (int q = 0; q < V; ++q) st.first[q] = st.acc[q];
-            st.first_id = t;
-            st.ht = 1;
-        } else {
-            grp_store_row<L, V, WIDE>(out, ROWMAP ? (int64_t)rowmap[t] : (int64_t)t, R, j, st.acc);
+        for (int q = 0; q < V / 2; ++q) {
+            const double2 x = *reinterpret_cast<const double2 *>(base + (size_t)(off + (unsigned)(16 * L * q)));
+            d[2 * q] = x.x; d[2 * q + 1] = x.y;
         }
+    } else {
 #pragma unroll
-        for (int q = 0; q < V; ++q) st.acc[q] = 0.0;
+        for (int q = 0; q < V; ++q) {
+            d[q] = L * q + j < R ? *reinterpret_cast<const double *>(base + (size_t)(off + (unsigned)(8 * L * q))) : 0.0;
+        }
     }
 }
+template <int L, bool WIDE>
+__device__ __forceinline__ unsigned lane_slot_bytes(int j) { return WIDE ? 16u * j : 8u * j; }
 
 // Close the first segment end of every walker of the tile and publish the tile summary.
 // wopen[(g*L + j)*V + q] holds walker g's open sum, wht[g] its has_tail flag (both already written
@@ -497,8 +493,10 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
                                                       void *scratch) {
     constexpr int NW = 256 / L;                // walkers per tile
     constexpr int WI = kTile / NW;             // items per walker
-    constexpr int SB = 4 * L;                  // items per super-block (4 per lane)
+    using RL = RecLayout<L, 2>;                // record = {row byte offset, tail id} + value
+    constexpr int SB = RL::SB;
     __shared__ __attribute__((aligned(16))) int32_t ts[kTile];
+    __shared__ __attribute__((aligned(16))) int32_t rec_all[NW * RL::kStride];
     __shared__ __attribute__((aligned(16))) double wopen[256 * V];       // [walker][lane j][V]
     __shared__ int wht[NW];
     const int64_t t = blockIdx.x;
@@ -513,31 +511,55 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
 #pragma unroll
     for (int q = 0; q < V; ++q) { st.acc[q] = 0.0; st.first[q] = 0.0; }
     st.ht = 0; st.first_id = -1;
+    int32_t *rec = rec_all + g * RL::kStride;
+    const unsigned R8 = 8u * (unsigned)R;
+    const unsigned slot = lane_slot_bytes<L, WIDE>(j);
+    char *outb = reinterpret_cast<char *>(out);
 
     constexpr int G = StepGroup<V>::value, NG = SB / G;
     for (int sb = 0; sb < WI / SB; ++sb) {
         const int64_t i0 = gb + SB * sb + 4 * j;                  // this lane's four items
         LaneItems nxt;
         if (sb + 1 < WI / SB) lane_load_items(nxt, crd, vals, i0 + SB, nnz);
-        int tl[4];
         {
             const int4 t4 = *reinterpret_cast<const int4 *>(ts + (i0 - tb));
-            tl[0] = t4.x; tl[1] = t4.y; tl[2] = t4.z; tl[3] = t4.w;
+            *reinterpret_cast<int4 *>(rec + 8 * j) =
+                make_int4((int)((unsigned)cur.cr[0] * R8), t4.x, (int)((unsigned)cur.cr[1] * R8), t4.y);
+            *reinterpret_cast<int4 *>(rec + 8 * j + 4) =
+                make_int4((int)((unsigned)cur.cr[2] * R8), t4.z, (int)((unsigned)cur.cr[3] * R8), t4.w);
+            *reinterpret_cast<double2 *>(rec + RL::kVal + 8 * j) = make_double2(cur.va[0], cur.va[1]);
+            *reinterpret_cast<double2 *>(rec + RL::kVal + 8 * j + 4) = make_double2(cur.va[2], cur.va[3]);
         }
+        __builtin_amdgcn_wave_barrier();                          // records are read by the other lanes of the group
         RowBuf<V> buf[2][G];
         auto issue = [&](auto gc, RowBuf<V> *bb) {
             static_for<0, G>([&](auto sc) {
                 constexpr int k = decltype(gc)::value * G + decltype(sc)::value;      // step inside the super-block
-                const int c = grp_bcast_i<L, k / 4>(cur.cr[k % 4]);
-                grp_load_row<L, V, WIDE>(Dn, c, R, j, bb[decltype(sc)::value].d);
+                RowBuf<V> &b = bb[decltype(sc)::value];
+                const int2 ct = *reinterpret_cast<const int2 *>(rec + 2 * k);
+                b.a = *reinterpret_cast<const double *>(rec + RL::kVal + 2 * k);
+                b.tail = ct.y;
+                grp_load_row_off<L, V, WIDE>(Dn, (unsigned)ct.x + slot, R, j, b.d);
             });
         };
         auto consume = [&](auto gc, const RowBuf<V> *bb) {
             static_for<0, G>([&](auto sc) {
-                constexpr int k = decltype(gc)::value * G + decltype(sc)::value;
-                const double a = grp_bcast_d<L, k / 4>(cur.va[k % 4]);
-                const int tt = grp_bcast_i<L, k / 4>(tl[k % 4]);
-                grp_consume<L, V, WIDE, ROWMAP>(st, a, tt, bb[decltype(sc)::value], rowmap, out, R, j);
+                const RowBuf<V> &b = bb[decltype(sc)::value];
+#pragma unroll
+                for (int q = 0; q < V; ++q) st.acc[q] = fma(b.a, b.d[q], st.acc[q]);
+                if (b.tail >= 0) {                                // the item ends segment `tail` (same for the group)
+                    if (!st.ht) {
+#pragma unroll
+                        for (int q = 0; q < V; ++q) st.first[q] = st.acc[q];
+                        st.first_id = b.tail;
+                        st.ht = 1;
+                    } else {
+                        const unsigned row = ROWMAP ? (unsigned)rowmap[b.tail] : (unsigned)b.tail;
+                        grp_store_row<L, V, WIDE>(reinterpret_cast<double *>(outb + (size_t)row * R8), 0, R, j, st.acc);
+                    }
+#pragma unroll
+                    for (int q = 0; q < V; ++q) st.acc[q] = 0.0;
+                }
             });
         };
         issue(IntC<0>{}, buf[0]);
@@ -546,6 +568,7 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
             if constexpr (gi + 1 < NG) issue(IntC<gi + 1>{}, buf[(gi + 1) & 1]);
             consume(gc, buf[gi & 1]);
         });
+        __builtin_amdgcn_wave_barrier();                          // all reads of this super-block's records are done
         if (sb + 1 < WI / SB) cur = nxt;
     }
 
@@ -571,6 +594,22 @@ hipError_t launch_rankR(const Schedule &sc, const int32_t *pos, const int32_t *c
         hipLaunchKernelGGL((k_stream_rankR<L, V, WIDE, false>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
                            (const int32_t *)sc.seg_begin->ptr, rowmap, Dn, out, sc.nnz, sc.ntiles, R, scratch);
     return hipGetLastError();
+}
+
+// Cross-lane broadcast inside a lane group (quad_perm inside a quad, plus one row_shr:4 / row_shl:4 with a
+// bank mask to cross the two quads of an 8-lane group); used by the MTTKRP walk, whose LDS budget goes
+// to its two tail maps.
+template <int L, int BP>
+__device__ __forceinline__ int grp_bcast_i(int v) {
+    static_assert(L == 4 || L == 8, "lane groups of 4 or 8");
+    const int x1 = __builtin_amdgcn_update_dpp(0, v, (BP % 4) * 0x55, 0xf, 0xf, false);     // quad_perm broadcast
+    if constexpr (L == 4) return x1;
+    else if constexpr (BP < 4) return __builtin_amdgcn_update_dpp(x1, x1, 0x114, 0xf, 0xa, false);   // row_shr:4 into the odd quads
+    else return __builtin_amdgcn_update_dpp(x1, x1, 0x104, 0xf, 0x5, false);                          // row_shl:4 into the even quads
+}
+template <int L, int BP>
+__device__ __forceinline__ double grp_bcast_d(double v) {
+    return __hiloint2double(grp_bcast_i<L, BP>(__double2hiint(v)), grp_bcast_i<L, BP>(__double2loint(v)));
 }
 
 // ---- MTTKRP: the same walk, two nested segment levels ---------------------------------------------
