@@ -78,6 +78,16 @@ comet_status build_schedule(comet_tensor &t, hipStream_t st) {
         comet_status rs = read_i32((const int32_t *)mx->ptr, 1, &h, st);
         if (rs != COMET_OK) return rs;
         sc.max_seg_len = h;
+        sc.nchunks = (sc.nnz + comet::kChunk - 1) / comet::kChunk;
+        sc.chunk_seg_begin = comet::dev_alloc(sizeof(int32_t) * (sc.nchunks + 1));
+        if (!sc.chunk_seg_begin) return COMET_ERR_ALLOC;
+        HIP_TRY(comet::build_seg_begin(t.pos_i(leaf), sc.nseg, sc.nnz, comet::kChunk, sc.nchunks,
+                                       (int32_t *)sc.chunk_seg_begin->ptr, st));
+        HIP_TRY(hipMemsetAsync(mx->ptr, 0, sizeof(int32_t), st));
+        HIP_TRY(comet::count_empty_segments(t.pos_i(leaf), sc.nseg, (int32_t *)mx->ptr, st));
+        rs = read_i32((const int32_t *)mx->ptr, 1, &h, st);
+        if (rs != COMET_OK) return rs;
+        sc.empty_segments = h;
         if (t.fmt == Format::CSF3) {
             HIP_TRY(hipMemsetAsync(mx->ptr, 0, sizeof(int32_t), st));
             HIP_TRY(comet::max_parent_span(t.pos_i(1), t.pos_len[1] - 1, t.pos_i(2), (int32_t *)mx->ptr, st));
@@ -340,10 +350,10 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
         return COMET_OK;
     }
     if (use_tiled(A, R, Dn, A->dims[1])) {
-        size_t need = comet::stream_scratch_bytes(A->sched.ntiles, R);
+        size_t need = comet::stream_scratch_bytes(R == 1 ? A->sched.nchunks : A->sched.ntiles, R);
         comet_status rs = ensure_scratch(A, need);
         if (rs != COMET_OK) return rs;
-        HIP_TRY(comet::stream_segreduce(A->sched, A->pos_i(1), A->crd_i(1), A->vals_d(), rowmap, Dn, R, out,
+        HIP_TRY(comet::stream_segreduce(A->sched, A->pos_i(1), A->crd_i(1), A->vals_d(), rowmap, Dn, A->dims[1], R, out,
                                         A->scratch->ptr, st));
         return COMET_OK;
     }
@@ -414,10 +424,10 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
     if (X->nvals > 0) {
         if (csf) {
             if (use_tiled(X, R, Dn, X->dims[2])) {
-                rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.ntiles, R));
+                rs = ensure_scratch(X, comet::stream_scratch_bytes(R == 1 ? X->sched.nchunks : X->sched.ntiles, R));
                 if (rs != COMET_OK) return rs;
-                HIP_TRY(comet::stream_segreduce(X->sched, X->pos_i(2), X->crd_i(2), X->vals_d(), nullptr, Dn, R, yv,
-                                                X->scratch->ptr, st));
+                HIP_TRY(comet::stream_segreduce(X->sched, X->pos_i(2), X->crd_i(2), X->vals_d(), nullptr, Dn, X->dims[2], R,
+                                                yv, X->scratch->ptr, st));
             } else {
                 HIP_TRY(comet::simple_segreduce(X->pos_i(2), X->crd_i(2), X->vals_d(), X->pos_len[2] - 1, X->nvals,
                                                 nullptr, Dn, R, yv, st));

@@ -27,6 +27,7 @@ hipError_t build_parent_begin(const int32_t *parent_pos, int64_t nparent, const 
 hipError_t build_run_base(const int32_t *c0, const int32_t *c1, int64_t nnz, int tile, int64_t ntiles,
                           int32_t *run_base /* [ntiles+1] */, hipStream_t st);
 hipError_t max_segment_length(const int32_t *pos, int64_t nseg, int32_t *out_max, hipStream_t st);
+hipError_t count_empty_segments(const int32_t *pos, int64_t nseg, int32_t *out_count, hipStream_t st);
 hipError_t max_parent_span(const int32_t *parent_pos, int64_t nparent, const int32_t *leaf_pos, int32_t *out_max,
                            hipStream_t st);
 

@@ -142,14 +142,14 @@ struct Rank1Carry {
 };
 
 template <bool ROWMAP>
-__device__ __forceinline__ void rank1_process_half(const Rank1Half &h, const double2 *xv, const int32_t *ts,
-                                                   int64_t base, int64_t tb, int64_t nnz, int lane, int w,
+__device__ __forceinline__ void rank1_process_half(const Rank1Half &h, const double2 *xv, const int2 *tt,
+                                                   int64_t base, int64_t nnz, int lane, int w,
                                                    const int32_t *__restrict__ rowmap, double *__restrict__ out,
                                                    Rank1Carry &cy, double *wsum_first, int *wsum_first_id) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         const int64_t i0 = base + b * 128 + 2 * lane;
-        const int2 t = *reinterpret_cast<const int2 *>(ts + (i0 - tb));
+        const int2 t = tt[b];                                // segment ids of the items that end a segment, else -1
         const double p0 = i0 < nnz ? h.a[b].x * xv[b].x : 0.0;
         const double p1 = i0 + 1 < nnz ? h.a[b].y * xv[b].y : 0.0;
         const int f = (t.x >= 0) | (t.y >= 0);
@@ -204,9 +204,14 @@ __device__ __forceinline__ void walk_rank1(Rank1Half &h0, const int32_t *ts, con
     rank1_gather(h0, x, xv);
     Rank1Half h1;
     rank1_load_half(h1, crd, vals, wb + 512, lane, nnz);
-    rank1_process_half<ROWMAP>(h0, xv, ts, wb, tb, nnz, lane, w, rowmap, out, cy, wsum_first, wsum_first_id);
+    int2 tt[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) tt[b] = *reinterpret_cast<const int2 *>(ts + (wb - tb) + b * 128 + 2 * lane);
+    rank1_process_half<ROWMAP>(h0, xv, tt, wb, nnz, lane, w, rowmap, out, cy, wsum_first, wsum_first_id);
     rank1_gather(h1, x, xv);
-    rank1_process_half<ROWMAP>(h1, xv, ts, wb + 512, tb, nnz, lane, w, rowmap, out, cy, wsum_first, wsum_first_id);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) tt[b] = *reinterpret_cast<const int2 *>(ts + (wb - tb) + 512 + b * 128 + 2 * lane);
+    rank1_process_half<ROWMAP>(h1, xv, tt, wb + 512, nnz, lane, w, rowmap, out, cy, wsum_first, wsum_first_id);
     if (lane == 0) { wsum_ht[w] = cy.cf; wsum_open[w] = cy.cv; }
 }
 
@@ -256,6 +261,92 @@ __global__ void __launch_bounds__(256) k_stream_rank1(const int32_t *__restrict_
     walk_rank1<ROWMAP>(h0, ts, crd, vals, x, rowmap, out, tb, nnz, wsum_ht, wsum_open, wsum_first, wsum_first_id);
     __syncthreads();
     finish_tile_rank1<ROWMAP>(wsum_ht, wsum_open, wsum_first, wsum_first_id, rowmap, out, carry_view(scratch, ntiles, 1), t);
+}
+
+// ---- rank-1 kernel with the dense vector staged in LDS ----------------------------------------------
+// When x (SpMV) / v (TTV) fits in the 160 KB of LDS next to a few hundred bytes of bookkeeping, one
+// workgroup of 16 wavefronts per CU copies it in once and every gather x[crd] becomes an LDS read: the
+// L1 / texture-address path, which handles only about one scattered 8-byte gather per clock per CU,
+// is then left to the streaming loads.  Each wavefront works alone on 1024-item chunks (no workgroup
+// barrier after the staging): it marks the segment ends of its chunk in a private 1024-bit mask,
+// gets the segment id of an end as (first segment of the chunk) + (ends before it) -- valid because
+// this kernel is only used when the level has no empty segment -- and writes the chunk summary
+// straight to the carry buffer (one entry per chunk).
+template <bool ROWMAP>
+__global__ void __launch_bounds__(1024) k_stream_rank1_ldsvec(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
+                                                              const double *__restrict__ vals,
+                                                              const int32_t *__restrict__ chunk_seg_begin,
+                                                              const int32_t *__restrict__ rowmap,
+                                                              const double *__restrict__ x, int64_t ncols,
+                                                              double *__restrict__ out, int64_t nnz, int64_t nchunks,
+                                                              void *scratch) {
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    const int64_t xpad = (ncols + 1) & ~(int64_t)1;
+    double *xs = reinterpret_cast<double *>(lds_raw);
+    unsigned *bits_all = reinterpret_cast<unsigned *>(lds_raw + xpad * 8);            // [16][32]
+    double *wfirst_all = reinterpret_cast<double *>(lds_raw + xpad * 8 + 16 * 128);   // [16]
+    int *wfirst_id_all = reinterpret_cast<int *>(lds_raw + xpad * 8 + 16 * 128 + 16 * 8);   // [16]
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    unsigned *bits = bits_all + w * 32;
+    const int64_t stride = (int64_t)gridDim.x * 16;
+    int64_t c = (int64_t)blockIdx.x * 16 + w;
+    Rank1Half h0;
+    if (c < nchunks) rank1_load_half(h0, crd, vals, c * kChunk, lane, nnz);          // in flight during the staging
+    for (int64_t i = (int64_t)threadIdx.x * 2; i + 1 < ncols; i += 2048)
+        *reinterpret_cast<double2 *>(xs + i) = *reinterpret_cast<const double2 *>(x + i);
+    if ((ncols & 1) && threadIdx.x == 0) xs[ncols - 1] = x[ncols - 1];
+    __syncthreads();
+    CarryView cb = carry_view(scratch, nchunks, 1);
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    for (; c < nchunks; c += stride) {
+        const int64_t cbeg = c * kChunk;
+        if (lane < 32) bits[lane] = 0u;
+        __builtin_amdgcn_wave_barrier();
+        const int32_t s0 = chunk_seg_begin[c], s1 = chunk_seg_begin[c + 1];
+        for (int32_t sgm = s0 + lane; sgm < s1; sgm += 64) {
+            const int64_t idx = (int64_t)pos[sgm + 1] - 1 - cbeg;                      // in [0, 1024): the segment ends here
+            atomicOr(&bits[idx >> 5], 1u << (idx & 31));
+        }
+        __builtin_amdgcn_wave_barrier();
+        Rank1Carry cy{0, 0.0};
+        int base_id = s0;
+        auto tails_of_half = [&](int half, int2 *tt) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const unsigned word = bits[(half * 4 + b) * 4 + (lane >> 4)];
+                const int sh = (2 * lane) & 31;
+                const bool t0 = (word >> sh) & 1u, t1 = (word >> (sh + 1)) & 1u;
+                const unsigned long long b0 = __ballot(t0), b1 = __ballot(t1);
+                const int id0 = base_id + __popcll(b0 & lt_mask) + __popcll(b1 & lt_mask);
+                tt[b].x = t0 ? id0 : -1;
+                tt[b].y = t1 ? id0 + (t0 ? 1 : 0) : -1;
+                base_id += __popcll(b0) + __popcll(b1);
+            }
+        };
+        auto gather = [&](const Rank1Half &h, double2 *xv) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) { xv[b].x = xs[h.c[b].x]; xv[b].y = xs[h.c[b].y]; }
+        };
+        double2 xv[4];
+        int2 tt[4];
+        Rank1Half h1;
+        rank1_load_half(h1, crd, vals, cbeg + 512, lane, nnz);
+        gather(h0, xv);
+        tails_of_half(0, tt);
+        rank1_process_half<ROWMAP>(h0, xv, tt, cbeg, nnz, lane, w, rowmap, out, cy, wfirst_all, wfirst_id_all);
+        if (c + stride < nchunks) rank1_load_half(h0, crd, vals, (c + stride) * kChunk, lane, nnz);   // next chunk
+        gather(h1, xv);
+        tails_of_half(1, tt);
+        rank1_process_half<ROWMAP>(h1, xv, tt, cbeg + 512, nnz, lane, w, rowmap, out, cy, wfirst_all, wfirst_id_all);
+        __builtin_amdgcn_wave_barrier();
+        if (lane == 0) {
+            cb.has_tail[c] = cy.cf;
+            cb.open[c] = cy.cv;
+            cb.first[c] = cy.cf ? wfirst_all[w] : 0.0;
+            cb.first_id[c] = cy.cf ? wfirst_id_all[w] : -1;
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
 }
 
 // ---- rank-1 kernel for sorted coordinate lists [CN,S,S] -------------------------------------------
@@ -843,6 +934,12 @@ static int lanes_per_item(int64_t R) {
     return 8;
 }
 
+// COMET_NO_LDS_VECTOR=1 keeps rank-1 operations on the L1-gather kernel (for measurements).
+static bool no_lds_vector() {
+    static int v = [] { const char *e = getenv("COMET_NO_LDS_VECTOR"); return e ? atoi(e) : 0; }();
+    return v != 0;
+}
+
 bool stream_supports_rank(int64_t R) { return R >= 1 && R <= 128; }
 bool stream_mttkrp_supports_rank(int64_t R) { return R >= 1 && R <= 128; }
 bool stream_supports_coo() { return true; }
@@ -886,13 +983,35 @@ size_t stream_scratch_bytes(int64_t ntiles, int64_t R) {
     }()
 
 hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
-                            const int32_t *rowmap, const double *Dn, int64_t R, double *out, void *scratch,
-                            hipStream_t st) {
+                            const int32_t *rowmap, const double *Dn, int64_t dense_rows, int64_t R, double *out,
+                            void *scratch, hipStream_t st) {
     if (sc.ntiles <= 0) return hipSuccess;
     if (!stream_supports_rank(R)) return hipErrorNotSupported;
     const int32_t *sb = (const int32_t *)sc.seg_begin->ptr;
     hipError_t e = hipSuccess;
     if (R == 1) {
+        const size_t lds_bytes = (size_t)((dense_rows + 1) & ~(int64_t)1) * 8 + 16 * 128 + 16 * 8 + 16 * 4;
+        if (sc.empty_segments == 0 && sc.chunk_seg_begin && sc.nchunks >= 16 && lds_bytes <= 160 * 1024 && !no_lds_vector()) {
+            // the dense vector fits in LDS and every segment holds a nonzero: wavefront-per-chunk kernel
+            static int ncu = [] { hipDeviceProp_t p; return hipGetDeviceProperties(&p, 0) == hipSuccess ? p.multiProcessorCount : 256; }();
+            const int64_t want = (sc.nchunks + 15) / 16;
+            const unsigned grid = (unsigned)(want < ncu ? want : ncu);
+            const int32_t *csb = (const int32_t *)sc.chunk_seg_begin->ptr;
+            if (rowmap) {
+                e = hipFuncSetAttribute((const void *)k_stream_rank1_ldsvec<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                if (e != hipSuccess) return e;
+                hipLaunchKernelGGL(k_stream_rank1_ldsvec<true>, dim3(grid), dim3(1024), lds_bytes, st, pos, crd, vals, csb,
+                                   rowmap, Dn, dense_rows, out, sc.nnz, sc.nchunks, scratch);
+            } else {
+                e = hipFuncSetAttribute((const void *)k_stream_rank1_ldsvec<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                if (e != hipSuccess) return e;
+                hipLaunchKernelGGL(k_stream_rank1_ldsvec<false>, dim3(grid), dim3(1024), lds_bytes, st, pos, crd, vals, csb,
+                                   rowmap, Dn, dense_rows, out, sc.nnz, sc.nchunks, scratch);
+            }
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+            return run_fixup(scratch, sc.nchunks, 1, rowmap, out, sc.max_seg_len / kChunk + 2, st);
+        }
         if (rowmap)
             hipLaunchKernelGGL(k_stream_rank1<true>, dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals, sb,
                                rowmap, Dn, out, sc.nnz, sc.ntiles, scratch);

@@ -20,10 +20,10 @@ bool   stream_supports_coo();
 size_t stream_scratch_bytes(int64_t ntiles, int64_t R);
 
 // out[row(s), :] = sum_{p in segment s} vals[p] * Dn[crd[p], :],  row(s) = rowmap ? rowmap[s] : s.
-// Every segment of the level is written (empty ones with zeros).
+// Every segment of the level is written (empty ones with zeros).  dense_rows = number of rows of Dn.
 hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
-                            const int32_t *rowmap, const double *Dn, int64_t R, double *out, void *scratch,
-                            hipStream_t st);
+                            const int32_t *rowmap, const double *Dn, int64_t dense_rows, int64_t R, double *out,
+                            void *scratch, hipStream_t st);
 
 // Sorted COO [CN,S,S]: one output (i, j, value) per run of equal (c0, c1).
 hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *c1, const int32_t *c2,

@@ -42,6 +42,8 @@ enum class Format { CSR, DCSR, COO2, COO3, CSF3, CSF3_DENSE_LEAF, OTHER };
 
 // Items per tile of the nonzero-tiled kernels (a multiple of every per-wave chunk they use).
 constexpr int kTile = 4096;
+// Items per chunk of the wavefront-per-chunk kernel (one wavefront's share of a tile).
+constexpr int kChunk = 1024;
 
 // Per-tensor schedule for the nonzero-tiled kernels, built once at creation.
 //   The leaf level's nonzeros are cut into tiles of kTile consecutive positions; seg_begin[t] is
@@ -55,6 +57,9 @@ struct Schedule {
     DevRef  slice_begin;   // int32 [ntiles + 1]   (CSF3 only)
     DevRef  run_base;      // int32 [ntiles + 1]   (COO3 only)
     int64_t nruns = 0;     // COO3: number of distinct (i,j) pairs
+    DevRef  chunk_seg_begin;   // int32 [nchunks + 1]: seg_begin at kChunk granularity
+    int64_t nchunks = 0;
+    int64_t empty_segments = -1;  // leaf segments without a nonzero (-1 = unknown)
     int64_t max_seg_len = 0;      // longest leaf segment, in nonzeros (0 = unknown)
     int64_t max_parent_len = 0;   // CSF3: most nonzeros under one slice (0 = unknown)
 };

@@ -254,4 +254,21 @@ hipError_t max_parent_span(const int32_t *parent_pos, int64_t nparent, const int
     return hipGetLastError();
 }
 
+__global__ void __launch_bounds__(256) k_count_empty(const int32_t *__restrict__ pos, int64_t nseg,
+                                                     int32_t *__restrict__ out) {
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int32_t c = 0;
+    for (int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; s < nseg; s += stride)
+        c += pos[s + 1] == pos[s] ? 1 : 0;
+    if (c) atomicAdd(out, c);
+}
+
+hipError_t count_empty_segments(const int32_t *pos, int64_t nseg, int32_t *out_count, hipStream_t st) {
+    if (nseg <= 0) return hipSuccess;
+    int64_t want = (nseg + 255) / 256;
+    unsigned grid = (unsigned)(want > 2048 ? 2048 : want);
+    hipLaunchKernelGGL(k_count_empty, dim3(grid), dim3(256), 0, st, pos, nseg, out_count);
+    return hipGetLastError();
+}
+
 }  // namespace comet
