@@ -107,6 +107,11 @@ comet_status build_schedule(comet_tensor &t, hipStream_t st) {
         if (rs != COMET_OK) return rs;
         sc.nruns = h;
         sc.nseg = h;
+        sc.nchunks = (sc.nnz + comet::kChunk - 1) / comet::kChunk;
+        sc.chunk_run_base = comet::dev_alloc(sizeof(int32_t) * (sc.nchunks + 1));
+        if (!sc.chunk_run_base) return COMET_ERR_ALLOC;
+        HIP_TRY(comet::build_run_base(t.crd_i(0), t.crd_i(1), sc.nnz, comet::kChunk, sc.nchunks,
+                                      (int32_t *)sc.chunk_run_base->ptr, st));
     }
     HIP_TRY(hipStreamSynchronize(st));
     return COMET_OK;
@@ -434,9 +439,9 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
             }
         } else {
             if (use_tiled(X, 1, Dn) && comet::stream_supports_coo()) {
-                rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.ntiles, 1));
+                rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.nchunks, 1));
                 if (rs != COMET_OK) return rs;
-                HIP_TRY(comet::stream_ttv_coo(X->sched, X->crd_i(0), X->crd_i(1), X->crd_i(2), X->vals_d(), Dn,
+                HIP_TRY(comet::stream_ttv_coo(X->sched, X->crd_i(0), X->crd_i(1), X->crd_i(2), X->vals_d(), Dn, X->dims[2],
                                               (int32_t *)y->crd[0]->ptr, (int32_t *)y->crd[1]->ptr, yv,
                                               X->scratch->ptr, st));
             } else {

@@ -272,14 +272,19 @@ __global__ void __launch_bounds__(256) k_stream_rank1(const int32_t *__restrict_
 // gets the segment id of an end as (first segment of the chunk) + (ends before it) -- valid because
 // this kernel is only used when the level has no empty segment -- and writes the chunk summary
 // straight to the carry buffer (one entry per chunk).
-template <bool ROWMAP>
+// COO = true: the input is a sorted coordinate list [CN,S,S]; segment ends come from neighbour
+// comparisons of (c0, c1) instead of pos, the id of a run is (runs started before the chunk) + (runs
+// started earlier in the chunk), and the result's coordinate arrays y0 / y1 are written here too.
+template <bool ROWMAP, bool COO>
 __global__ void __launch_bounds__(1024) k_stream_rank1_ldsvec(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
                                                               const double *__restrict__ vals,
-                                                              const int32_t *__restrict__ chunk_seg_begin,
+                                                              const int32_t *__restrict__ chunk_begin,
                                                               const int32_t *__restrict__ rowmap,
                                                               const double *__restrict__ x, int64_t ncols,
                                                               double *__restrict__ out, int64_t nnz, int64_t nchunks,
-                                                              void *scratch) {
+                                                              void *scratch, const int32_t *__restrict__ c0,
+                                                              const int32_t *__restrict__ c1, int32_t *__restrict__ y0,
+                                                              int32_t *__restrict__ y1) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     const int64_t xpad = (ncols + 1) & ~(int64_t)1;
     double *xs = reinterpret_cast<double *>(lds_raw);
@@ -300,16 +305,68 @@ __global__ void __launch_bounds__(1024) k_stream_rank1_ldsvec(const int32_t *__r
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     for (; c < nchunks; c += stride) {
         const int64_t cbeg = c * kChunk;
-        if (lane < 32) bits[lane] = 0u;
-        __builtin_amdgcn_wave_barrier();
-        const int32_t s0 = chunk_seg_begin[c], s1 = chunk_seg_begin[c + 1];
-        for (int32_t sgm = s0 + lane; sgm < s1; sgm += 64) {
-            const int64_t idx = (int64_t)pos[sgm + 1] - 1 - cbeg;                      // in [0, 1024): the segment ends here
-            atomicOr(&bits[idx >> 5], 1u << (idx & 31));
+        int base_id;
+        if constexpr (COO) {
+            constexpr int kRows = kChunk / 64;
+            unsigned long long hm[kRows], hx[kRows];     // run starts; the same with items past the end counted as starts
+            const int runs_before = chunk_begin[c];
+            // all coordinate loads of the chunk are issued together; the predecessor of an item comes from the
+            // neighbouring lane (wave_shr:1), of lane 0 from the previous row (or the item before the chunk)
+            const int64_t inext = cbeg + kChunk;
+            int before0 = -2, before1 = -2, after0 = -1, after1 = -1;
+            if (cbeg > 0) { before0 = c0[cbeg - 1]; before1 = c1[cbeg - 1]; }
+            if (inext < nnz) { after0 = c0[inext]; after1 = c1[inext]; }
+            int running = runs_before;
+#pragma unroll
+            for (int rb = 0; rb < kRows; rb += 8) {               // two batches of 8 rows keep the register count down
+                int a0[8], a1[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const int64_t i = cbeg + 64 * (rb + q) + lane;
+                    a0[q] = i < nnz ? c0[i] : -1;
+                    a1[q] = i < nnz ? c1[i] : -1;
+                }
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const int r = rb + q;
+                    const int64_t i = cbeg + 64 * r + lane;
+                    const int p0 = dpp_i<0x138, 0xf>(before0, a0[q]);
+                    const int p1 = dpp_i<0x138, 0xf>(before1, a1[q]);
+                    const bool differs = a0[q] != p0 || a1[q] != p1;
+                    hm[r] = __ballot(differs && i < nnz);
+                    hx[r] = __ballot(differs);
+                    before0 = __builtin_amdgcn_readlane(a0[q], 63);
+                    before1 = __builtin_amdgcn_readlane(a1[q], 63);
+                    if ((hm[r] >> lane) & 1ull) {
+                        const int id = running + __popcll(hm[r] & lt_mask);
+                        y0[id] = a0[q]; y1[id] = a1[q];
+                    }
+                    running += __popcll(hm[r]);
+                }
+            }
+            const bool next_head = after0 != before0 || after1 != before1;
+#pragma unroll
+            for (int r = 0; r < kRows; ++r) {
+            // item e ends a run when item e+1 starts one or lies past the end of the list
+                const unsigned long long nextbit = r + 1 < kRows ? (hx[r + 1] & 1ull) : (next_head ? 1ull : 0ull);
+                const int64_t left = nnz - (cbeg + 64 * r);          // items of this row that exist
+                const unsigned long long exist = left >= 64 ? ~0ull : (left <= 0 ? 0ull : ((1ull << left) - 1ull));
+                const unsigned long long tmask = ((hx[r] >> 1) | (nextbit << 63)) & exist;
+                if (lane == 0) *reinterpret_cast<unsigned long long *>(bits + 2 * r) = tmask;
+            }
+            base_id = runs_before - ((hm[0] & 1ull) ? 0 : 1);        // the run that holds the chunk's first item
+        } else {
+            if (lane < 32) bits[lane] = 0u;
+            __builtin_amdgcn_wave_barrier();
+            const int32_t s0 = chunk_begin[c], s1 = chunk_begin[c + 1];
+            for (int32_t sgm = s0 + lane; sgm < s1; sgm += 64) {
+                const int64_t idx = (int64_t)pos[sgm + 1] - 1 - cbeg;                  // in [0, 1024): the segment ends here
+                atomicOr(&bits[idx >> 5], 1u << (idx & 31));
+            }
+            base_id = s0;
         }
         __builtin_amdgcn_wave_barrier();
         Rank1Carry cy{0, 0.0};
-        int base_id = s0;
         auto tails_of_half = [&](int half, int2 *tt) {
 #pragma unroll
             for (int b = 0; b < 4; ++b) {
@@ -875,22 +932,33 @@ __global__ void __launch_bounds__(256) k_fixup_level(const double *__restrict__ 
     const int64_t u1 = u0 + kFixGroup < n_lo ? u0 + kFixGroup : n_lo;
     int rf = 0, gid = -1;
     double rv = 0.0, gfirst = 0.0;
-#pragma unroll 8
-    for (int64_t u = u0; u < u1; ++u) {
-        const int ht = lo_ht[u];
-        const double op = lo_open[u * R + r];
-        if (ht) {
-            const double value = rv + lo_first[u * R + r];
-            const int32_t id = lo_id[u];
-            if (rf) {
-                const int64_t row = rowmap ? (int64_t)rowmap[id] : (int64_t)id;
-                out[row * R + r] = value;
+    for (int64_t ub = u0; ub < u1; ub += 16) {
+        // 16 summaries at a time: all loads are independent of the fold, so they are issued together
+        int ht[16], id[16];
+        double op[16], fi[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int64_t u = ub + i;
+            const bool in = u < u1;
+            ht[i] = in ? lo_ht[u] : 0;
+            id[i] = in ? lo_id[u] : -1;
+            op[i] = in ? lo_open[u * R + r] : 0.0;
+            fi[i] = in ? lo_first[u * R + r] : 0.0;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (ht[i]) {
+                const double value = rv + fi[i];
+                if (rf) {
+                    const int64_t row = rowmap ? (int64_t)rowmap[id[i]] : (int64_t)id[i];
+                    out[row * R + r] = value;
+                } else {
+                    gfirst = value; gid = id[i]; rf = 1;
+                }
+                rv = op[i];
             } else {
-                gfirst = value; gid = id; rf = 1;
+                rv += op[i];
             }
-            rv = op;
-        } else {
-            rv += op;
         }
     }
     up_first[g * R + r] = gfirst;
@@ -998,15 +1066,17 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
             const unsigned grid = (unsigned)(want < ncu ? want : ncu);
             const int32_t *csb = (const int32_t *)sc.chunk_seg_begin->ptr;
             if (rowmap) {
-                e = hipFuncSetAttribute((const void *)k_stream_rank1_ldsvec<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                e = hipFuncSetAttribute((const void *)k_stream_rank1_ldsvec<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
                 if (e != hipSuccess) return e;
-                hipLaunchKernelGGL(k_stream_rank1_ldsvec<true>, dim3(grid), dim3(1024), lds_bytes, st, pos, crd, vals, csb,
-                                   rowmap, Dn, dense_rows, out, sc.nnz, sc.nchunks, scratch);
+                hipLaunchKernelGGL((k_stream_rank1_ldsvec<true, false>), dim3(grid), dim3(1024), lds_bytes, st, pos, crd, vals,
+                                   csb, rowmap, Dn, dense_rows, out, sc.nnz, sc.nchunks, scratch, (const int32_t *)nullptr,
+                                   (const int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr);
             } else {
-                e = hipFuncSetAttribute((const void *)k_stream_rank1_ldsvec<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                e = hipFuncSetAttribute((const void *)k_stream_rank1_ldsvec<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
                 if (e != hipSuccess) return e;
-                hipLaunchKernelGGL(k_stream_rank1_ldsvec<false>, dim3(grid), dim3(1024), lds_bytes, st, pos, crd, vals, csb,
-                                   rowmap, Dn, dense_rows, out, sc.nnz, sc.nchunks, scratch);
+                hipLaunchKernelGGL((k_stream_rank1_ldsvec<false, false>), dim3(grid), dim3(1024), lds_bytes, st, pos, crd, vals,
+                                   csb, rowmap, Dn, dense_rows, out, sc.nnz, sc.nchunks, scratch, (const int32_t *)nullptr,
+                                   (const int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr);
             }
             e = hipGetLastError();
             if (e != hipSuccess) return e;
@@ -1027,12 +1097,29 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
 }
 
 hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *c1, const int32_t *c2,
-                          const double *vals, const double *v, int32_t *y0, int32_t *y1, double *yv, void *scratch,
-                          hipStream_t st) {
+                          const double *vals, const double *v, int64_t dense_rows, int32_t *y0, int32_t *y1, double *yv,
+                          void *scratch, hipStream_t st) {
     if (sc.ntiles <= 0) return hipSuccess;
+    // a run of equal (c0, c1) holds at most one nonzero per coordinate of the last mode
+    const int64_t max_run = dense_rows;
+    const size_t lds_bytes = (size_t)((dense_rows + 1) & ~(int64_t)1) * 8 + 16 * 128 + 16 * 8 + 16 * 4;
+    if (sc.chunk_run_base && sc.nchunks >= 16 && lds_bytes <= 160 * 1024 && !no_lds_vector()) {
+        static int ncu = [] { hipDeviceProp_t p; return hipGetDeviceProperties(&p, 0) == hipSuccess ? p.multiProcessorCount : 256; }();
+        const int64_t want = (sc.nchunks + 15) / 16;
+        const unsigned grid = (unsigned)(want < ncu ? want : ncu);
+        hipError_t e = hipFuncSetAttribute((const void *)k_stream_rank1_ldsvec<false, true>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((k_stream_rank1_ldsvec<false, true>), dim3(grid), dim3(1024), lds_bytes, st,
+                           (const int32_t *)nullptr, c2, vals, (const int32_t *)sc.chunk_run_base->ptr,
+                           (const int32_t *)nullptr, v, dense_rows, yv, sc.nnz, sc.nchunks, scratch, c0, c1, y0, y1);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        return run_fixup(scratch, sc.nchunks, 1, nullptr, yv, max_run / kChunk + 2, st);
+    }
     hipLaunchKernelGGL(k_stream_rank1_coo, dim3((unsigned)sc.ntiles), dim3(256), 0, st, c0, c1, c2, vals,
                        (const int32_t *)sc.run_base->ptr, v, y0, y1, yv, sc.nnz, sc.ntiles, scratch);
-    return run_fixup(scratch, sc.ntiles, 1, nullptr, yv, sc.max_seg_len > 0 ? sc.max_seg_len / kTile + 2 : 0, st);
+    return run_fixup(scratch, sc.ntiles, 1, nullptr, yv, max_run / kTile + 2, st);
 }
 
 hipError_t stream_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t *crd1, int64_t nslice,

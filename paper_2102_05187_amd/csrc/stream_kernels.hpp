@@ -27,7 +27,7 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
 
 // Sorted COO [CN,S,S]: one output (i, j, value) per run of equal (c0, c1).
 hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *c1, const int32_t *c2,
-                          const double *vals, const double *v, int32_t *y0, int32_t *y1, double *yv,
+                          const double *vals, const double *v, int64_t dense_rows, int32_t *y0, int32_t *y1, double *yv,
                           void *scratch, hipStream_t st);
 
 // M[crd1[s], :] = sum_{f in slice s} B[crd2[f], :] * (sum_{p in fiber f} vals[p] * C[crd3[p], :]).

@@ -58,6 +58,7 @@ struct Schedule {
     DevRef  run_base;      // int32 [ntiles + 1]   (COO3 only)
     int64_t nruns = 0;     // COO3: number of distinct (i,j) pairs
     DevRef  chunk_seg_begin;   // int32 [nchunks + 1]: seg_begin at kChunk granularity
+    DevRef  chunk_run_base;    // int32 [nchunks + 1]: run_base at kChunk granularity (COO3 only)
     int64_t nchunks = 0;
     int64_t empty_segments = -1;  // leaf segments without a nonzero (-1 = unknown)
     int64_t max_seg_len = 0;      // longest leaf segment, in nonzeros (0 = unknown)
