@@ -57,10 +57,33 @@ def count_distinct(t):
     return int(torch.unique(t).numel())
 
 
-def roofline(bytes_per_launch, ms):
+_TRAFFIC = None
+
+
+def measured_traffic(op):
+    """HBM bytes of one call (fetch + write) from the committed rocprofv3 counter summary, or None.
+
+    The counters cannot be read from inside this process; profiles/hbm_traffic.json holds what
+    `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` measured for this same command at full size."""
+    global _TRAFFIC
+    if _TRAFFIC is None:
+        try:
+            with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+                _TRAFFIC = json.load(f).get("ops", {})
+        except (OSError, ValueError):
+            _TRAFFIC = {}
+    e = _TRAFFIC.get(op)
+    return None if e is None else int(e["fetch_bytes"]) + int(e["write_bytes"])
+
+
+def roofline(bytes_per_launch, ms, op=None, full_size=True):
     gbs = bytes_per_launch / (ms * 1e-3) / 1e9
-    return {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None, "bytes_per_launch": int(bytes_per_launch)}
+    traffic = measured_traffic(op) if (op and full_size) else None
+    out = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+           "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic, "bytes_per_launch": int(bytes_per_launch)}
+    if traffic is not None:
+        out["traffic_gbs"] = round(traffic / (ms * 1e-3) / 1e9, 1)
+    return out
 
 
 def run_op(op, args, comet, dev):
@@ -167,7 +190,7 @@ def run_op(op, args, comet, dev):
     ms = tm["mean_ms"]
     entry = {"workload": desc, "ms": round(ms, 5), "median_ms": round(tm["median_ms"], 5),
              "min_ms": round(tm["min_ms"], 5), "gflops": round(flops / (ms * 1e-3) / 1e9, 2), "flops": int(flops),
-             "roofline": roofline(nbytes, ms), "setup_s": round(gen_s, 2), **extra}
+             "roofline": roofline(nbytes, ms, op, args.scale == 1.0 and not args.identity_ranks), "setup_s": round(gen_s, 2), **extra}
     log("[bench] %-9s %s: %.4f ms/step  %.1f GFLOP/s  %.1f GB/s (%.1f%% of 8 TB/s)  [setup %.1fs]" % (
         op, desc, ms, entry["gflops"], entry["roofline"]["achieved"], 100 * entry["roofline"]["frac"], gen_s))
     return entry, keep
