@@ -474,14 +474,20 @@ comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *
     const double *B = factors[1], *C = factors[2];
     if (!B || !C) return COMET_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
-    // rows of M whose index is not stored at the root level receive no contribution
-    HIP_TRY(comet::fill_zero_f64(M, X->dims[0] * R, st));
+    const int64_t nslice = X->pos_len[1] - 1;
+    const bool tiled = X->nvals > 0 &&
+                       use_tiled(X, R, B, X->dims[1] > X->dims[2] ? X->dims[1] : X->dims[2]) && aligned16(C) &&
+                       comet::stream_mttkrp_supports_rank(R);
+    // Rows of M whose index is not stored at the root level receive no contribution.  The tiled kernel
+    // writes every stored slice's row itself (a slice without nonzeros is cleared in its slice pass), so
+    // when most rows are stored only the gaps between them are cleared; otherwise all of M is.
+    if (tiled && nslice * 2 >= X->dims[0]) HIP_TRY(comet::zero_unstored_rows(X->crd_i(0), nslice, X->dims[0], R, M, st));
+    else HIP_TRY(comet::fill_zero_f64(M, X->dims[0] * R, st));
     if (X->nvals == 0) return COMET_OK;
-    if (use_tiled(X, R, B, X->dims[1] > X->dims[2] ? X->dims[1] : X->dims[2]) && aligned16(C) &&
-        comet::stream_mttkrp_supports_rank(R)) {
+    if (tiled) {
         comet_status rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.ntiles, R));
         if (rs != COMET_OK) return rs;
-        HIP_TRY(comet::stream_mttkrp(X->sched, X->pos_i(1), X->crd_i(0), X->pos_len[1] - 1, X->pos_i(2), X->crd_i(1),
+        HIP_TRY(comet::stream_mttkrp(X->sched, X->pos_i(1), X->crd_i(0), nslice, X->pos_i(2), X->crd_i(1),
                                      X->crd_i(2), X->vals_d(), B, C, R, M, X->scratch->ptr, st));
         return COMET_OK;
     }

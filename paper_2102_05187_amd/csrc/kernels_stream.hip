@@ -806,6 +806,10 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
             if (e > b) { il = (int64_t)e - 1; break; }
         }
         if (il >= tb && il < te) tm[il - tb] = crd1[sl];
+        if (il < 0) {                                             // a stored slice without any nonzero: its row is zero
+            double *row = M + (int64_t)crd1[sl] * R;
+            for (int r = 0; r < R; ++r) row[r] = 0.0;
+        }
     }
     __syncthreads();
 

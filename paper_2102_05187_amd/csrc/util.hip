@@ -271,4 +271,24 @@ hipError_t count_empty_segments(const int32_t *pos, int64_t nseg, int32_t *out_c
     return hipGetLastError();
 }
 
+// Clears the rows of a dense [nrows x R] result whose index is not stored in the sorted list idx[0..n):
+// row ranges (idx[s-1], idx[s]) for s = 0..n (with idx[-1] = -1 and idx[n] = nrows).  One thread per
+// (gap, 16-byte piece); gaps are short when most rows are stored, which is the case this serves.
+__global__ void __launch_bounds__(256) k_zero_unstored_rows(const int32_t *__restrict__ idx, int64_t n, int64_t nrows,
+                                                            int R, double *__restrict__ out) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; s <= n; s += stride) {
+        const int64_t lo = s == 0 ? 0 : (int64_t)idx[s - 1] + 1;
+        const int64_t hi = s == n ? nrows : (int64_t)idx[s];
+        for (int64_t p = lo * R; p < hi * R; ++p) out[p] = 0.0;
+    }
+}
+
+hipError_t zero_unstored_rows(const int32_t *idx, int64_t n, int64_t nrows, int64_t R, double *out, hipStream_t st) {
+    int64_t want = (n + 1 + 255) / 256;
+    unsigned grid = (unsigned)(want > 4096 ? 4096 : want);
+    hipLaunchKernelGGL(k_zero_unstored_rows, dim3(grid), dim3(256), 0, st, idx, n, nrows, (int)R, out);
+    return hipGetLastError();
+}
+
 }  // namespace comet

@@ -312,3 +312,33 @@ def test_copy_flag_detaches_from_caller_arrays(comet):
     y2 = comet.comet_spmv(A, x)
     torch.cuda.synchronize()
     assert torch.equal(y1, y2)
+
+
+def test_empty_slices_and_fibers_are_accepted_and_contribute_nothing(comet):
+    """A stored slice without fibers and a stored fiber without nonzeros (reading R19): the level walker
+    reaches every value exactly once, TTV keeps one (zero) value for the empty fiber, MTTKRP leaves the
+    rows of the empty slice and of the unstored index at zero."""
+    dims = (4, 3, 5)
+    tags = [1, 1, 1]
+    pos = [np.array([0, 3], np.int32), np.array([0, 2, 2, 3], np.int32), np.array([0, 2, 2, 4], np.int32)]
+    crd = [np.array([0, 1, 3], np.int32), np.array([0, 2, 1], np.int32), np.array([1, 3, 0, 4], np.int32)]
+    vals = np.array([1.5, -2.0, 0.25, 4.0])
+    coords, seen = oracle.walk(tags, pos, crd, 4)
+    assert np.all(seen == 1)
+    X = comet.comet_tensor_create(dims, tags, [torch.from_numpy(p).cuda() for p in pos],
+                                  [torch.from_numpy(c).cuda() for c in crd], torch.from_numpy(vals).cuda())
+    v = gen.dense_operand(9, 0, (5,))
+    B, C = gen.dense_operand(9, 1, (3, 16)), gen.dense_operand(9, 2, (5, 16))
+    for variant in VARIANTS:
+        X.set_variant(variant)
+        Y = comet.comet_ttv(X, 2, dev(v))
+        M = torch.full((4, 16), float("nan"), dtype=torch.float64, device="cuda")
+        comet.comet_mttkrp(X, 0, [None, dev(B), dev(C)], M)
+        torch.cuda.synchronize()
+        ref = oracle.ttv(coords[:, 0], coords[:, 1], coords[:, 2], vals, dims, np_(v))
+        got = np_(Y.vals())
+        assert got.shape == (3,) and got[1] == 0.0                      # the empty fiber (0, 2)
+        assert_values_close(got[[0, 2]], ref["vals"], ref["abs"], "ttv with an empty fiber")
+        refM, absM = oracle.mttkrp(coords[:, 0], coords[:, 1], coords[:, 2], vals, dims, np_(B), np_(C))
+        assert_values_close(np_(M), refM, absM, "mttkrp with an empty slice")
+        assert bool((M[1] == 0).all()) and bool((M[2] == 0).all())
