@@ -3,20 +3,27 @@
 // Work is cut by nonzeros, not by rows: tile t owns leaf positions [t*kTile, (t+1)*kTile), whatever
 // segments (rows / fibers / slices) they belong to, so a power-law head segment is spread over many
 // workgroups -- load imbalance across rows is what the paper names as the main source of slowdown
-// (Section 8.3).  Inside a tile each wavefront streams a contiguous quarter with wide coalesced
-// loads and reduces it with a segmented scan; the per-level access rule is the compressed-unique
-// one of Table "Generated code to access nonzeros coordinates" (segment s owns positions
-// pos[s]..pos[s+1]-1, coordinate crd[p], value vals[p]).
+// (Section 8.3).  The per-level access rule is the compressed-unique one of Table "Generated code to
+// access nonzeros coordinates" (segment s owns positions pos[s]..pos[s+1]-1, coordinate crd[p], value
+// vals[p]); sorted coordinate lists use the compressed-nonunique / singleton rule (one coordinate per
+// position, a segment = a run of equal leading coordinates).
 //
-// Segment ends are marked in an LDS map: ts[i] = id of the segment whose LAST nonzero is tile item
-// i, else -1.  A unit of work (lane, wavefront, tile) summarises its item range as
+// Segment ends are marked in LDS (a map ts[i] = id of the segment whose LAST nonzero is tile item i,
+// else -1; or a bit mask when ids can be counted).  A unit of work (lane or lane group, wavefront,
+// tile) summarises its item range as
 //     has_tail    a segment ends inside the range
 //     first       sum of the items up to and including the first segment end   (+ its segment id)
 //     open        sum of the items after the last segment end (all items if there is none)
 // and two adjacent summaries combine associatively; a segment that closes at the boundary of two
 // units is final once the left unit contains a segment end.  Tile summaries go to a carry buffer
-// and a second small kernel finishes the segments cut by tile boundaries in a fixed order, so the
+// and small follow-up kernels finish the segments cut by tile boundaries in a fixed order, so the
 // results do not depend on scheduling (no atomics).
+//
+// Kernels:  k_stream_rank1_ldsvec  rank 1, dense vector staged in LDS, one wavefront per 1024-item chunk
+//           k_stream_rank1[_coo]   rank 1, vector gathered through L1, tail-id map per 4096-item tile
+//           k_stream_rankR         rank R, lane groups walk item runs, per-item records in LDS
+//           k_stream_mttkrp        rank R, two nested segment levels (fibers inside slices)
+//           k_fixup_level / k_stream_fixup   carry resolution
 #include <cstdlib>
 
 #include "stream_kernels.hpp"
