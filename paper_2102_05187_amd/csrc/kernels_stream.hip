@@ -47,6 +47,18 @@ __device__ __forceinline__ double dpp_d(double old, double v) {
     int hi = __builtin_amdgcn_update_dpp(__double2hiint(old), __double2hiint(v), CTRL, ROW_MASK, 0xf, false);
     return __hiloint2double(hi, lo);
 }
+// Same with every row and bank enabled and zero fill for lanes that have no source (bound_ctrl): the
+// result does not depend on a previous register value, so no identity has to be materialised first.
+template <int CTRL>
+__device__ __forceinline__ int dpp0_i(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp0_d(double v) {
+    int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, true);
+    int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
 __device__ __forceinline__ double readlane_d(double v, int lane) {
     int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
     int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
@@ -56,6 +68,13 @@ __device__ __forceinline__ double readlane_d(double v, int lane) {
 // Inclusive segmented scan over the 64 lanes.  Element = (f, v); combine(left, right) =
 // (left.f | right.f, right.f ? right.v : left.v + right.v): a flagged element cuts the running sum.
 __device__ __forceinline__ void segscan_inclusive(int &f, double &v) {
+#define COMET_SCAN_STEP0(CTRL)                            \
+    {                                                     \
+        int nf = dpp0_i<CTRL>(f);                         \
+        double nv = dpp0_d<CTRL>(v);                      \
+        v = f ? v : nv + v;                               \
+        f |= nf;                                          \
+    }
 #define COMET_SCAN_STEP(CTRL, RM)                         \
     {                                                     \
         int nf = dpp_i<CTRL, RM>(0, f);                   \
@@ -63,12 +82,13 @@ __device__ __forceinline__ void segscan_inclusive(int &f, double &v) {
         v = f ? v : nv + v;                               \
         f |= nf;                                          \
     }
-    COMET_SCAN_STEP(0x111, 0xf)   // row_shr:1
-    COMET_SCAN_STEP(0x112, 0xf)   // row_shr:2
-    COMET_SCAN_STEP(0x114, 0xf)   // row_shr:4
-    COMET_SCAN_STEP(0x118, 0xf)   // row_shr:8
+    COMET_SCAN_STEP0(0x111)       // row_shr:1
+    COMET_SCAN_STEP0(0x112)       // row_shr:2
+    COMET_SCAN_STEP0(0x114)       // row_shr:4
+    COMET_SCAN_STEP0(0x118)       // row_shr:8
     COMET_SCAN_STEP(0x142, 0xa)   // row_bcast:15 into rows 1 and 3
     COMET_SCAN_STEP(0x143, 0xc)   // row_bcast:31 into rows 2 and 3
+#undef COMET_SCAN_STEP0
 #undef COMET_SCAN_STEP
 }
 
@@ -171,8 +191,8 @@ __device__ __forceinline__ void rank1_process_half(const Rank1Half &h, const dou
         double sv = open;
         segscan_inclusive(sf, sv);
         // exclusive value for this lane = carry (+) inclusive value of the previous lane
-        const int pf = dpp_i<0x138, 0xf>(0, sf);             // wave_shr:1, lane 0 keeps the identity
-        const double pv = dpp_d<0x138, 0xf>(0.0, sv);
+        const int pf = dpp0_i<0x138>(sf);                    // wave_shr:1, lane 0 gets the identity (0, 0.0)
+        const double pv = dpp0_d<0x138>(sv);
         const int ef = cy.cf | pf;
         const double ev = pf ? pv : cy.cv + pv;
         if (f) {
@@ -1004,6 +1024,14 @@ hipError_t run_fixup(void *scratch, int64_t ntiles, int R, const int32_t *rowmap
 
 }  // namespace
 
+// Allows a kernel to use up to the whole 160 KB of LDS as dynamic shared memory; done once per kernel
+// (it is not a stream operation, but calling it once keeps it out of captured regions after the first call).
+template <auto Kernel>
+static hipError_t allow_full_lds() {
+    static hipError_t status = hipFuncSetAttribute((const void *)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    return status;
+}
+
 // Lane-group width of the rank-R kernels: 8 by default; COMET_LANES=4 selects the quad mapping
 // (for measurements).  Ranks up to 8 always use quads.
 static int lanes_per_item(int64_t R) {
@@ -1077,13 +1105,13 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
             const unsigned grid = (unsigned)(want < ncu ? want : ncu);
             const int32_t *csb = (const int32_t *)sc.chunk_seg_begin->ptr;
             if (rowmap) {
-                e = hipFuncSetAttribute((const void *)k_stream_rank1_ldsvec<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                e = allow_full_lds<k_stream_rank1_ldsvec<true, false>>();
                 if (e != hipSuccess) return e;
                 hipLaunchKernelGGL((k_stream_rank1_ldsvec<true, false>), dim3(grid), dim3(1024), lds_bytes, st, pos, crd, vals,
                                    csb, rowmap, Dn, dense_rows, out, sc.nnz, sc.nchunks, scratch, (const int32_t *)nullptr,
                                    (const int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr);
             } else {
-                e = hipFuncSetAttribute((const void *)k_stream_rank1_ldsvec<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+                e = allow_full_lds<k_stream_rank1_ldsvec<false, false>>();
                 if (e != hipSuccess) return e;
                 hipLaunchKernelGGL((k_stream_rank1_ldsvec<false, false>), dim3(grid), dim3(1024), lds_bytes, st, pos, crd, vals,
                                    csb, rowmap, Dn, dense_rows, out, sc.nnz, sc.nchunks, scratch, (const int32_t *)nullptr,
@@ -1118,8 +1146,7 @@ hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *
         static int ncu = [] { hipDeviceProp_t p; return hipGetDeviceProperties(&p, 0) == hipSuccess ? p.multiProcessorCount : 256; }();
         const int64_t want = (sc.nchunks + 15) / 16;
         const unsigned grid = (unsigned)(want < ncu ? want : ncu);
-        hipError_t e = hipFuncSetAttribute((const void *)k_stream_rank1_ldsvec<false, true>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        hipError_t e = allow_full_lds<k_stream_rank1_ldsvec<false, true>>();
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL((k_stream_rank1_ldsvec<false, true>), dim3(grid), dim3(1024), lds_bytes, st,
                            (const int32_t *)nullptr, c2, vals, (const int32_t *)sc.chunk_run_base->ptr,
