@@ -15,7 +15,7 @@ from util import assert_index_equal, assert_values_close, np_
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [1, 0]          # 1 = simple kernels, 0 = automatic (tiled where specialised)
+VARIANTS = [1, 2, 0]       # 1 = simple kernels, 2 = tiled wherever specialised, 0 = the library's own choice
 
 
 @pytest.fixture(scope="module")
