@@ -26,7 +26,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-ALL_OPS = ["spmm", "spmv", "ttv", "ttv_coo", "ttm", "mttkrp16", "mttkrp64"]
+ALL_OPS = ["spmm", "spmv", "ttv", "ttv_coo", "ttm", "mttkrp16", "mttkrp64", "ttv_m0", "ttm_m0", "mttkrp16_m1"]
+# "<op>_m<n>": the same operation along / for mode n of the same tensor, on the storage that
+# comet_tensor_reorder builds for it (first-mode TTV and TTM are the forms Section 8.2 writes out)
 
 
 def log(*a):
@@ -181,6 +183,9 @@ def run_op(op, args, comet, dev):
         extra = {"nnz": nnz, "rows": n, "R": R, "touched_B_rows": touched, "gather_bytes": 8 * R * nnz}
         keep = dict(A=A, L=L, B=B, C=C, coo=(rows, cols, vals), n=n)
     else:
+        full_op, mode_n = op, None
+        if "_m" in op:
+            op, mode_n = op.split("_m")[0], int(op.split("_m")[1])
         R = {"ttv": 1, "ttv_coo": 1, "ttm": 16, "mttkrp16": 16, "mttkrp64": 64}[op]
         kw = {"permute": not args.identity_ranks}
         if op.startswith("ttv"):
@@ -202,33 +207,53 @@ def run_op(op, args, comet, dev):
         del i, j, k
         X = comet.from_levels(L).set_variant(args.variant)
         extra = {"nnz": nnz, "nfib": nfib, "n1": n1, "dims": list(dims), "R": R, "draws": c["info"]["draws"]}
+        # level order of the storage the operation runs on, and the mode it contracts / produces
+        if mode_n is None:
+            order, mode = (0, 1, 2), (0 if op.startswith("mttkrp") else 2)
+        else:
+            rest = [m for m in range(3) if m != mode_n]
+            order, mode = ((mode_n, *rest) if op.startswith("mttkrp") else (*rest, mode_n)), mode_n
+            t0 = time.perf_counter()
+            Xr = comet.comet_tensor_reorder(X, order).set_variant(args.variant)
+            torch.cuda.synchronize()
+            extra["reorder_s"] = round(time.perf_counter() - t0, 4)
+            touched_k = count_distinct(Xr.crd(2))
+            nfib, n1 = int(Xr.crd(1).numel()), int(Xr.crd(0).numel())
+            extra.update(nfib=nfib, n1=n1, level_order=list(order))
+            keep["X0"], X = X, Xr
+        ld = [dims[m] for m in order]           # sizes per level
+        where = "%s, levels hold modes %s" % ("x".join(map(str, dims)), "".join(str(m + 1) for m in order))
         if op in ("ttv", "ttv_coo"):
-            v = c["v"]
-            Y = comet.comet_ttv(X, 2, v)
-            fn = lambda: comet.comet_ttv(X, 2, v, Y)
+            v = c["v"] if mode_n is None else gen.dense_operand(0, 8, (ld[2],), dev)
+            Y = comet.comet_ttv(X, mode, v)
+            fn = lambda: comet.comet_ttv(X, mode, v, Y)
             flops = 2 * nnz
             nbytes = (12 if op == "ttv" else 20) * nnz + 16 * nfib + 8 * touched_k
-            desc = "TTV %s %s, %d nnz, %d fibers, Zipf(1.3)" % ("CSF" if op == "ttv" else "COO", "x".join(map(str, dims)), nnz, nfib)
-            keep = dict(X=X, L=L, v=v, Y=Y)
+            desc = "TTV mode %d %s %s, %d nnz, %d fibers, Zipf(1.3)" % (mode + 1, "CSF" if op == "ttv" else "COO", where, nnz, nfib)
+            keep.update(X=X, L=L, v=v, Y=Y)
         elif op == "ttm":
-            U = c["U"]
-            Y = comet.comet_ttm(X, 2, U)
-            fn = lambda: comet.comet_ttm(X, 2, U, Y)
+            U = c["U"] if mode_n is None else gen.dense_operand(0, 8, (ld[2], R), dev)
+            Y = comet.comet_ttm(X, mode, U)
+            fn = lambda: comet.comet_ttm(X, mode, U, Y)
             flops = 2 * R * nnz
             nbytes = 12 * nnz + (8 + 8 * R) * nfib + 8 * R * touched_k
-            desc = "TTM CSF %s, %d nnz, %d fibers, U %dx%d" % ("x".join(map(str, dims)), nnz, nfib, dims[2], R)
+            desc = "TTM mode %d CSF %s, %d nnz, %d fibers, U %dx%d" % (mode + 1, where, nnz, nfib, ld[2], R)
             extra["gather_bytes"] = 8 * R * nnz
-            keep = dict(X=X, L=L, U=U, Y=Y)
+            keep.update(X=X, L=L, U=U, Y=Y)
         else:
-            Bf, Cf = c["B"], c["C"]
-            M = torch.empty((dims[0], R), dtype=torch.float64, device=dev)
-            fn = lambda: comet.comet_mttkrp(X, 0, [None, Bf, Cf], M)
-            touched_j = count_distinct(L.crd[1])
+            if mode_n is None:
+                fs = [None, c["B"], c["C"]]
+            else:
+                fs = [None if m == mode else gen.dense_operand(0, 8 + m, (dims[m], R), dev) for m in range(3)]
+            M = torch.empty((ld[0], R), dtype=torch.float64, device=dev)
+            fn = lambda: comet.comet_mttkrp(X, mode, fs, M)
+            touched_j = count_distinct(L.crd[1]) if mode_n is None else count_distinct(X.crd(1))
             flops = 2 * R * (nnz + nfib)
-            nbytes = 12 * nnz + 8 * nfib + 8 * n1 + 8 * R * (touched_j + touched_k + dims[0])
-            desc = "MTTKRP mode-1 CSF %s, %d nnz, %d fibers, %d slices, R=%d" % ("x".join(map(str, dims)), nnz, nfib, n1, R)
+            nbytes = 12 * nnz + 8 * nfib + 8 * n1 + 8 * R * (touched_j + touched_k + ld[0])
+            desc = "MTTKRP mode %d CSF %s, %d nnz, %d fibers, %d slices, R=%d" % (mode + 1, where, nnz, nfib, n1, R)
             extra["gather_bytes"] = 8 * R * (nnz + nfib)
-            keep = dict(X=X, L=L, B=Bf, C=Cf, M=M)
+            keep.update(X=X, L=L, fs=fs, M=M)
+        op = full_op
     torch.cuda.synchronize()
     gen_s = time.perf_counter() - t_gen
     steps = args.steps

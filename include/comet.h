@@ -71,6 +71,9 @@ typedef struct {
     int64_t        crd_len[COMET_MAX_ORDER];
     const double  *vals;                      /* device pointer                                 */
     int64_t        nvals;
+    int32_t        mode_of_level[COMET_MAX_ORDER];  /* tensor mode stored at each level: 0,1,2,..
+                                                 * unless comet_tensor_reorder chose another order;
+                                                 * dims / levels / pos / crd above are per LEVEL    */
 } comet_tensor_info_t;
 
 /*
@@ -115,6 +118,33 @@ comet_status comet_tensor_destroy(comet_tensor *t);
  * stay valid until the handle is destroyed. */
 comet_status comet_tensor_info(const comet_tensor *t, comet_tensor_info_t *info);
 
+/*
+ * Store X again with its modes in another level order, every level compressed-unique
+ * ([CU,CU] for order 2, [CU,CU,CU] for order 3).  Section 4 ties each level to one mode and the
+ * operations below contract (TTV, TTM) the mode of the LAST level or produce (MTTKRP) the mode of
+ * the FIRST level, so this call is how the other modes are reached -- e.g. the first-mode TTV / TTM
+ * that Section 8.2 writes out need the order {1, 2, 0}.  It also converts: an (even unsorted)
+ * coordinate list [CN,S(,S)] or a CSR / DCSR matrix comes back as sorted CSF / DCSR, and the order
+ * {1, 0} transposes a matrix.
+ *
+ *   X           handle of format [D,CU], [CU,CU], [CN,S], [CN,S,S] or [CU,CU,CU]; for a coordinate
+ *               list the nonzeros may come in any order (create it without COMET_VALIDATE).
+ *   mode_order  host, [order]; a permutation of X's modes: level l of the result stores mode
+ *               mode_order[l] of the tensor (modes are numbered as in the tensor X was first
+ *               created from, also when X itself is a reordered handle).
+ *   out         host; receives a new handle that owns all its arrays (nothing is shared with X) and
+ *               reports the order in comet_tensor_info_t::mode_of_level.  Its dims are per level.
+ *
+ * Work: one key/value radix sort of the nonzeros on the device plus a few streaming passes;
+ * temporary device memory of about 40 bytes per nonzero.  Synchronises with `stream`.
+ * Errors: COMET_ERR_INVALID_ARG if mode_order is not a permutation; COMET_ERR_UNSUPPORTED if the
+ * bit widths of the mode sizes add up to more than 64 or the format is not listed above;
+ * COMET_ERR_BAD_FORMAT if two nonzeros have the same coordinates (coordinates out of range are not
+ * detected here: use COMET_VALIDATE at creation for sorted input).
+ */
+comet_status comet_tensor_reorder(const comet_tensor *X, const int32_t *mode_order, comet_tensor **out,
+                                  void *stream);
+
 /* SpMV, y = A x :  y_i = sum_j a_ij x_j   (Section 8.2, SpMV).
  *   A   order-2 handle, [D,CU] or [CU,CU].
  *   x   device, [dims[1]].          y   device, [dims[0]]; every entry is overwritten
@@ -129,9 +159,11 @@ comet_status comet_spmm(const comet_tensor *A, const double *B, int64_t R, doubl
 
 /* SpTTV, Y = X x_mode v :  y_ij = sum_k x_ijk v_k   (Section 8.2, SpTTV).
  *   X     order-3 handle, [CU,CU,CU] or sorted [CN,S,S].
- *   mode  contracted mode; must be 2 (the mode stored in the last level), else
- *         COMET_ERR_UNSUPPORTED.
- *   v     device, [dims[2]].
+ *   mode  contracted mode (0, 1 or 2, numbered as in the original tensor); it must be the mode
+ *         stored in the last level -- 2 unless the handle comes from comet_tensor_reorder -- else
+ *         COMET_ERR_UNSUPPORTED.  Section 8.2's first-mode product y_jk = sum_i x_ijk v_i is
+ *         comet_ttv(reorder(X, {1,2,0}), 0, v).
+ *   v     device, [size of the contracted mode].
  *   Y     host; *Y must be NULL or a handle returned earlier by this call for the same X.
  *         On return *Y is an order-2 sparse result with the uncontracted levels of X:
  *         [CU,CU] whose pos/crd are X's level-0/1 arrays (shared, not copied) for CSF input,
@@ -141,8 +173,8 @@ comet_status comet_ttv(const comet_tensor *X, int mode, const double *v, comet_t
 
 /* SpTTM, Y = X x_mode U :  y_ijr = sum_k x_ijk u_kr   (Section 8.2, SpTTM; R takes the place
  * of the contracted mode).
- *   X     order-3 handle, [CU,CU,CU].      mode  must be 2.
- *   U     device, [dims[2] x R] row-major, 1 <= R <= 1024.
+ *   X     order-3 handle, [CU,CU,CU].      mode  as for comet_ttv (the mode of the last level).
+ *   U     device, [size of the contracted mode x R] row-major, 1 <= R <= 1024.
  *   Y     as for comet_ttv; the result is [CU,CU,D] with dims (I, J, R): levels 0/1 shared
  *         with X, a dense last level of size R, vals of [#fibers x R] row-major. */
 comet_status comet_ttm(const comet_tensor *X, int mode, const double *U, int64_t R,
@@ -151,10 +183,14 @@ comet_status comet_ttm(const comet_tensor *X, int mode, const double *U, int64_t
 /* MTTKRP, M = X_(mode) (C (.) B) :  m_ir = sum_jk x_ijk b_jr c_kr.  The paper names the operation
  * (Section 8.3) without defining it; this is the usual definition with the output indexed by
  * the mode stored in the root level.
- *   X        order-3 handle, [CU,CU,CU].   mode  must be 0.
- *   factors  host array of 3 device pointers; factors[1] = B [dims[1] x R], factors[2] = C
- *            [dims[2] x R], row-major; factors[mode] is ignored.
- *   M        device, [dims[0] x R] row-major, overwritten (rows without a stored slice = 0). */
+ *   X        order-3 handle, [CU,CU,CU].
+ *   mode     output mode (numbered as in the original tensor); must be the mode stored in the root
+ *            level -- 0 unless the handle comes from comet_tensor_reorder, e.g. {1,0,2} for mode 1
+ *            -- else COMET_ERR_UNSUPPORTED.
+ *   factors  host array of 3 device pointers indexed by MODE: factors[m] is the [size of mode m x R]
+ *            row-major factor of mode m; factors[mode] is ignored.
+ *   M        device, [size of mode `mode` x R] row-major, overwritten (rows without a stored
+ *            slice = 0). */
 comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *factors,
                           int64_t R, double *M, void *stream);
 

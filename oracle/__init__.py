@@ -138,6 +138,35 @@ def mttkrp(ci, cj, ck, vals, dims: Sequence[int], B, C) -> Tuple[np.ndarray, np.
     return M, Ma
 
 
+# ---- any mode (Section 8.2 writes TTV / TTM for a general mode n and spells out n = 1) -----------------
+# Only the roles of the coordinate arrays change: the contracted (or, for MTTKRP, the output) mode
+# takes the place the functions above give to their fixed mode, the other two keep their order.
+def _other_modes(mode: int) -> Tuple[int, int]:
+    assert mode in (0, 1, 2)
+    a, b = [m for m in range(3) if m != mode]
+    return a, b
+
+
+def ttv_mode(coords, vals, dims: Sequence[int], mode: int, v) -> Dict[str, np.ndarray]:
+    """Y = X x_mode v: the sum runs over mode `mode` (0-based); the output lists the distinct
+    coordinate pairs of the two remaining modes (in their original order), lexicographically."""
+    a, b = _other_modes(mode)
+    return ttv(coords[a], coords[b], coords[mode], vals, (dims[a], dims[b], dims[mode]), v)
+
+
+def ttm_mode(coords, vals, dims: Sequence[int], mode: int, U) -> Dict[str, np.ndarray]:
+    """Y = X x_mode U with U of shape (dims[mode], R): R values per distinct pair of the other modes."""
+    a, b = _other_modes(mode)
+    return ttm(coords[a], coords[b], coords[mode], vals, (dims[a], dims[b], dims[mode]), U)
+
+
+def mttkrp_mode(coords, vals, dims: Sequence[int], mode: int, factors) -> Tuple[np.ndarray, np.ndarray]:
+    """M(i_mode, r) = sum over the other two modes of X(i0,i1,i2) * F_a(i_a, r) * F_b(i_b, r),
+    factors indexed by mode (factors[mode] unused); returns (M, A) of shape (dims[mode], R)."""
+    a, b = _other_modes(mode)
+    return mttkrp(coords[mode], coords[a], coords[b], vals, (dims[mode], dims[a], dims[b]), factors[a], factors[b])
+
+
 def walk(tags: Sequence[int], pos: Sequence[Optional[np.ndarray]], crd: Sequence[Optional[np.ndarray]],
          nvals: int) -> Tuple[np.ndarray, np.ndarray]:
     """Expand per-level storage to coordinates: (coords[nvals, order], times each value was reached)."""

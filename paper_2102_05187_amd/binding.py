@@ -26,7 +26,8 @@ _STATUS_NAMES = {0: "COMET_OK", 1: "COMET_ERR_INVALID_ARG", 2: "COMET_ERR_BAD_FO
                  4: "COMET_ERR_UNSUPPORTED", 5: "COMET_ERR_ALLOC", 6: "COMET_ERR_DEVICE"}
 
 EXPORTS = ["comet_tensor_create", "comet_tensor_destroy", "comet_tensor_info", "comet_spmv", "comet_spmm",
-           "comet_ttv", "comet_ttm", "comet_mttkrp", "comet_status_string", "comet_tensor_set_variant"]
+           "comet_ttv", "comet_ttm", "comet_mttkrp", "comet_status_string", "comet_tensor_set_variant",
+           "comet_tensor_reorder"]
 
 
 class CometError(RuntimeError):
@@ -45,7 +46,8 @@ class _Info(ctypes.Structure):
                 ("crd", ctypes.c_void_p * COMET_MAX_ORDER),
                 ("crd_len", ctypes.c_int64 * COMET_MAX_ORDER),
                 ("vals", ctypes.c_void_p),
-                ("nvals", ctypes.c_int64)]
+                ("nvals", ctypes.c_int64),
+                ("mode_of_level", ctypes.c_int32 * COMET_MAX_ORDER)]
 
 
 _LIB = None
@@ -68,6 +70,7 @@ def _lib():
         lib.comet_ttm.argtypes = [vp, ci, vp, i64, ctypes.POINTER(vp), vp]
         lib.comet_mttkrp.argtypes = [vp, ci, vp, i64, vp, vp]
         lib.comet_tensor_set_variant.argtypes = [vp, ci]
+        lib.comet_tensor_reorder.argtypes = [vp, vp, ctypes.POINTER(vp), vp]
         lib.comet_status_string.argtypes = [ci]
         lib.comet_status_string.restype = ctypes.c_char_p
         for n in EXPORTS:
@@ -143,6 +146,18 @@ class Tensor:
         inf = self.info()
         return [int(inf.dims[l]) for l in range(inf.order)]
 
+    def mode_of_level(self) -> List[int]:
+        inf = self.info()
+        return [int(inf.mode_of_level[l]) for l in range(inf.order)]
+
+    def mode_dims(self) -> List[int]:
+        """Sizes indexed by tensor mode (dims() is indexed by level)."""
+        inf = self.info()
+        out = [0] * inf.order
+        for l in range(inf.order):
+            out[int(inf.mode_of_level[l])] = int(inf.dims[l])
+        return out
+
     def pos(self, l: int) -> Optional[torch.Tensor]:
         inf = self.info()
         return None if inf.pos_len[l] == 0 else self._wrap(inf.pos[l], inf.pos_len[l], "<i4", torch.int32)
@@ -201,6 +216,16 @@ def comet_tensor_destroy(t: Tensor):
     t.destroy()
 
 
+def comet_tensor_reorder(X: Tensor, mode_order: Sequence[int], stream=None) -> Tensor:
+    order = len(X.dims())
+    if len(mode_order) != order:
+        raise CometError(1, "comet_tensor_reorder")
+    c_order = (ctypes.c_int32 * order)(*[int(m) for m in mode_order])
+    out = ctypes.c_void_p(None)
+    _check(_lib().comet_tensor_reorder(X.handle, c_order, ctypes.byref(out), _stream(stream)), "comet_tensor_reorder")
+    return Tensor(out.value)
+
+
 def comet_spmv(A: Tensor, x: torch.Tensor, y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     x = _dev(x, torch.float64, "x")
     if len(A.dims()) != 2:
@@ -236,7 +261,7 @@ def comet_spmm(A: Tensor, B: torch.Tensor, C: Optional[torch.Tensor] = None, str
 
 def comet_ttv(X: Tensor, mode: int, v: torch.Tensor, Y: Optional[Tensor] = None, stream=None) -> Tensor:
     v = _dev(v, torch.float64, "v")
-    dims = X.dims()
+    dims = X.mode_dims()
     if len(dims) != 3:
         raise CometError(4, "comet_ttv")
     if 0 <= mode < 3 and v.numel() != dims[mode]:
@@ -248,7 +273,7 @@ def comet_ttv(X: Tensor, mode: int, v: torch.Tensor, Y: Optional[Tensor] = None,
 
 def comet_ttm(X: Tensor, mode: int, U: torch.Tensor, Y: Optional[Tensor] = None, stream=None) -> Tensor:
     U = _dev(U, torch.float64, "U")
-    dims = X.dims()
+    dims = X.mode_dims()
     if len(dims) != 3:
         raise CometError(4, "comet_ttm")
     if U.dim() != 2 or (0 <= mode < 3 and U.shape[0] != dims[mode]):
@@ -260,7 +285,7 @@ def comet_ttm(X: Tensor, mode: int, U: torch.Tensor, Y: Optional[Tensor] = None,
 
 def comet_mttkrp(X: Tensor, mode: int, factors: Sequence[Optional[torch.Tensor]],
                  M: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    dims = X.dims()
+    dims = X.mode_dims()
     if len(dims) != 3 or len(factors) != 3:
         raise CometError(4, "comet_mttkrp")
     fs = [None if (f is None or l == mode) else _dev(f, torch.float64, "factors[%d]" % l) for l, f in enumerate(factors)]

@@ -332,6 +332,7 @@ comet_status comet_tensor_info(const comet_tensor *t, comet_tensor_info_t *info)
     for (int l = 0; l < t->order; ++l) {
         info->dims[l] = t->dims[l];
         info->levels[l] = t->levels[l];
+        info->mode_of_level[l] = t->mode_of_level[l];
         info->pos[l] = t->pos_len[l] ? t->pos_i(l) : nullptr;
         info->pos_len[l] = t->pos_len[l];
         info->crd[l] = t->crd_len[l] ? t->crd_i(l) : nullptr;
@@ -345,6 +346,137 @@ comet_status comet_tensor_info(const comet_tensor *t, comet_tensor_info_t *info)
 comet_status comet_tensor_set_variant(comet_tensor *t, int variant) {
     if (!t || variant < 0 || variant > 2) return COMET_ERR_INVALID_ARG;
     t->variant = variant;
+    return COMET_OK;
+}
+
+// ---- re-storing with another mode order ----------------------------------------------------------
+static int bit_width(int64_t dim) {
+    int b = 1;
+    while (b < 63 && (int64_t(1) << b) < dim) ++b;
+    return b;
+}
+
+comet_status comet_tensor_reorder(const comet_tensor *X, const int32_t *mode_order, comet_tensor **out,
+                                  void *stream) {
+    if (!out) return COMET_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!X || !mode_order) return COMET_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const int order = X->order;
+    comet::CoordSource src;
+    switch (X->fmt) {
+    case Format::CSR:  src.kind = comet::CoordSource::kCsr; break;
+    case Format::DCSR: src.kind = comet::CoordSource::kDcsr; break;
+    case Format::COO2: case Format::COO3: src.kind = comet::CoordSource::kCoo; break;
+    case Format::CSF3: src.kind = comet::CoordSource::kCsf3; break;
+    default: return COMET_ERR_UNSUPPORTED;
+    }
+    src.order = order;
+    src.nnz = X->nvals;
+    for (int l = 0; l < order; ++l) {
+        src.pos[l] = X->pos_i(l); src.npos[l] = (int32_t)X->pos_len[l]; src.crd[l] = X->crd_i(l);
+    }
+    comet::KeyLayout lay;
+    bool used[COMET_MAX_ORDER] = {false, false, false, false};
+    int bits[3] = {0, 0, 0}, total_bits = 0;
+    for (int l = 0; l < order; ++l) {
+        int s = -1;
+        for (int q = 0; q < order; ++q) if (X->mode_of_level[q] == mode_order[l]) s = q;
+        if (s < 0 || used[s]) return COMET_ERR_INVALID_ARG;     // not a permutation of the modes
+        used[s] = true;
+        lay.src_level[l] = s;
+        bits[l] = bit_width(X->dims[s]);
+        total_bits += bits[l];
+    }
+    if (total_bits > 64) return COMET_ERR_UNSUPPORTED;           // the packed coordinate must fit one key
+    for (int l = order - 1, sh = 0; l >= 0; --l) {
+        lay.shift[l] = sh;
+        lay.mask[l] = bits[l] >= 64 ? ~uint64_t(0) : (uint64_t(1) << bits[l]) - 1;
+        sh += bits[l];
+    }
+
+    comet_tensor *t = new (std::nothrow) comet_tensor();
+    if (!t) return COMET_ERR_ALLOC;
+    std::unique_ptr<comet_tensor> guard(t);
+    t->order = order;
+    t->nvals = X->nvals;
+    for (int l = 0; l < order; ++l) {
+        t->dims[l] = X->dims[lay.src_level[l]];
+        t->levels[l] = COMET_CU;
+        t->mode_of_level[l] = mode_order[l];
+    }
+    t->fmt = classify(order, t->levels);
+
+    const int64_t n = X->nvals;
+    int64_t nmid = 0, nroot = 0;        // order 3: #(root,middle) prefixes and #root coordinates; order 2: nroot only
+    DevRef keys, flags, before;
+    if (n > 0) {
+        DevRef raw = comet::dev_alloc(sizeof(uint64_t) * n);
+        keys = comet::dev_alloc(sizeof(uint64_t) * n);
+        t->vals = comet::dev_alloc(sizeof(double) * n);
+        flags = comet::dev_alloc(sizeof(uint64_t) * n);
+        before = comet::dev_alloc(sizeof(uint64_t) * n);
+        DevRef err = comet::dev_alloc(sizeof(int32_t));
+        if (!raw || !keys || !t->vals || !flags || !before || !err) return COMET_ERR_ALLOC;
+        HIP_TRY(comet::reorder_pack_keys(src, lay, (uint64_t *)raw->ptr, st));
+        size_t tb = 0;
+        HIP_TRY(comet::reorder_sort_pairs(nullptr, &tb, (const uint64_t *)raw->ptr, (uint64_t *)keys->ptr, X->vals_d(),
+                                          (double *)t->vals->ptr, n, total_bits, st));
+        DevRef temp = comet::dev_alloc(tb);
+        if (!temp) return COMET_ERR_ALLOC;
+        HIP_TRY(comet::reorder_sort_pairs(temp->ptr, &tb, (const uint64_t *)raw->ptr, (uint64_t *)keys->ptr, X->vals_d(),
+                                          (double *)t->vals->ptr, n, total_bits, st));
+        HIP_TRY(hipMemsetAsync(err->ptr, 0, sizeof(int32_t), st));
+        HIP_TRY(comet::reorder_mark_heads((const uint64_t *)keys->ptr, n, lay, order, (uint64_t *)flags->ptr,
+                                          (int32_t *)err->ptr, st));
+        size_t sb = 0;
+        HIP_TRY(comet::reorder_scan_flags(nullptr, &sb, (const uint64_t *)flags->ptr, (uint64_t *)before->ptr, n, st));
+        HIP_TRY(hipStreamSynchronize(st));      // the sort is done with `temp` before it is replaced
+        temp = comet::dev_alloc(sb);
+        if (!temp) return COMET_ERR_ALLOC;
+        HIP_TRY(comet::reorder_scan_flags(temp->ptr, &sb, (const uint64_t *)flags->ptr, (uint64_t *)before->ptr, n, st));
+        uint64_t last[2] = {0, 0};
+        int32_t dup = 0;
+        HIP_TRY(hipMemcpyAsync(&last[0], (const uint64_t *)before->ptr + (n - 1), sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipMemcpyAsync(&last[1], (const uint64_t *)flags->ptr + (n - 1), sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipMemcpyAsync(&dup, err->ptr, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        if (dup) return COMET_ERR_BAD_FORMAT;   // one coordinate stored more than once
+        const uint64_t tot = last[0] + last[1];
+        if (order == 3) { nmid = (int64_t)(tot & 0xffffffffu); nroot = (int64_t)(tot >> 32); }
+        else nroot = (int64_t)(tot & 0xffffffffu);
+    } else {
+        t->vals = comet::dev_alloc(16);
+        if (!t->vals) return COMET_ERR_ALLOC;
+    }
+
+    // -- the new levels ---------------------------------------------------------------------------
+    const int64_t count[3] = {nroot, order == 3 ? nmid : n, n};   // positions per level (order 2 uses [0], [1])
+    comet::CuLevels lv;
+    for (int l = 0; l < order; ++l) {
+        const int64_t parents = l == 0 ? 1 : count[l - 1];
+        t->pos_len[l] = parents + 1;
+        t->crd_len[l] = count[l];
+        t->pos[l] = comet::dev_alloc(sizeof(int32_t) * t->pos_len[l]);
+        t->crd[l] = comet::dev_alloc(sizeof(int32_t) * t->crd_len[l]);
+        if (!t->pos[l] || !t->crd[l]) return COMET_ERR_ALLOC;
+        lv.pos[l] = (int32_t *)t->pos[l]->ptr;
+        lv.crd[l] = (int32_t *)t->crd[l]->ptr;
+    }
+    {
+        int32_t h[2] = {0, (int32_t)nroot};
+        HIP_TRY(hipMemcpyAsync(lv.pos[0], h, sizeof h, hipMemcpyHostToDevice, st));
+        HIP_TRY(hipStreamSynchronize(st));
+    }
+    if (n > 0) {
+        HIP_TRY(comet::reorder_cut_levels((const uint64_t *)keys->ptr, (const uint64_t *)flags->ptr,
+                                          (const uint64_t *)before->ptr, n, lay, order, lv, st));
+    } else {
+        for (int l = 1; l < order; ++l) HIP_TRY(hipMemsetAsync(lv.pos[l], 0, sizeof(int32_t), st));
+    }
+    comet_status rs = build_schedule(*t, st);   // synchronises: the temporaries above may go
+    if (rs != COMET_OK) return rs;
+    *out = guard.release();
     return COMET_OK;
 }
 
@@ -392,7 +524,8 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
     if (R < 1 || R > 1024) return COMET_ERR_UNSUPPORTED;
     const bool csf = X->fmt == Format::CSF3, coo = X->fmt == Format::COO3;
     if (!csf && !(coo && kind == 1)) return COMET_ERR_UNSUPPORTED;
-    if (mode != 2) return mode >= 0 && mode < 3 ? COMET_ERR_UNSUPPORTED : COMET_ERR_INVALID_ARG;
+    if (mode < 0 || mode >= 3) return COMET_ERR_INVALID_ARG;
+    if (mode != X->mode_of_level[2]) return COMET_ERR_UNSUPPORTED;   // re-store with comet_tensor_reorder first
     bool fresh = false;
     comet_status rs = result_handle(X, kind, R, Y, &fresh);
     if (rs != COMET_OK) return rs;
@@ -403,6 +536,7 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
     if (fresh) {
         y->order = kind == 1 ? 2 : 3;
         y->dims[0] = X->dims[0]; y->dims[1] = X->dims[1];
+        for (int l = 0; l < 3; ++l) y->mode_of_level[l] = X->mode_of_level[l];
         if (csf) {
             y->levels[0] = COMET_CU; y->levels[1] = COMET_CU;
             for (int l = 0; l < 2; ++l) {
@@ -479,9 +613,11 @@ comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *
                           void *stream) {
     if (!X || !factors || !M) return COMET_ERR_INVALID_ARG;
     if (X->fmt != Format::CSF3) return COMET_ERR_UNSUPPORTED;
-    if (mode != 0) return mode >= 0 && mode < 3 ? COMET_ERR_UNSUPPORTED : COMET_ERR_INVALID_ARG;
+    if (mode < 0 || mode >= 3) return COMET_ERR_INVALID_ARG;
+    if (mode != X->mode_of_level[0]) return COMET_ERR_UNSUPPORTED;   // re-store with comet_tensor_reorder first
     if (R < 1 || R > 1024) return COMET_ERR_UNSUPPORTED;
-    const double *B = factors[1], *C = factors[2];
+    // B belongs to the mode of the middle level, C to the mode of the last level
+    const double *B = factors[X->mode_of_level[1]], *C = factors[X->mode_of_level[2]];
     if (!B || !C) return COMET_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     const int64_t nslice = X->pos_len[1] - 1;

@@ -48,4 +48,40 @@ hipError_t simple_ttv_coo(const int32_t *c0, const int32_t *c1, const int32_t *c
                           int64_t nnz, int tile, int64_t ntiles, const int32_t *run_base, const double *v,
                           int32_t *ycrd0, int32_t *ycrd1, double *yvals, hipStream_t st);
 
+// ---- mode reordering (reorder.hip) ------------------------------------------------------------
+// Where the coordinates of nonzero p of the source tensor come from.
+struct CoordSource {
+    enum Kind { kCsr, kDcsr, kCoo, kCsf3 };
+    int kind = kCoo;
+    int order = 0;
+    int64_t nnz = 0;
+    const int32_t *pos[3] = {nullptr, nullptr, nullptr};
+    int32_t npos[3] = {0, 0, 0};
+    const int32_t *crd[3] = {nullptr, nullptr, nullptr};
+};
+// 64-bit sort key: new level l takes the coordinate of source level src_level[l], shifted left by
+// shift[l] (shift of the last level is 0) and at most mask[l].
+struct KeyLayout {
+    int src_level[3] = {0, 1, 2};
+    int shift[3] = {0, 0, 0};
+    uint64_t mask[3] = {0, 0, 0};
+};
+// Output arrays of the all-compressed-unique storage (pos[0] = {0, #root} is written by the host).
+struct CuLevels {
+    int32_t *pos[3] = {nullptr, nullptr, nullptr};
+    int32_t *crd[3] = {nullptr, nullptr, nullptr};
+};
+hipError_t reorder_pack_keys(const CoordSource &src, const KeyLayout &lay, uint64_t *keys, hipStream_t st);
+// Both follow the two-call convention: temp == nullptr only sets *temp_bytes.
+hipError_t reorder_sort_pairs(void *temp, size_t *temp_bytes, const uint64_t *keys_in, uint64_t *keys_out,
+                              const double *vals_in, double *vals_out, int64_t n, int key_bits, hipStream_t st);
+hipError_t reorder_scan_flags(void *temp, size_t *temp_bytes, const uint64_t *flags, uint64_t *before, int64_t n,
+                              hipStream_t st);
+// flags: low half counts new (root, middle) prefixes (new rows for order 2), high half new root
+// coordinates (order 3).  *err |= 1 if two nonzeros share all coordinates.
+hipError_t reorder_mark_heads(const uint64_t *keys, int64_t n, const KeyLayout &lay, int order, uint64_t *flags,
+                              int32_t *err, hipStream_t st);
+hipError_t reorder_cut_levels(const uint64_t *keys, const uint64_t *flags, const uint64_t *before, int64_t n,
+                              const KeyLayout &lay, int order, const CuLevels &out, hipStream_t st);
+
 }  // namespace comet

@@ -1,0 +1,159 @@
+// Re-storing a tensor with its modes in another level order (all levels compressed-unique).
+//
+// The contractions walk the level tree from the root, so the contracted mode of TTV / TTM has to sit
+// in the last level and the output mode of MTTKRP in the first (paper Section 8.2 defines TTV and TTM
+// for the first mode; Section 4 fixes that level l stores one mode).  This file builds the storage
+// for any mode order on the device: expand every nonzero to its coordinates, pack them into one
+// 64-bit key in the new order, radix-sort (key, value) pairs, and cut the sorted list into the
+// pos / crd arrays of the new levels.  None of it is on the timed path of an operation.
+#include <cstring>
+
+#include <rocprim/rocprim.hpp>
+
+#include "kernels.hpp"
+
+namespace comet {
+
+namespace {
+
+inline unsigned blocks_for(int64_t n, int per_block) {
+    int64_t b = (n + per_block - 1) / per_block;
+    return (unsigned)(b < 1 ? 1 : b);
+}
+
+// Largest s in [0, n) with pos[s] <= p, for a non-decreasing pos[0..n] with pos[0] <= p < pos[n].
+__device__ inline int32_t owner_of(const int32_t *__restrict__ pos, int32_t n, int32_t p) {
+    int32_t lo = 0, hi = n;              // invariant: pos[lo] <= p < pos[hi]
+    while (hi - lo > 1) {
+        int32_t mid = lo + ((hi - lo) >> 1);
+        if (pos[mid] <= p) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ void __launch_bounds__(256) k_pack_keys(CoordSource src, KeyLayout lay, uint64_t *__restrict__ keys) {
+    int64_t p64 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p64 >= src.nnz) return;
+    int32_t p = (int32_t)p64;
+    uint64_t c[3] = {0, 0, 0};
+    switch (src.kind) {
+    case CoordSource::kCsr:
+        c[0] = (uint64_t)owner_of(src.pos[1], src.npos[1] - 1, p);
+        c[1] = (uint64_t)src.crd[1][p];
+        break;
+    case CoordSource::kDcsr:
+        c[0] = (uint64_t)src.crd[0][owner_of(src.pos[1], src.npos[1] - 1, p)];
+        c[1] = (uint64_t)src.crd[1][p];
+        break;
+    case CoordSource::kCoo:
+        for (int l = 0; l < src.order; ++l) c[l] = (uint64_t)src.crd[l][p];
+        break;
+    case CoordSource::kCsf3: {
+        int32_t f = owner_of(src.pos[2], src.npos[2] - 1, p);
+        int32_t s = owner_of(src.pos[1], src.npos[1] - 1, f);
+        c[0] = (uint64_t)src.crd[0][s];
+        c[1] = (uint64_t)src.crd[1][f];
+        c[2] = (uint64_t)src.crd[2][p];
+        break;
+    }
+    }
+    uint64_t key = 0;
+    for (int l = 0; l < src.order; ++l) key |= c[lay.src_level[l]] << lay.shift[l];
+    keys[p] = key;
+}
+
+// flags[p] = (first nonzero of a new root coordinate ? 1 << 32 : 0) | (first nonzero of a new
+// (root, middle) prefix ? 1 : 0); for order 2 only the low half is used (new row).  Equal
+// neighbouring keys mean one coordinate stored twice: *err is set.
+__global__ void __launch_bounds__(256) k_mark_heads(const uint64_t *__restrict__ keys, int64_t n, KeyLayout lay,
+                                                    int order, uint64_t *__restrict__ flags, int32_t *err) {
+    int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p >= n) return;
+    uint64_t k = keys[p];
+    uint64_t f;
+    if (p == 0) {
+        f = order == 3 ? ((uint64_t(1) << 32) | 1u) : 1u;
+    } else {
+        uint64_t q = keys[p - 1];
+        if (q == k) atomicOr(err, 1);
+        if (order == 3) {
+            bool root = (k >> lay.shift[0]) != (q >> lay.shift[0]);
+            bool mid  = (k >> lay.shift[1]) != (q >> lay.shift[1]);
+            f = (root ? (uint64_t(1) << 32) : 0) | (mid ? 1u : 0u);
+        } else {
+            f = (k >> lay.shift[0]) != (q >> lay.shift[0]) ? 1u : 0u;
+        }
+    }
+    flags[p] = f;
+}
+
+// `before[p]` = exclusive prefix sum of flags.  Writes the new levels (see CuLevels).
+__global__ void __launch_bounds__(256) k_cut_levels(const uint64_t *__restrict__ keys, const uint64_t *__restrict__ flags,
+                                                    const uint64_t *__restrict__ before, int64_t n, KeyLayout lay,
+                                                    int order, CuLevels out) {
+    int64_t p64 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p64 >= n) return;
+    const int32_t p = (int32_t)p64;
+    const uint64_t k = keys[p], f = flags[p], b = before[p];
+    const int32_t lo = (int32_t)(b & 0xffffffffu), hi = (int32_t)(b >> 32);
+    const int leaf = order - 1;
+    out.crd[leaf][p] = (int32_t)(k & lay.mask[leaf]);
+    if (order == 3) {
+        if (f & 1u) {
+            out.crd[1][lo] = (int32_t)((k >> lay.shift[1]) & lay.mask[1]);
+            out.pos[2][lo] = p;
+        }
+        if (f >> 32) {
+            out.crd[0][hi] = (int32_t)(k >> lay.shift[0]);
+            out.pos[1][hi] = lo;
+        }
+        if (p64 == n - 1) {
+            int32_t nmid = lo + (int32_t)(f & 1u), nroot = hi + (int32_t)(f >> 32);
+            out.pos[2][nmid] = (int32_t)n;
+            out.pos[1][nroot] = nmid;
+        }
+    } else {
+        if (f & 1u) {
+            out.crd[0][lo] = (int32_t)(k >> lay.shift[0]);
+            out.pos[1][lo] = p;
+        }
+        if (p64 == n - 1) out.pos[1][lo + (int32_t)(f & 1u)] = (int32_t)n;
+    }
+}
+
+}  // namespace
+
+hipError_t reorder_pack_keys(const CoordSource &src, const KeyLayout &lay, uint64_t *keys, hipStream_t st) {
+    if (src.nnz <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_pack_keys, dim3(blocks_for(src.nnz, 256)), dim3(256), 0, st, src, lay, keys);
+    return hipGetLastError();
+}
+
+hipError_t reorder_sort_pairs(void *temp, size_t *temp_bytes, const uint64_t *keys_in, uint64_t *keys_out,
+                              const double *vals_in, double *vals_out, int64_t n, int key_bits, hipStream_t st) {
+    return rocprim::radix_sort_pairs(temp, *temp_bytes, keys_in, keys_out, vals_in, vals_out, (size_t)n, 0u,
+                                     (unsigned)key_bits, st);
+}
+
+hipError_t reorder_mark_heads(const uint64_t *keys, int64_t n, const KeyLayout &lay, int order, uint64_t *flags,
+                              int32_t *err, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_mark_heads, dim3(blocks_for(n, 256)), dim3(256), 0, st, keys, n, lay, order, flags, err);
+    return hipGetLastError();
+}
+
+hipError_t reorder_scan_flags(void *temp, size_t *temp_bytes, const uint64_t *flags, uint64_t *before, int64_t n,
+                              hipStream_t st) {
+    return rocprim::exclusive_scan(temp, *temp_bytes, flags, before, uint64_t(0), (size_t)n,
+                                   rocprim::plus<uint64_t>(), st);
+}
+
+hipError_t reorder_cut_levels(const uint64_t *keys, const uint64_t *flags, const uint64_t *before, int64_t n,
+                              const KeyLayout &lay, int order, const CuLevels &out, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_cut_levels, dim3(blocks_for(n, 256)), dim3(256), 0, st, keys, flags, before, n, lay, order,
+                       out);
+    return hipGetLastError();
+}
+
+}  // namespace comet

@@ -71,6 +71,7 @@ struct comet_tensor {
     int32_t order = 0;
     int64_t dims[COMET_MAX_ORDER] = {0, 0, 0, 0};
     int32_t levels[COMET_MAX_ORDER] = {0, 0, 0, 0};
+    int32_t mode_of_level[COMET_MAX_ORDER] = {0, 1, 2, 3};   // tensor mode stored at each level
     comet::DevRef pos[COMET_MAX_ORDER], crd[COMET_MAX_ORDER], vals;
     int64_t pos_len[COMET_MAX_ORDER] = {0, 0, 0, 0};
     int64_t crd_len[COMET_MAX_ORDER] = {0, 0, 0, 0};

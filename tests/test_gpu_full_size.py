@@ -159,3 +159,50 @@ def test_mttkrp_config(comet, R):
     stored[L.crd[0].to(torch.int64)] = True
     assert bool((M[~stored] == 0.0).all())
     assert not bool(torch.isnan(M).any())
+
+
+def _expand_csf(T):
+    """Coordinates per level of every nonzero of a [CU,CU,CU] handle (torch index work only)."""
+    pos2, pos3 = T.pos(1).to(torch.int64), T.pos(2).to(torch.int64)
+    fib_of_nnz = torch.repeat_interleave(torch.arange(pos3.numel() - 1, device=DEV), pos3[1:] - pos3[:-1])
+    slice_of_fib = torch.repeat_interleave(torch.arange(pos2.numel() - 1, device=DEV), pos2[1:] - pos2[:-1])
+    c1 = T.crd(1).to(torch.int64)[fib_of_nnz]
+    c0 = T.crd(0).to(torch.int64)[slice_of_fib][fib_of_nnz]
+    return c0, c1, T.crd(2).to(torch.int64), fib_of_nnz
+
+
+def test_first_mode_ttv_config(comet, ttv_config):
+    """Section 8.2 writes TTV for the first mode: y_jk = sum_i x_ijk v_i.  The tensor is re-stored in
+    the order (1, 2, 0) on the device, checked as a whole against a sort of the packed coordinates,
+    then contracted; sampled output fibers against the oracle."""
+    c = ttv_config
+    i, j, k, vals = c["coo"]
+    dims = c["dims"]
+    L = fmt.pack_csf3(dims, i, j, k, vals)
+    X = comet.from_levels(L)
+    say("first-mode ttv full size nnz=%d" % vals.numel())
+    Xr = comet.comet_tensor_reorder(X, (1, 2, 0))
+    torch.cuda.synchronize()
+    assert Xr.mode_of_level() == [1, 2, 0] and Xr.dims() == [dims[1], dims[2], dims[0]]
+    # whole-structure check: the walked coordinates are the original ones sorted by (j, k, i)
+    key = (j * dims[2] + k) * dims[0] + i
+    skey, perm = torch.sort(key)
+    assert bool((skey[1:] > skey[:-1]).all())
+    c0, c1, c2, fib_of_nnz = _expand_csf(Xr)
+    assert torch.equal((c0 * dims[2] + c1) * dims[0] + c2, skey)
+    assert torch.equal(Xr.vals(), vals[perm])
+    pos2 = Xr.pos(1).to(torch.int64)
+    assert bool((pos2[1:] > pos2[:-1]).all())            # no empty slices or fibers are produced
+    del key, skey, perm
+    v = gen.dense_operand(0, 7, (dims[0],), DEV)
+    Y = comet.comet_ttv(Xr, 0, v)
+    torch.cuda.synchronize()
+    pos3 = Xr.pos(2).to(torch.int64)
+    lens = pos3[1:] - pos3[:-1]
+    heavy = torch.topk(lens, 4).indices.cpu()
+    fids = sample_ids(lens.numel(), 4000, heavy, 6)
+    idx, which = ranges_to_index(pos3[fids], pos3[fids + 1])
+    # oracle on the nonzeros of the sampled (j,k) fibers, in the original mode numbering
+    ref = oracle.ttv_mode((np_(c2[idx]), np_(c0[idx]), np_(c1[idx])), np_(Xr.vals()[idx]), dims, 0, np_(v))
+    assert len(ref["vals"]) == fids.numel()
+    assert_values_close(np_(Y.vals()[fids]), ref["vals"], ref["abs"], "first-mode ttv sampled fibers")

@@ -119,6 +119,31 @@ def test_tensor_ops_match_exact_dense_brute_force(density, dims):
     _assert_tight(M, brute_mttkrp(Xd, B, U), Ma)
 
 
+@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("dims", [(3, 4, 5), (6, 2, 7)])
+def test_any_mode_ops_match_exact_dense_brute_force(mode, dims):
+    """Mode-n TTV / TTM / MTTKRP against the literal sums on the dense array with the contracted
+    (output) axis moved to the place the mode-3 (mode-1) brute force expects it."""
+    seed = 40 + mode + dims[0]
+    coords = tuple(np_(t) for t in gen.bernoulli_tensor3(dims, 0.4, seed))
+    vals, coords = coords[3], coords[:3]
+    Xd = _dense_from_coo(dims, coords, vals)
+    F = [np_(gen.dense_operand(seed, m, (dims[m], 3))) for m in range(3)]
+    a, b = [m for m in range(3) if m != mode]
+    full = brute_ttm(np.moveaxis(Xd, mode, 2), F[mode])          # indexed (i_a, i_b, r)
+    Y = oracle.ttm_mode(coords, vals, dims, mode, F[mode])
+    pairs = sorted(set(zip(coords[a].tolist(), coords[b].tolist())))
+    assert list(zip(Y["i"].tolist(), Y["j"].tolist())) == pairs
+    for g, (x, y) in enumerate(pairs):
+        _assert_tight(Y["vals"][g], full[x, y], Y["abs"][g])
+    yv = oracle.ttv_mode(coords, vals, dims, mode, F[mode][:, 1])
+    assert list(zip(yv["i"].tolist(), yv["j"].tolist())) == pairs
+    for g, (x, y) in enumerate(pairs):
+        _assert_tight(yv["vals"][g], full[x, y, 1], yv["abs"][g])
+    M, Ma = oracle.mttkrp_mode(coords, vals, dims, mode, F)
+    _assert_tight(M, brute_mttkrp(np.moveaxis(Xd, mode, 0), F[a], F[b]), Ma)
+
+
 # ------------------------------------------------------------------------------------------
 # hand-worked example
 # ------------------------------------------------------------------------------------------
