@@ -334,7 +334,7 @@ __global__ void __launch_bounds__(1024) k_stream_rank1_ldsvec(const int32_t *__r
         const int64_t cbeg = c * kChunk;
         int base_id;
         if constexpr (COO) {
-            constexpr int kRows = kChunk / 64;
+            constexpr int kRows = kChunk / 64, kBatch = 4;
             unsigned long long hm[kRows], hx[kRows];     // run starts; the same with items past the end counted as starts
             const int runs_before = chunk_begin[c];
             // all coordinate loads of the chunk are issued together; the predecessor of an item comes from the
@@ -345,16 +345,16 @@ __global__ void __launch_bounds__(1024) k_stream_rank1_ldsvec(const int32_t *__r
             if (inext < nnz) { after0 = c0[inext]; after1 = c1[inext]; }
             int running = runs_before;
 #pragma unroll
-            for (int rb = 0; rb < kRows; rb += 8) {               // two batches of 8 rows keep the register count down
-                int a0[8], a1[8];
+            for (int rb = 0; rb < kRows; rb += kBatch) {          // batches of rows keep the register count down
+                int a0[kBatch], a1[kBatch];
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
+                for (int q = 0; q < kBatch; ++q) {
                     const int64_t i = cbeg + 64 * (rb + q) + lane;
                     a0[q] = i < nnz ? c0[i] : -1;
                     a1[q] = i < nnz ? c1[i] : -1;
                 }
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
+                for (int q = 0; q < kBatch; ++q) {
                     const int r = rb + q;
                     const int64_t i = cbeg + 64 * r + lane;
                     const int p0 = dpp_i<0x138, 0xf>(before0, a0[q]);
