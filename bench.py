@@ -180,7 +180,8 @@ def run_op(op, args, comet, dev):
         flops = 2 * R * nnz
         nbytes = 12 * nnz + (4 + 8 * R) * n + 8 * R * touched
         desc = "SpMM CSR %dx%d, %d nnz, Zipf(1.8) rows capped at 10000, B %dx%d" % (n, n, nnz, n, R)
-        extra = {"nnz": nnz, "rows": n, "R": R, "touched_B_rows": touched, "gather_bytes": 8 * R * nnz}
+        extra = {"nnz": nnz, "rows": n, "R": R, "touched_B_rows": touched, "gather_bytes": 8 * R * nnz,
+                 "touched_row_bytes": 8 * R * touched}
         keep = dict(A=A, L=L, B=B, C=C, coo=(rows, cols, vals), n=n)
     else:
         full_op, mode_n = op, None
@@ -239,6 +240,7 @@ def run_op(op, args, comet, dev):
             nbytes = 12 * nnz + (8 + 8 * R) * nfib + 8 * R * touched_k
             desc = "TTM mode %d CSF %s, %d nnz, %d fibers, U %dx%d" % (mode + 1, where, nnz, nfib, ld[2], R)
             extra["gather_bytes"] = 8 * R * nnz
+            extra["touched_row_bytes"] = 8 * R * touched_k
             keep.update(X=X, L=L, U=U, Y=Y)
         else:
             if mode_n is None:
@@ -252,6 +254,7 @@ def run_op(op, args, comet, dev):
             nbytes = 12 * nnz + 8 * nfib + 8 * n1 + 8 * R * (touched_j + touched_k + ld[0])
             desc = "MTTKRP mode %d CSF %s, %d nnz, %d fibers, %d slices, R=%d" % (mode + 1, where, nnz, nfib, n1, R)
             extra["gather_bytes"] = 8 * R * (nnz + nfib)
+            extra["touched_row_bytes"] = 8 * R * (touched_j + touched_k)
             keep.update(X=X, L=L, fs=fs, M=M)
         op = full_op
     torch.cuda.synchronize()
@@ -261,6 +264,11 @@ def run_op(op, args, comet, dev):
     ms = tm["mean_ms"]
     if op == "spmv":
         extra.update(small_problem_latency(fn, keep["y"], dev))
+    if "gather_bytes" in extra:
+        # second roofline: every operand-row gather counted as HBM traffic (no cache reuse at all) instead of
+        # each touched row once -- the upper bracket of what the call has to move
+        streamed = nbytes - extra.get("touched_row_bytes", 0)
+        extra["roofline_no_reuse"] = roofline(streamed + extra["gather_bytes"], ms)
     entry = {"workload": desc, "ms": round(ms, 5), "median_ms": round(tm["median_ms"], 5),
              "min_ms": round(tm["min_ms"], 5), "gflops": round(flops / (ms * 1e-3) / 1e9, 2), "flops": int(flops),
              "roofline": roofline(nbytes, ms, op, args.scale == 1.0 and not args.identity_ranks), "setup_s": round(gen_s, 2), **extra}
