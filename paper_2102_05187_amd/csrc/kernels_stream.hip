@@ -845,43 +845,34 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
     double facc[V], sacc[V], first[V];
 #pragma unroll
     for (int q = 0; q < V; ++q) { facc[q] = 0.0; sacc[q] = 0.0; first[q] = 0.0; }
-    int ht = 0, first_row = -1, first_pos = -1, last_is_tail = 1;     // first_pos: walker-relative item of the first fiber end
-    const unsigned rowbytes = (unsigned)R * 8u, slot = lane_slot_bytes<L, WIDE>(j);
+    int ht = 0, first_row = -1, first_fid = -1, last_is_tail = 1;
 
     constexpr int G = StepGroup<V>::value, NG = SB / G;
     for (int sb = 0; sb < WI / SB; ++sb) {
         const int64_t i0 = gb + SB * sb + 4 * j;
         LaneItems nxt;
         if (sb + 1 < WI / SB) lane_load_items(nxt, crd3, vals, i0 + SB, nnz);
-        int tl[4], tr[4];
+        int tl[4], tr[4], jb[4];
         {
             const int4 t4 = *reinterpret_cast<const int4 *>(ts + (i0 - tb));
             const int4 m4 = *reinterpret_cast<const int4 *>(tm + (i0 - tb));
             tl[0] = t4.x; tl[1] = t4.y; tl[2] = t4.z; tl[3] = t4.w;
             tr[0] = m4.x; tr[1] = m4.y; tr[2] = m4.z; tr[3] = m4.w;
         }
-        // Per item, before anything is broadcast: the byte offset of its C row with two flag bits in
-        // the (always zero) low bits -- 1: a fiber ends here, 2: a slice ends here -- and the byte
-        // offset of the B row of the fiber that ends here.  After the broadcast a gather address is
-        // one 32-bit add away from the operand's base.
-        unsigned coff[4], boff[4];
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            coff[s] = (unsigned)cur.cr[s] * rowbytes | (tl[s] >= 0 ? 1u : 0u) | (tr[s] >= 0 ? 2u : 0u);
-            boff[s] = tl[s] >= 0 ? (unsigned)crd2[tl[s]] * rowbytes : 0u;
-        }
+        for (int s = 0; s < 4; ++s) jb[s] = tl[s] >= 0 ? crd2[tl[s]] : 0;      // B row of a fiber that ends here
         const bool any_item = gb + SB * sb < nnz;
         RowBuf<V> cbuf[2][G], bbuf[2][G];
         auto issue = [&](auto gc, RowBuf<V> *cb_, RowBuf<V> *bb_) {
             static_for<0, G>([&](auto sc) {
                 constexpr int k = decltype(gc)::value * G + decltype(sc)::value;
                 constexpr int s_ = decltype(sc)::value;
-                const unsigned cf = (unsigned)grp_bcast_i<L, k / 4>((int)coff[k % 4]);
-                cb_[s_].tail = (int)(cf & 3u);
-                grp_load_row_off<L, V, WIDE>(Cm, (cf & ~7u) + slot, R, j, cb_[s_].d);
-                if (cf & 1u) {                                    // the fiber ends here: its B row is needed too
-                    const unsigned bo = (unsigned)grp_bcast_i<L, k / 4>((int)boff[k % 4]);
-                    grp_load_row_off<L, V, WIDE>(Bm, bo + slot, R, j, bb_[s_].d);
+                const int c = grp_bcast_i<L, k / 4>(cur.cr[k % 4]);
+                grp_load_row<L, V, WIDE>(Cm, c, R, j, cb_[s_].d);
+                const int tf = grp_bcast_i<L, k / 4>(tl[k % 4]);
+                if (tf >= 0) {                                    // the fiber ends here: its B row is needed too
+                    const int jrow = grp_bcast_i<L, k / 4>(jb[k % 4]);
+                    grp_load_row<L, V, WIDE>(Bm, jrow, R, j, bb_[s_].d);
                 }
             });
         };
@@ -890,16 +881,16 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
                 constexpr int k = decltype(gc)::value * G + decltype(sc)::value;
                 constexpr int s_ = decltype(sc)::value;
                 const double a = grp_bcast_d<L, k / 4>(cur.va[k % 4]);
-                const int fl = cb_[s_].tail;
+                const int tf = grp_bcast_i<L, k / 4>(tl[k % 4]);
+                const int tmr = grp_bcast_i<L, k / 4>(tr[k % 4]);
 #pragma unroll
                 for (int q = 0; q < V; ++q) facc[q] = fma(a, cb_[s_].d[q], facc[q]);
-                if (any_item) last_is_tail = fl & 1;
-                if (fl & 1) {
-                    if (first_pos < 0) first_pos = SB * sb + k;
+                if (any_item) last_is_tail = tf >= 0;
+                if (tf >= 0) {
+                    if (first_fid < 0) first_fid = tf;
 #pragma unroll
                     for (int q = 0; q < V; ++q) { sacc[q] = fma(bb_[s_].d[q], facc[q], sacc[q]); facc[q] = 0.0; }
-                    if (fl & 2) {
-                        const int tmr = grp_bcast_i<L, k / 4>(tr[k % 4]);
+                    if (tmr >= 0) {
                         if (!ht) {
 #pragma unroll
                             for (int q = 0; q < V; ++q) first[q] = sacc[q];
@@ -924,7 +915,7 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
 
     // A fiber left open at the end of this walker's range ends at the next fiber end of the tile, or,
     // if there is none, it is the fiber that contains the first nonzero of the next tile.
-    if (j == 0) wfirst_fid[g] = first_pos >= 0 ? ts[gb - tb + first_pos] : -1;
+    if (j == 0) wfirst_fid[g] = first_fid;
     __syncthreads();                                              // also: every walk is done, the maps are dead
     if (!last_is_tail) {
         int64_t fid = seg_begin[t + 1];
