@@ -280,7 +280,7 @@ def run_op(op, args, comet, dev):
     return entry, keep
 
 
-def cpu_baseline_spmm(keep, budget_nnz=6_000_000):
+def cpu_baseline_spmm(keep, budget_nnz=40_000_000):
     """The CPU oracle (single thread, as it stands) on the leading rows of the headline matrix."""
     import numpy as np
     import torch

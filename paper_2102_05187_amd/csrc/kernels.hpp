@@ -9,7 +9,6 @@ namespace comet {
 
 // ---- utilities (util.hip) -----------------------------------------------------------------------
 hipError_t fill_zero_f64(double *p, int64_t n, hipStream_t st);
-hipError_t fill_i32(int32_t *p, int64_t n, int32_t value, hipStream_t st);
 // out[r, :] = 0 for every row r of [0, nrows) that does not occur in the sorted, duplicate-free list idx[0..n).
 hipError_t zero_unstored_rows(const int32_t *idx, int64_t n, int64_t nrows, int64_t R, double *out, hipStream_t st);
 

@@ -30,19 +30,6 @@ hipError_t fill_zero_f64(double *p, int64_t n, hipStream_t st) {
     return hipGetLastError();
 }
 
-__global__ void __launch_bounds__(256) k_fill_i32(int32_t *__restrict__ p, int64_t n, int32_t v) {
-    int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
-}
-
-hipError_t fill_i32(int32_t *p, int64_t n, int32_t value, hipStream_t st) {
-    if (n <= 0) return hipSuccess;
-    int64_t want = (n + 255) / 256;
-    unsigned grid = (unsigned)(want > 4096 ? 4096 : want);
-    hipLaunchKernelGGL(k_fill_i32, dim3(grid), dim3(256), 0, st, p, n, value);
-    return hipGetLastError();
-}
-
 // ---------------------------------------------------------------------------------------------
 // structure checks (bits: 1 pos, 2 range, 4 order inside a CU segment, 8 COO order)
 // ---------------------------------------------------------------------------------------------
