@@ -18,7 +18,10 @@
  *   - Every call returns a comet_status; nothing aborts or throws.  Device faults caused
  *     by arrays that violate the format (and were not validated) are not detected.
  *   - A tensor handle owns per-tensor scratch memory: at most one operation per handle may
- *     be in flight at a time (operations on one stream are ordered and therefore safe).
+ *     be in flight at a time (operations on one stream are ordered and therefore safe).  The
+ *     scratch is allocated by the first operation of a given rank R on the handle (a device
+ *     allocation, so that first call cannot be captured into a HIP graph); later calls with the
+ *     same or a smaller R allocate nothing, clear what they reuse with kernels, and can be captured.
  */
 #ifndef COMET_H
 #define COMET_H

@@ -573,9 +573,12 @@ struct LaneItems {
 __device__ __forceinline__ void lane_load_items(LaneItems &it, const int32_t *__restrict__ crd,
                                                 const double *__restrict__ vals, int64_t i0, int64_t nnz) {
     if (i0 + 3 < nnz) {
-        const int4 c4 = *reinterpret_cast<const int4 *>(crd + i0);
-        const double2 a01 = *reinterpret_cast<const double2 *>(vals + i0);
-        const double2 a23 = *reinterpret_cast<const double2 *>(vals + i0 + 2);
+        // streamed once: non-temporal, so the caches keep the operand rows rather than the nonzeros
+        typedef int v4i __attribute__((ext_vector_type(4)));
+        typedef double v2d __attribute__((ext_vector_type(2)));
+        const v4i c4 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(crd + i0));
+        const v2d a01 = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(vals + i0));
+        const v2d a23 = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(vals + i0 + 2));
         it.cr[0] = c4.x; it.cr[1] = c4.y; it.cr[2] = c4.z; it.cr[3] = c4.w;
         it.va[0] = a01.x; it.va[1] = a01.y; it.va[2] = a23.x; it.va[3] = a23.y;
     } else {

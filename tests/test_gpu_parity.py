@@ -301,6 +301,29 @@ def test_shape_mode_and_rank_errors(comet):
     comet.comet_mttkrp(X, 0, [None, B, C])
 
 
+def test_operations_follow_the_stream_they_are_given(comet):
+    """Work is enqueued on the caller's stream: issued on a side stream behind a long-running fill of the
+    operand, the product must see the filled operand, and the result must be complete once that stream
+    (not the default one) has been waited for."""
+    (n, m), (rows, cols, vals) = MATRIX_CASES["zipf_rows"]
+    A = comet.from_levels(fmt.pack_csr(n, m, rows, cols, vals).to("cuda"))
+    R = 16
+    Bh = gen.dense_operand(31, 0, (m, R))
+    side = torch.cuda.Stream()
+    B = torch.zeros((m, R), dtype=torch.float64, device="cuda")
+    C = torch.full((n, R), float("nan"), dtype=torch.float64, device="cuda")
+    junk = torch.empty(1 << 26, dtype=torch.float64, device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for _ in range(4):
+            junk.fill_(1.0)                      # keeps the side stream busy ahead of the copy
+        B.copy_(dev(Bh), non_blocking=True)
+        comet.comet_spmm(A, B, C)                 # binding passes the current (side) stream
+    side.synchronize()
+    ref, absum = oracle.spmm(np_(rows), np_(cols), np_(vals), (n, m), np_(Bh))
+    assert_values_close(np_(C), ref, absum, "spmm on a side stream")
+
+
 def test_copy_flag_detaches_from_caller_arrays(comet):
     (I, J), (rows, cols, vals) = MATRIX_CASES["config1"]
     L = fmt.pack_csr(I, J, rows, cols, vals).to("cuda")
