@@ -558,6 +558,23 @@ __device__ __forceinline__ void grp_store_row(double *__restrict__ out, int64_t 
     }
 }
 
+// The same for a result row that this kernel does not read again: non-temporal stores.
+template <int L, int V, bool WIDE>
+__device__ __forceinline__ void grp_store_row_stream(double *__restrict__ out, int64_t row, int R, int j, const double *v) {
+    double *p = out + row * R;
+    if constexpr (WIDE) {
+        typedef double v2d __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int q = 0; q < V / 2; ++q) {
+            v2d x; x.x = v[2 * q]; x.y = v[2 * q + 1];
+            __builtin_nontemporal_store(x, reinterpret_cast<v2d *>(p + 2 * L * q + 2 * j));
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < V; ++q) { int r = L * q + j; if (r < R) __builtin_nontemporal_store(v[q], p + r); }
+    }
+}
+
 // compile-time loop: f(IntC<B>{}), ..., f(IntC<E-1>{})
 template <int N> struct IntC { static constexpr int value = N; };
 template <int B, int E, class F>
@@ -733,7 +750,7 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
                         st.ht = 1;
                     } else {
                         const unsigned row = ROWMAP ? (unsigned)rowmap[b.tail] : (unsigned)b.tail;
-                        grp_store_row<L, V, WIDE>(reinterpret_cast<double *>(outb + (size_t)row * R8), 0, R, j, st.acc);
+                        grp_store_row_stream<L, V, WIDE>(reinterpret_cast<double *>(outb + (size_t)row * R8), 0, R, j, st.acc);
                     }
 #pragma unroll
                     for (int q = 0; q < V; ++q) st.acc[q] = 0.0;
