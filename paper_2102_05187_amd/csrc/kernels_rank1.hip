@@ -1,36 +1,11 @@
-// Nonzero-tiled streaming kernels for gfx950 (wave64).
-//
-// Work is cut by nonzeros, not by rows: tile t owns leaf positions [t*kTile, (t+1)*kTile), whatever
-// segments (rows / fibers / slices) they belong to, so a power-law head segment is spread over many
-// workgroups -- load imbalance across rows is what the paper names as the main source of slowdown
-// (Section 8.3).  The per-level access rule is the compressed-unique one of Table "Generated code to
-// access nonzeros coordinates" (segment s owns positions pos[s]..pos[s+1]-1, coordinate crd[p], value
-// vals[p]); sorted coordinate lists use the compressed-nonunique / singleton rule (one coordinate per
-// position, a segment = a run of equal leading coordinates).
-//
-// Segment ends are marked in LDS (a map ts[i] = id of the segment whose LAST nonzero is tile item i,
-// else -1; or a bit mask when ids can be counted).  A unit of work (lane or lane group, wavefront,
-// tile) summarises its item range as
-//     has_tail    a segment ends inside the range
-//     first       sum of the items up to and including the first segment end   (+ its segment id)
-//     open        sum of the items after the last segment end (all items if there is none)
-// and two adjacent summaries combine associatively; a segment that closes at the boundary of two
-// units is final once the left unit contains a segment end.  Tile summaries go to a carry buffer
-// and small follow-up kernels finish the segments cut by tile boundaries in a fixed order, so the
-// results do not depend on scheduling (no atomics).
-//
-// Kernels:  k_stream_rank1_ldsvec  rank 1, dense vector staged in LDS, one wavefront per 1024-item chunk
-//           k_stream_rank1[_coo]   rank 1, vector gathered through L1, tail-id map per 4096-item tile
-//           k_stream_rankR         rank R, lane groups walk item runs, per-item records in LDS
-//           k_stream_mttkrp        rank R, two nested segment levels (fibers inside slices)
-//           k_fixup_level / k_stream_fixup   carry resolution
-#include <cstdlib>
-
-#include "stream_kernels.hpp"
+// Rank-1 kernels of the nonzero-tiled family (SpMV, TTV on CSF and on sorted coordinate lists), the
+// carry fix-up kernels shared by all of them, and the host entry points of the family.
+#include "stream_common.hpp"
 
 namespace comet {
 
 namespace {
+
 
 constexpr int kWaves = 4;                    // wavefronts per workgroup
 constexpr int kWaveItems = kTile / kWaves;   // 1024 consecutive items per wavefront
@@ -90,49 +65,6 @@ __device__ __forceinline__ void segscan_inclusive(int &f, double &v) {
     COMET_SCAN_STEP(0x143, 0xc)   // row_bcast:31 into rows 2 and 3
 #undef COMET_SCAN_STEP0
 #undef COMET_SCAN_STEP
-}
-
-// Carry-buffer layout inside the per-tensor scratch.  Level 0 holds one summary per tile: first[R],
-// open[R] (fp64), has_tail and first_id (int32).  Level l+1 holds one summary per group of
-// kFixGroup consecutive level-l summaries (same layout), so that a segment cut over thousands of
-// tiles is finished in a few short passes instead of one long serial walk.
-constexpr int kFixGroup = 64;
-struct CarryView {
-    double  *first, *open;
-    int32_t *has_tail, *first_id;
-};
-__host__ __device__ inline size_t carry_level_bytes(int64_t n, int64_t R) {
-    size_t b = (size_t)n * (size_t)R * 2 * sizeof(double) + (size_t)n * 2 * sizeof(int32_t);
-    return (b + 255) & ~(size_t)255;
-}
-__host__ __device__ inline CarryView carry_view(void *scratch, int64_t n, int64_t R) {
-    CarryView c;
-    c.first = (double *)scratch;
-    c.open = c.first + n * R;
-    c.has_tail = (int32_t *)(c.open + n * R);
-    c.first_id = c.has_tail + n;
-    return c;
-}
-
-// ---- phase A/B for compressed levels: fill the tail map from pos, zero-fill empty segments -------
-// Segments [seg_begin[t], seg_begin[t+1]) end inside tile t (the segment that contains the first
-// item of the next tile ends later), so each of them owns exactly one map entry.
-__device__ __forceinline__ void build_tail_map_from_pos(int32_t *ts, const int32_t *__restrict__ pos,
-                                                        const int32_t *__restrict__ rowmap, int64_t tb, int32_t s0,
-                                                        int32_t s1, double *__restrict__ out, int R) {
-    for (int i = threadIdx.x * 4; i < kTile; i += blockDim.x * 4)
-        *reinterpret_cast<int4 *>(ts + i) = make_int4(-1, -1, -1, -1);
-    __syncthreads();
-    for (int32_t s = s0 + threadIdx.x; s < s1; s += blockDim.x) {
-        int32_t b = pos[s], e = pos[s + 1];
-        if (e > b) {
-            ts[(int64_t)e - 1 - tb] = s;
-        } else {
-            int64_t row = rowmap ? (int64_t)rowmap[s] : (int64_t)s;
-            for (int r = 0; r < R; ++r) out[row * R + r] = 0.0;
-        }
-    }
-    __syncthreads();
 }
 
 // ---- rank-1 walk ---------------------------------------------------------------------------------
@@ -513,461 +445,6 @@ __global__ void __launch_bounds__(256) k_stream_fixup(void *scratch, int64_t nti
 }
 
 
-// ---- rank-R walk: a group of L lanes (4 or 8) walks a run of consecutive items --------------------
-// The 256 threads of a tile form 256/L lane groups ("walkers"); walker g owns the 16*L consecutive
-// items [tb + 16*L*g, +16*L).  Every 4*L items (a super-block) each lane loads four consecutive
-// (crd, val) pairs with 16-byte loads, looks up their tail ids, turns crd into the byte offset of
-// the operand row, and writes one small record per item into the walker's private LDS area.  The
-// group then takes the items one at a time: every lane reads the current item's record with a
-// broadcast LDS read (no cross-lane VALU work), adds its own 16-byte slot, and gathers its share of
-// the operand row Dn[crd, :] -- contiguous 16-byte pieces (WIDE, R a multiple of 2L: lane j takes
-// ranks 2L*q+2j, 2L*q+2j+1) or 8-byte pieces (lane j takes ranks L*q+j) -- so a load instruction
-// reads each gathered row as one contiguous run of 16*L bytes.  Gathers run G steps ahead of the
-// FMAs (double-buffered in registers).  Row offsets are 32-bit, so an operand must be < 4 GiB.
-template <int L, int NI>
-struct RecLayout {                                     // per-walker record area, in 4-byte words
-    static constexpr int SB = 4 * L;                   // items per super-block
-    static constexpr int kVal = NI * SB;               // values start after the integer records
-    static constexpr int kStride = NI * SB + 2 * SB + 4;   // + 16 bytes so that walkers start on different banks
-};
-
-// This lane's share of a dense row: V values.
-template <int L, int V, bool WIDE>
-__device__ __forceinline__ void grp_load_row(const double *__restrict__ Dn, int64_t row, int R, int j, double *d) {
-    const double *rowp = Dn + row * R;
-    if constexpr (WIDE) {
-#pragma unroll
-        for (int q = 0; q < V / 2; ++q) {
-            const double2 x = *reinterpret_cast<const double2 *>(rowp + 2 * L * q + 2 * j);
-            d[2 * q] = x.x; d[2 * q + 1] = x.y;
-        }
-    } else {
-#pragma unroll
-        for (int q = 0; q < V; ++q) { int r = L * q + j; d[q] = r < R ? rowp[r] : 0.0; }
-    }
-}
-template <int L, int V, bool WIDE>
-__device__ __forceinline__ void grp_store_row(double *__restrict__ out, int64_t row, int R, int j, const double *v) {
-    double *p = out + row * R;
-    if constexpr (WIDE) {
-#pragma unroll
-        for (int q = 0; q < V / 2; ++q) *reinterpret_cast<double2 *>(p + 2 * L * q + 2 * j) = make_double2(v[2 * q], v[2 * q + 1]);
-    } else {
-#pragma unroll
-        for (int q = 0; q < V; ++q) { int r = L * q + j; if (r < R) p[r] = v[q]; }
-    }
-}
-
-// The same for a result row that this kernel does not read again: non-temporal stores.
-template <int L, int V, bool WIDE>
-__device__ __forceinline__ void grp_store_row_stream(double *__restrict__ out, int64_t row, int R, int j, const double *v) {
-    double *p = out + row * R;
-    if constexpr (WIDE) {
-        typedef double v2d __attribute__((ext_vector_type(2)));
-#pragma unroll
-        for (int q = 0; q < V / 2; ++q) {
-            v2d x; x.x = v[2 * q]; x.y = v[2 * q + 1];
-            __builtin_nontemporal_store(x, reinterpret_cast<v2d *>(p + 2 * L * q + 2 * j));
-        }
-    } else {
-#pragma unroll
-        for (int q = 0; q < V; ++q) { int r = L * q + j; if (r < R) __builtin_nontemporal_store(v[q], p + r); }
-    }
-}
-
-// compile-time loop: f(IntC<B>{}), ..., f(IntC<E-1>{})
-template <int N> struct IntC { static constexpr int value = N; };
-template <int B, int E, class F>
-__device__ __forceinline__ void static_for(F &&f) {
-    if constexpr (B < E) { f(IntC<B>{}); static_for<B + 1, E>(f); }
-}
-
-// Four consecutive items of one lane: the streamed part of a 4*L-item super-block.
-struct LaneItems {
-    int    cr[4];
-    double va[4];
-};
-__device__ __forceinline__ void lane_load_items(LaneItems &it, const int32_t *__restrict__ crd,
-                                                const double *__restrict__ vals, int64_t i0, int64_t nnz) {
-    if (i0 + 3 < nnz) {
-        // streamed once: non-temporal, so the caches keep the operand rows rather than the nonzeros
-        typedef int v4i __attribute__((ext_vector_type(4)));
-        typedef double v2d __attribute__((ext_vector_type(2)));
-        const v4i c4 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(crd + i0));
-        const v2d a01 = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(vals + i0));
-        const v2d a23 = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(vals + i0 + 2));
-        it.cr[0] = c4.x; it.cr[1] = c4.y; it.cr[2] = c4.z; it.cr[3] = c4.w;
-        it.va[0] = a01.x; it.va[1] = a01.y; it.va[2] = a23.x; it.va[3] = a23.y;
-    } else {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) { bool in = i0 + s < nnz; it.cr[s] = in ? crd[i0 + s] : 0; it.va[s] = in ? vals[i0 + s] : 0.0; }
-    }
-}
-
-template <int V> struct RowBuf { double d[V]; int tail; double a; int boff, mrow; };
-
-// Steps per pipeline group: the gathers of group g+1 are in flight while group g is consumed.
-template <int V> struct StepGroup { static constexpr int value = V <= 4 ? 4 : (V <= 8 ? 2 : 1); };
-
-template <int V>
-struct WalkState {
-    double acc[V];
-    double first[V];
-    int ht, first_id;
-};
-
-// This lane's share of the dense row that starts `off` bytes into Dn (off already includes the
-// lane's own slot).
-template <int L, int V, bool WIDE>
-__device__ __forceinline__ void grp_load_row_off(const double *__restrict__ Dn, unsigned off, int R, int j, double *d) {
-    const char *base = reinterpret_cast<const char *>(Dn);
-    if constexpr (WIDE) {
-#pragma unroll
-        for (int q = 0; q < V / 2; ++q) {
-            const double2 x = *reinterpret_cast<const double2 *>(base + (size_t)(off + (unsigned)(16 * L * q)));
-            d[2 * q] = x.x; d[2 * q + 1] = x.y;
-        }
-    } else {
-#pragma unroll
-        for (int q = 0; q < V; ++q) {
-            d[q] = L * q + j < R ? *reinterpret_cast<const double *>(base + (size_t)(off + (unsigned)(8 * L * q))) : 0.0;
-        }
-    }
-}
-template <int L, bool WIDE>
-__device__ __forceinline__ unsigned lane_slot_bytes(int j) { return WIDE ? 16u * j : 8u * j; }
-
-// Close the first segment end of every walker of the tile and publish the tile summary.
-// wopen[(g*L + j)*V + q] holds walker g's open sum, wht[g] its has_tail flag (both already written
-// and separated from this call by a barrier).  `first_row` is the output row of the walker's first
-// segment end; `open` its trailing sum.
-template <int L, int V, bool WIDE>
-__device__ __forceinline__ void finish_tile_walkers(const double *wopen, const int *wht, int g, int j, int ht,
-                                                    const double *first, int64_t first_row, int32_t first_id,
-                                                    const double *open, double *__restrict__ out, int R,
-                                                    CarryView cb, int64_t t) {
-    constexpr int NW = 256 / L;
-    const bool last = g == NW - 1;
-    if (!(ht || last)) return;
-    double sum[V];
-#pragma unroll
-    for (int q = 0; q < V; ++q) sum[q] = 0.0;
-    int found = 0;
-    for (int g2 = g - 1; g2 >= 0; --g2) {
-        const double *wo = wopen + (g2 * L + j) * V;
-#pragma unroll
-        for (int q = 0; q < V; ++q) sum[q] += wo[q];
-        if (wht[g2]) { found = 1; break; }
-    }
-    if (ht) {
-        double value[V];
-#pragma unroll
-        for (int q = 0; q < V; ++q) value[q] = sum[q] + first[q];
-        if (found) {
-            grp_store_row<L, V, WIDE>(out, first_row, R, j, value);
-        } else {                                              // first segment end of the whole tile
-            grp_store_row<L, V, WIDE>(cb.first, t, R, j, value);
-            if (j == 0) cb.first_id[t] = first_id;
-        }
-    }
-    if (last) {
-        double topen[V];
-#pragma unroll
-        for (int q = 0; q < V; ++q) topen[q] = ht ? open[q] : open[q] + sum[q];
-        grp_store_row<L, V, WIDE>(cb.open, t, R, j, topen);
-        if (j == 0) cb.has_tail[t] = ht | found;
-    }
-}
-
-template <int L, int V, bool WIDE, bool ROWMAP>
-__global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
-                                                      const double *__restrict__ vals,
-                                                      const int32_t *__restrict__ seg_begin,
-                                                      const int32_t *__restrict__ rowmap, const double *__restrict__ Dn,
-                                                      double *__restrict__ out, int64_t nnz, int64_t ntiles, int R,
-                                                      void *scratch) {
-    constexpr int NW = 256 / L;                // walkers per tile
-    constexpr int WI = kTile / NW;             // items per walker
-    using RL = RecLayout<L, 2>;                // record = {row byte offset, tail id} + value
-    constexpr int SB = RL::SB;
-    __shared__ __attribute__((aligned(16))) int32_t ts[kTile];
-    __shared__ __attribute__((aligned(16))) int32_t rec_all[NW * RL::kStride];
-    __shared__ __attribute__((aligned(16))) double wopen[256 * V];       // [walker][lane j][V]
-    __shared__ int wht[NW];
-    const int64_t t = blockIdx.x;
-    const int64_t tb = t * (int64_t)kTile;
-    const int g = threadIdx.x / L, j = threadIdx.x % L;
-    const int64_t gb = tb + (int64_t)g * WI;                      // first item of this walker
-    LaneItems cur;
-    lane_load_items(cur, crd, vals, gb + 4 * j, nnz);             // in flight while the map is built
-    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, R);
-
-    WalkState<V> st;
-#pragma unroll
-    for (int q = 0; q < V; ++q) { st.acc[q] = 0.0; st.first[q] = 0.0; }
-    st.ht = 0; st.first_id = -1;
-    int32_t *rec = rec_all + g * RL::kStride;
-    const unsigned R8 = 8u * (unsigned)R;
-    const unsigned slot = lane_slot_bytes<L, WIDE>(j);
-    char *outb = reinterpret_cast<char *>(out);
-
-    constexpr int G = StepGroup<V>::value, NG = SB / G;
-    for (int sb = 0; sb < WI / SB; ++sb) {
-        const int64_t i0 = gb + SB * sb + 4 * j;                  // this lane's four items
-        LaneItems nxt;
-        if (sb + 1 < WI / SB) lane_load_items(nxt, crd, vals, i0 + SB, nnz);
-        {
-            const int4 t4 = *reinterpret_cast<const int4 *>(ts + (i0 - tb));
-            *reinterpret_cast<int4 *>(rec + 8 * j) =
-                make_int4((int)((unsigned)cur.cr[0] * R8), t4.x, (int)((unsigned)cur.cr[1] * R8), t4.y);
-            *reinterpret_cast<int4 *>(rec + 8 * j + 4) =
-                make_int4((int)((unsigned)cur.cr[2] * R8), t4.z, (int)((unsigned)cur.cr[3] * R8), t4.w);
-            *reinterpret_cast<double2 *>(rec + RL::kVal + 8 * j) = make_double2(cur.va[0], cur.va[1]);
-            *reinterpret_cast<double2 *>(rec + RL::kVal + 8 * j + 4) = make_double2(cur.va[2], cur.va[3]);
-        }
-        __builtin_amdgcn_wave_barrier();                          // records are read by the other lanes of the group
-        RowBuf<V> buf[2][G];
-        auto issue = [&](auto gc, RowBuf<V> *bb) {
-            static_for<0, G>([&](auto sc) {
-                constexpr int k = decltype(gc)::value * G + decltype(sc)::value;      // step inside the super-block
-                RowBuf<V> &b = bb[decltype(sc)::value];
-                const int2 ct = *reinterpret_cast<const int2 *>(rec + 2 * k);
-                b.a = *reinterpret_cast<const double *>(rec + RL::kVal + 2 * k);
-                b.tail = ct.y;
-                grp_load_row_off<L, V, WIDE>(Dn, (unsigned)ct.x + slot, R, j, b.d);
-            });
-        };
-        auto consume = [&](auto gc, const RowBuf<V> *bb) {
-            static_for<0, G>([&](auto sc) {
-                const RowBuf<V> &b = bb[decltype(sc)::value];
-#pragma unroll
-                for (int q = 0; q < V; ++q) st.acc[q] = fma(b.a, b.d[q], st.acc[q]);
-                if (b.tail >= 0) {                                // the item ends segment `tail` (same for the group)
-                    if (!st.ht) {
-#pragma unroll
-                        for (int q = 0; q < V; ++q) st.first[q] = st.acc[q];
-                        st.first_id = b.tail;
-                        st.ht = 1;
-                    } else {
-                        const unsigned row = ROWMAP ? (unsigned)rowmap[b.tail] : (unsigned)b.tail;
-                        grp_store_row_stream<L, V, WIDE>(reinterpret_cast<double *>(outb + (size_t)row * R8), 0, R, j, st.acc);
-                    }
-#pragma unroll
-                    for (int q = 0; q < V; ++q) st.acc[q] = 0.0;
-                }
-            });
-        };
-        issue(IntC<0>{}, buf[0]);
-        static_for<0, NG>([&](auto gc) {
-            constexpr int gi = decltype(gc)::value;
-            if constexpr (gi + 1 < NG) issue(IntC<gi + 1>{}, buf[(gi + 1) & 1]);
-            consume(gc, buf[gi & 1]);
-        });
-        __builtin_amdgcn_wave_barrier();                          // all reads of this super-block's records are done
-        if (sb + 1 < WI / SB) cur = nxt;
-    }
-
-    {
-        double *wo = wopen + (g * L + j) * V;
-#pragma unroll
-        for (int q = 0; q < V; ++q) wo[q] = st.acc[q];
-        if (j == 0) wht[g] = st.ht;
-    }
-    __syncthreads();
-    const int64_t first_row = st.ht ? (ROWMAP ? (int64_t)rowmap[st.first_id] : (int64_t)st.first_id) : 0;
-    finish_tile_walkers<L, V, WIDE>(wopen, wht, g, j, st.ht, st.first, first_row, st.first_id, st.acc, out, R,
-                                    carry_view(scratch, ntiles, R), t);
-}
-
-template <int L, int V, bool WIDE>
-hipError_t launch_rankR(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
-                        const int32_t *rowmap, const double *Dn, int R, double *out, void *scratch, hipStream_t st) {
-    if (rowmap)
-        hipLaunchKernelGGL((k_stream_rankR<L, V, WIDE, true>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
-                           (const int32_t *)sc.seg_begin->ptr, rowmap, Dn, out, sc.nnz, sc.ntiles, R, scratch);
-    else
-        hipLaunchKernelGGL((k_stream_rankR<L, V, WIDE, false>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
-                           (const int32_t *)sc.seg_begin->ptr, rowmap, Dn, out, sc.nnz, sc.ntiles, R, scratch);
-    return hipGetLastError();
-}
-
-// Cross-lane broadcast inside a lane group (quad_perm inside a quad, plus one row_shr:4 / row_shl:4 with a
-// bank mask to cross the two quads of an 8-lane group); used by the MTTKRP walk, whose LDS budget goes
-// to its two tail maps.
-template <int L, int BP>
-__device__ __forceinline__ int grp_bcast_i(int v) {
-    static_assert(L == 4 || L == 8, "lane groups of 4 or 8");
-    // quad_perm broadcast; every lane is written, and bound_ctrl with full masks tells the compiler so
-    // (no move of the unused old value in front of it)
-    const int x1 = __builtin_amdgcn_update_dpp(0, v, (BP % 4) * 0x55, 0xf, 0xf, true);
-    if constexpr (L == 4) return x1;
-    else if constexpr (BP < 4) return __builtin_amdgcn_update_dpp(x1, x1, 0x114, 0xf, 0xa, false);   // row_shr:4 into the odd quads
-    else return __builtin_amdgcn_update_dpp(x1, x1, 0x104, 0xf, 0x5, false);                          // row_shl:4 into the even quads
-}
-template <int L, int BP>
-__device__ __forceinline__ double grp_bcast_d(double v) {
-    return __hiloint2double(grp_bcast_i<L, BP>(__double2hiint(v)), grp_bcast_i<L, BP>(__double2loint(v)));
-}
-
-// ---- MTTKRP: the same walk, two nested segment levels ---------------------------------------------
-// Inner level: fibers (segments of pos3); the per-fiber sum of vals * C[crd3, :] is scaled by the row
-// B[crd2[fiber], :] when the fiber ends and folded into the slice accumulator.  Scaling is linear,
-// so a fiber cut by a walker or tile boundary is folded piecewise (each piece times the same B row);
-// only the slice level needs carries.  Outer level: slices (segments of pos2); a slice end writes
-// row crd1[slice] of M.  Two LDS maps, both keyed by tile item: ts = fiber id at a fiber's last
-// nonzero, tm = output row at a slice's last nonzero (-1 elsewhere).
-template <int L, int V, bool WIDE>
-__global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict__ pos2, const int32_t *__restrict__ crd1,
-                                                       const int32_t *__restrict__ pos3, const int32_t *__restrict__ crd2,
-                                                       const int32_t *__restrict__ crd3, const double *__restrict__ vals,
-                                                       const int32_t *__restrict__ seg_begin,
-                                                       const int32_t *__restrict__ slice_begin,
-                                                       const double *__restrict__ Bm, const double *__restrict__ Cm,
-                                                       double *__restrict__ M, int64_t nnz, int64_t nfib, int64_t ntiles,
-                                                       int R, void *scratch) {
-    constexpr int NW = 256 / L, WI = kTile / NW, SB = 4 * L;
-    constexpr int kMapInts = 2 * kTile;
-    constexpr int kOpenInts = 256 * V * 2;
-    constexpr int kLdsInts = kMapInts > kOpenInts ? kMapInts : kOpenInts;
-    __shared__ __attribute__((aligned(16))) int32_t lds[kLdsInts];
-    __shared__ int wht[NW], wfirst_fid[NW];
-    int32_t *ts = lds, *tm = lds + kTile;
-    double *wopen = reinterpret_cast<double *>(lds);              // reused once the maps are dead
-    const int64_t t = blockIdx.x;
-    const int64_t tb = t * (int64_t)kTile, te = tb + kTile;
-    const int g = threadIdx.x / L, j = threadIdx.x % L;
-    const int64_t gb = tb + (int64_t)g * WI;
-    LaneItems cur;
-    lane_load_items(cur, crd3, vals, gb + 4 * j, nnz);            // in flight while the maps are built
-
-    for (int i = threadIdx.x * 4; i < 2 * kTile; i += blockDim.x * 4)
-        *reinterpret_cast<int4 *>(lds + i) = make_int4(-1, -1, -1, -1);
-    __syncthreads();
-    for (int32_t f = seg_begin[t] + threadIdx.x; f < seg_begin[t + 1]; f += blockDim.x) {
-        int32_t b = pos3[f], e = pos3[f + 1];
-        if (e > b) ts[(int64_t)e - 1 - tb] = f;
-    }
-    for (int32_t sl = slice_begin[t] + threadIdx.x; sl < slice_begin[t + 1]; sl += blockDim.x) {
-        int32_t fb = pos2[sl], fe = pos2[sl + 1];
-        int64_t il = -1;                                          // last nonzero of the slice
-        for (int32_t f = fe - 1; f >= fb; --f) {
-            int32_t b = pos3[f], e = pos3[f + 1];
-            if (e > b) { il = (int64_t)e - 1; break; }
-        }
-        if (il >= tb && il < te) tm[il - tb] = crd1[sl];
-        if (il < 0) {                                             // a stored slice without any nonzero: its row is zero
-            double *row = M + (int64_t)crd1[sl] * R;
-            for (int r = 0; r < R; ++r) row[r] = 0.0;
-        }
-    }
-    __syncthreads();
-
-    double facc[V], sacc[V], first[V];
-#pragma unroll
-    for (int q = 0; q < V; ++q) { facc[q] = 0.0; sacc[q] = 0.0; first[q] = 0.0; }
-    int ht = 0, first_row = -1, first_fid = -1, last_is_tail = 1;
-
-    constexpr int G = StepGroup<V>::value, NG = SB / G;
-    for (int sb = 0; sb < WI / SB; ++sb) {
-        const int64_t i0 = gb + SB * sb + 4 * j;
-        LaneItems nxt;
-        if (sb + 1 < WI / SB) lane_load_items(nxt, crd3, vals, i0 + SB, nnz);
-        int tl[4], tr[4], jb[4];
-        {
-            const int4 t4 = *reinterpret_cast<const int4 *>(ts + (i0 - tb));
-            const int4 m4 = *reinterpret_cast<const int4 *>(tm + (i0 - tb));
-            tl[0] = t4.x; tl[1] = t4.y; tl[2] = t4.z; tl[3] = t4.w;
-            tr[0] = m4.x; tr[1] = m4.y; tr[2] = m4.z; tr[3] = m4.w;
-        }
-#pragma unroll
-        for (int s = 0; s < 4; ++s) jb[s] = tl[s] >= 0 ? crd2[tl[s]] : 0;      // B row of a fiber that ends here
-        const bool any_item = gb + SB * sb < nnz;
-        RowBuf<V> cbuf[2][G], bbuf[2][G];
-        auto issue = [&](auto gc, RowBuf<V> *cb_, RowBuf<V> *bb_) {
-            static_for<0, G>([&](auto sc) {
-                constexpr int k = decltype(gc)::value * G + decltype(sc)::value;
-                constexpr int s_ = decltype(sc)::value;
-                const int c = grp_bcast_i<L, k / 4>(cur.cr[k % 4]);
-                grp_load_row<L, V, WIDE>(Cm, c, R, j, cb_[s_].d);
-                const int tf = grp_bcast_i<L, k / 4>(tl[k % 4]);
-                if (tf >= 0) {                                    // the fiber ends here: its B row is needed too
-                    const int jrow = grp_bcast_i<L, k / 4>(jb[k % 4]);
-                    grp_load_row<L, V, WIDE>(Bm, jrow, R, j, bb_[s_].d);
-                }
-            });
-        };
-        auto consume = [&](auto gc, const RowBuf<V> *cb_, const RowBuf<V> *bb_) {
-            static_for<0, G>([&](auto sc) {
-                constexpr int k = decltype(gc)::value * G + decltype(sc)::value;
-                constexpr int s_ = decltype(sc)::value;
-                const double a = grp_bcast_d<L, k / 4>(cur.va[k % 4]);
-                const int tf = grp_bcast_i<L, k / 4>(tl[k % 4]);
-                const int tmr = grp_bcast_i<L, k / 4>(tr[k % 4]);
-#pragma unroll
-                for (int q = 0; q < V; ++q) facc[q] = fma(a, cb_[s_].d[q], facc[q]);
-                if (any_item) last_is_tail = tf >= 0;
-                if (tf >= 0) {
-                    if (first_fid < 0) first_fid = tf;
-#pragma unroll
-                    for (int q = 0; q < V; ++q) { sacc[q] = fma(bb_[s_].d[q], facc[q], sacc[q]); facc[q] = 0.0; }
-                    if (tmr >= 0) {
-                        if (!ht) {
-#pragma unroll
-                            for (int q = 0; q < V; ++q) first[q] = sacc[q];
-                            first_row = tmr; ht = 1;
-                        } else {
-                            grp_store_row<L, V, WIDE>(M, tmr, R, j, sacc);
-                        }
-#pragma unroll
-                        for (int q = 0; q < V; ++q) sacc[q] = 0.0;
-                    }
-                }
-            });
-        };
-        issue(IntC<0>{}, cbuf[0], bbuf[0]);
-        static_for<0, NG>([&](auto gc) {
-            constexpr int gi = decltype(gc)::value;
-            if constexpr (gi + 1 < NG) issue(IntC<gi + 1>{}, cbuf[(gi + 1) & 1], bbuf[(gi + 1) & 1]);
-            consume(gc, cbuf[gi & 1], bbuf[gi & 1]);
-        });
-        if (sb + 1 < WI / SB) cur = nxt;
-    }
-
-    // A fiber left open at the end of this walker's range ends at the next fiber end of the tile, or,
-    // if there is none, it is the fiber that contains the first nonzero of the next tile.
-    if (j == 0) wfirst_fid[g] = first_fid;
-    __syncthreads();                                              // also: every walk is done, the maps are dead
-    if (!last_is_tail) {
-        int64_t fid = seg_begin[t + 1];
-        for (int g2 = g + 1; g2 < NW; ++g2) { int f2 = wfirst_fid[g2]; if (f2 >= 0) { fid = f2; break; } }
-        if (fid < nfib) {
-            double bw[V];
-            grp_load_row<L, V, WIDE>(Bm, crd2[fid], R, j, bw);
-#pragma unroll
-            for (int q = 0; q < V; ++q) sacc[q] = fma(bw[q], facc[q], sacc[q]);
-        }
-    }
-    {
-        double *wo = wopen + (g * L + j) * V;
-#pragma unroll
-        for (int q = 0; q < V; ++q) wo[q] = sacc[q];
-        if (j == 0) wht[g] = ht;
-    }
-    __syncthreads();
-    finish_tile_walkers<L, V, WIDE>(wopen, wht, g, j, ht, first, first_row, first_row, sacc, M, R,
-                                    carry_view(scratch, ntiles, R), t);
-}
-
-template <int L, int V, bool WIDE>
-hipError_t launch_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t *crd1, const int32_t *pos3,
-                         const int32_t *crd2, const int32_t *crd3, const double *vals, const double *B, const double *C,
-                         int R, double *M, void *scratch, hipStream_t st) {
-    hipLaunchKernelGGL((k_stream_mttkrp<L, V, WIDE>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos2, crd1, pos3, crd2,
-                       crd3, vals, (const int32_t *)sc.seg_begin->ptr, (const int32_t *)sc.slice_begin->ptr, B, C, M,
-                       sc.nnz, sc.nseg, sc.ntiles, R, scratch);
-    return hipGetLastError();
-}
-
 // One pass of the hierarchical fix-up: thread (g, r) folds the kFixGroup summaries of group g in
 // order.  A segment end whose carry chain starts inside the group is final and is written to out;
 // the group's own summary (first segment end, trailing open sum) goes one level up.
@@ -1019,6 +496,9 @@ __global__ void __launch_bounds__(256) k_fixup_level(const double *__restrict__ 
     if (r == 0) { up_ht[g] = rf; up_id[g] = gid; }
 }
 
+
+}  // namespace
+
 // Finish every segment that a tile boundary cut: fold the tile summaries level by level, then
 // walk the few top-level summaries serially.  `max_chain` bounds the number of consecutive tiles
 // one segment can span (0 = unknown); short chains go straight to the serial walk.
@@ -1044,7 +524,6 @@ hipError_t run_fixup(void *scratch, int64_t ntiles, int R, const int32_t *rowmap
     return hipGetLastError();
 }
 
-}  // namespace
 
 // Allows a kernel to use up to the whole 160 KB of LDS as dynamic shared memory; done once per kernel
 // (it is not a stream operation, but calling it once keeps it out of captured regions after the first call).
@@ -1052,15 +531,6 @@ template <auto Kernel>
 static hipError_t allow_full_lds() {
     static hipError_t status = hipFuncSetAttribute((const void *)Kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     return status;
-}
-
-// Lane-group width of the rank-R kernels: 8 by default; COMET_LANES=4 selects the quad mapping
-// (for measurements).  Ranks up to 8 always use quads.
-static int lanes_per_item(int64_t R) {
-    static int forced = [] { const char *e = getenv("COMET_LANES"); return e ? atoi(e) : 0; }();
-    if (R <= 8) return 4;
-    if (forced == 4 && R <= 64) return 4;
-    return 8;
 }
 
 // COMET_NO_LDS_VECTOR=1 keeps rank-1 operations on the L1-gather kernel (for measurements).
@@ -1083,33 +553,6 @@ size_t stream_scratch_bytes(int64_t ntiles, int64_t R) {
     }
     return total + 256;
 }
-
-// Calls F<L, V, WIDE>(args...) for the specialisation that covers rank R.
-#define COMET_DISPATCH_RANK(F, R, ...)                                                     \
-    [&]() -> hipError_t {                                                                  \
-        const int r_ = (int)(R);                                                           \
-        if (lanes_per_item(r_) == 4) {                                                     \
-            if (r_ == 8)  return F<4, 2, true>(__VA_ARGS__);                               \
-            if (r_ == 16) return F<4, 4, true>(__VA_ARGS__);                               \
-            if (r_ == 32) return F<4, 8, true>(__VA_ARGS__);                               \
-            if (r_ == 64) return F<4, 16, true>(__VA_ARGS__);                              \
-            if (r_ <= 4)  return F<4, 1, false>(__VA_ARGS__);                              \
-            if (r_ <= 8)  return F<4, 2, false>(__VA_ARGS__);                              \
-            if (r_ <= 16) return F<4, 4, false>(__VA_ARGS__);                              \
-            if (r_ <= 32) return F<4, 8, false>(__VA_ARGS__);                              \
-            return F<4, 16, false>(__VA_ARGS__);                                           \
-        }                                                                                  \
-        if (r_ == 16)  return F<8, 2, true>(__VA_ARGS__);                                  \
-        if (r_ == 32)  return F<8, 4, true>(__VA_ARGS__);                                  \
-        if (r_ == 48)  return F<8, 6, true>(__VA_ARGS__);                                  \
-        if (r_ == 64)  return F<8, 8, true>(__VA_ARGS__);                                  \
-        if (r_ == 96)  return F<8, 12, true>(__VA_ARGS__);                                 \
-        if (r_ == 128) return F<8, 16, true>(__VA_ARGS__);                                 \
-        if (r_ <= 16)  return F<8, 2, false>(__VA_ARGS__);                                 \
-        if (r_ <= 32)  return F<8, 4, false>(__VA_ARGS__);                                 \
-        if (r_ <= 64)  return F<8, 8, false>(__VA_ARGS__);                                 \
-        return F<8, 16, false>(__VA_ARGS__);                                               \
-    }()
 
 hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                             const int32_t *rowmap, const double *Dn, int64_t dense_rows, int64_t R, double *out,
@@ -1151,7 +594,7 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
                                rowmap, Dn, out, sc.nnz, sc.ntiles, scratch);
         e = hipGetLastError();
     } else {
-        e = COMET_DISPATCH_RANK(launch_rankR, R, sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
+        e = stream_segreduce_rankR(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
     }
     if (e != hipSuccess) return e;
     return run_fixup(scratch, sc.ntiles, (int)R, rowmap, out, sc.max_seg_len / kTile + 2, st);
@@ -1180,18 +623,6 @@ hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *
     hipLaunchKernelGGL(k_stream_rank1_coo, dim3((unsigned)sc.ntiles), dim3(256), 0, st, c0, c1, c2, vals,
                        (const int32_t *)sc.run_base->ptr, v, y0, y1, yv, sc.nnz, sc.ntiles, scratch);
     return run_fixup(scratch, sc.ntiles, 1, nullptr, yv, max_run / kTile + 2, st);
-}
-
-hipError_t stream_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t *crd1, int64_t nslice,
-                         const int32_t *pos3, const int32_t *crd2, const int32_t *crd3, const double *vals,
-                         const double *B, const double *C, int64_t R, double *M, void *scratch, hipStream_t st) {
-    (void)nslice;
-    if (sc.ntiles <= 0) return hipSuccess;
-    if (!stream_mttkrp_supports_rank(R) || !sc.slice_begin) return hipErrorNotSupported;
-    const int r = (int)R;
-    hipError_t e = COMET_DISPATCH_RANK(launch_mttkrp, R, sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
-    if (e != hipSuccess) return e;
-    return run_fixup(scratch, sc.ntiles, r, nullptr, M, sc.max_parent_len > 0 ? sc.max_parent_len / kTile + 2 : 0, st);
 }
 
 }  // namespace comet

@@ -1,4 +1,5 @@
-// Launchers of the nonzero-tiled streaming kernels (definitions in kernels_stream.hip).
+// Launchers of the nonzero-tiled streaming kernels (definitions in kernels_rank1.hip, kernels_rankR.hip,
+// kernels_mttkrp.hip; shared device code in stream_common.hpp).
 //
 // The leaf level's nonzeros are processed in tiles of kTile consecutive positions regardless of
 // where segment (row / fiber / slice) boundaries fall, so a power-law head segment is spread
