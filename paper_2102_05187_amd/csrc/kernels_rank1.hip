@@ -282,8 +282,8 @@ __global__ void __launch_bounds__(1024) k_stream_rank1_ldsvec(const int32_t *__r
 #pragma unroll
                 for (int q = 0; q < kBatch; ++q) {
                     const int64_t i = cbeg + 64 * (rb + q) + lane;
-                    a0[q] = i < nnz ? c0[i] : -1;
-                    a1[q] = i < nnz ? c1[i] : -1;
+                    a0[q] = i < nnz ? __builtin_nontemporal_load(c0 + i) : -1;
+                    a1[q] = i < nnz ? __builtin_nontemporal_load(c1 + i) : -1;
                 }
 #pragma unroll
                 for (int q = 0; q < kBatch; ++q) {
