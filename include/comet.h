@@ -148,6 +148,17 @@ comet_status comet_tensor_info(const comet_tensor *t, comet_tensor_info_t *info)
 comet_status comet_tensor_reorder(const comet_tensor *X, const int32_t *mode_order, comet_tensor **out,
                                   void *stream);
 
+/*
+ * The same with a choice of the result's level formats: the conversion that the paper's runtime
+ * function space_read() performs after reading a coordinate list (Section 5), on the device.
+ *   levels   host, [order]; one of [CU,CU], [D,CU] (CSR), [CN,S] for order 2 and [CU,CU,CU],
+ *            [CN,S,S] for order 3; a coordinate-list result is sorted and duplicate-free.
+ * Other arguments, work and errors as for comet_tensor_reorder (which is this call with every
+ * level CU); other level tuples give COMET_ERR_UNSUPPORTED.
+ */
+comet_status comet_tensor_convert(const comet_tensor *X, const int32_t *mode_order, const comet_level_t *levels,
+                                  comet_tensor **out, void *stream);
+
 /* SpMV, y = A x :  y_i = sum_j a_ij x_j   (Section 8.2, SpMV).
  *   A   order-2 handle, [D,CU] or [CU,CU].
  *   x   device, [dims[1]].          y   device, [dims[0]]; every entry is overwritten

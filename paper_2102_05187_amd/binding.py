@@ -27,7 +27,7 @@ _STATUS_NAMES = {0: "COMET_OK", 1: "COMET_ERR_INVALID_ARG", 2: "COMET_ERR_BAD_FO
 
 EXPORTS = ["comet_tensor_create", "comet_tensor_destroy", "comet_tensor_info", "comet_spmv", "comet_spmm",
            "comet_ttv", "comet_ttm", "comet_mttkrp", "comet_status_string", "comet_tensor_set_variant",
-           "comet_tensor_reorder"]
+           "comet_tensor_reorder", "comet_tensor_convert"]
 
 
 class CometError(RuntimeError):
@@ -71,6 +71,7 @@ def _lib():
         lib.comet_mttkrp.argtypes = [vp, ci, vp, i64, vp, vp]
         lib.comet_tensor_set_variant.argtypes = [vp, ci]
         lib.comet_tensor_reorder.argtypes = [vp, vp, ctypes.POINTER(vp), vp]
+        lib.comet_tensor_convert.argtypes = [vp, vp, vp, ctypes.POINTER(vp), vp]
         lib.comet_status_string.argtypes = [ci]
         lib.comet_status_string.restype = ctypes.c_char_p
         for n in EXPORTS:
@@ -223,6 +224,17 @@ def comet_tensor_reorder(X: Tensor, mode_order: Sequence[int], stream=None) -> T
     c_order = (ctypes.c_int32 * order)(*[int(m) for m in mode_order])
     out = ctypes.c_void_p(None)
     _check(_lib().comet_tensor_reorder(X.handle, c_order, ctypes.byref(out), _stream(stream)), "comet_tensor_reorder")
+    return Tensor(out.value)
+
+
+def comet_tensor_convert(X: Tensor, mode_order: Sequence[int], levels: Sequence[int], stream=None) -> Tensor:
+    order = len(X.dims())
+    if len(mode_order) != order or len(levels) != order:
+        raise CometError(1, "comet_tensor_convert")
+    c_order = (ctypes.c_int32 * order)(*[int(m) for m in mode_order])
+    c_lv = (ctypes.c_int * order)(*[int(t) for t in levels])
+    out = ctypes.c_void_p(None)
+    _check(_lib().comet_tensor_convert(X.handle, c_order, c_lv, ctypes.byref(out), _stream(stream)), "comet_tensor_convert")
     return Tensor(out.value)
 
 

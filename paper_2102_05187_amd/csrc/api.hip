@@ -356,12 +356,10 @@ static int bit_width(int64_t dim) {
     return b;
 }
 
-comet_status comet_tensor_reorder(const comet_tensor *X, const int32_t *mode_order, comet_tensor **out,
-                                  void *stream) {
-    if (!out) return COMET_ERR_INVALID_ARG;
-    *out = nullptr;
-    if (!X || !mode_order) return COMET_ERR_INVALID_ARG;
-    hipStream_t st = (hipStream_t)stream;
+enum class Target { ALL_CU, CSR, COO };
+
+static comet_status restore(const comet_tensor *X, const int32_t *mode_order, Target target, comet_tensor **out,
+                            hipStream_t st) {
     const int order = X->order;
     comet::CoordSource src;
     switch (X->fmt) {
@@ -451,33 +449,93 @@ comet_status comet_tensor_reorder(const comet_tensor *X, const int32_t *mode_ord
     }
 
     // -- the new levels ---------------------------------------------------------------------------
-    const int64_t count[3] = {nroot, order == 3 ? nmid : n, n};   // positions per level (order 2 uses [0], [1])
     comet::CuLevels lv;
-    for (int l = 0; l < order; ++l) {
-        const int64_t parents = l == 0 ? 1 : count[l - 1];
-        t->pos_len[l] = parents + 1;
-        t->crd_len[l] = count[l];
-        t->pos[l] = comet::dev_alloc(sizeof(int32_t) * t->pos_len[l]);
-        t->crd[l] = comet::dev_alloc(sizeof(int32_t) * t->crd_len[l]);
-        if (!t->pos[l] || !t->crd[l]) return COMET_ERR_ALLOC;
-        lv.pos[l] = (int32_t *)t->pos[l]->ptr;
-        lv.crd[l] = (int32_t *)t->crd[l]->ptr;
-    }
-    {
-        int32_t h[2] = {0, (int32_t)nroot};
-        HIP_TRY(hipMemcpyAsync(lv.pos[0], h, sizeof h, hipMemcpyHostToDevice, st));
+    if (target == Target::COO) {
+        t->levels[0] = COMET_CN;
+        for (int l = 1; l < order; ++l) t->levels[l] = COMET_S;
+        t->pos_len[0] = 2;
+        t->pos[0] = comet::dev_alloc(2 * sizeof(int32_t));
+        if (!t->pos[0]) return COMET_ERR_ALLOC;
+        for (int l = 0; l < order; ++l) {
+            t->crd_len[l] = n;
+            t->crd[l] = comet::dev_alloc(sizeof(int32_t) * n);
+            if (!t->crd[l]) return COMET_ERR_ALLOC;
+            lv.crd[l] = (int32_t *)t->crd[l]->ptr;
+        }
+        int32_t h[2] = {0, (int32_t)n};
+        HIP_TRY(hipMemcpyAsync(t->pos[0]->ptr, h, sizeof h, hipMemcpyHostToDevice, st));
         HIP_TRY(hipStreamSynchronize(st));
-    }
-    if (n > 0) {
-        HIP_TRY(comet::reorder_cut_levels((const uint64_t *)keys->ptr, (const uint64_t *)flags->ptr,
-                                          (const uint64_t *)before->ptr, n, lay, order, lv, st));
+        if (n > 0) HIP_TRY(comet::reorder_unpack_keys((const uint64_t *)keys->ptr, n, lay, order, lv, st));
     } else {
-        for (int l = 1; l < order; ++l) HIP_TRY(hipMemsetAsync(lv.pos[l], 0, sizeof(int32_t), st));
+        const int64_t count[3] = {nroot, order == 3 ? nmid : n, n};   // positions per level (order 2 uses [0], [1])
+        for (int l = 0; l < order; ++l) {
+            const int64_t parents = l == 0 ? 1 : count[l - 1];
+            t->pos_len[l] = parents + 1;
+            t->crd_len[l] = count[l];
+            t->pos[l] = comet::dev_alloc(sizeof(int32_t) * t->pos_len[l]);
+            t->crd[l] = comet::dev_alloc(sizeof(int32_t) * t->crd_len[l]);
+            if (!t->pos[l] || !t->crd[l]) return COMET_ERR_ALLOC;
+            lv.pos[l] = (int32_t *)t->pos[l]->ptr;
+            lv.crd[l] = (int32_t *)t->crd[l]->ptr;
+        }
+        {
+            int32_t h[2] = {0, (int32_t)nroot};
+            HIP_TRY(hipMemcpyAsync(lv.pos[0], h, sizeof h, hipMemcpyHostToDevice, st));
+            HIP_TRY(hipStreamSynchronize(st));
+        }
+        if (n > 0) {
+            HIP_TRY(comet::reorder_cut_levels((const uint64_t *)keys->ptr, (const uint64_t *)flags->ptr,
+                                              (const uint64_t *)before->ptr, n, lay, order, lv, st));
+        } else {
+            for (int l = 1; l < order; ++l) HIP_TRY(hipMemsetAsync(lv.pos[l], 0, sizeof(int32_t), st));
+        }
+        if (target == Target::CSR) {
+            // dense root: one pos entry per row of the matrix instead of one per stored row
+            const int64_t dim0 = t->dims[0];
+            DevRef dense = comet::dev_alloc(sizeof(int32_t) * (dim0 + 1));
+            DevRef size0 = comet::dev_alloc(sizeof(int32_t));
+            if (!dense || !size0) return COMET_ERR_ALLOC;
+            HIP_TRY(comet::reorder_dense_pos(lv.crd[0], nroot, lv.pos[1], dim0, n, (int32_t *)dense->ptr, st));
+            int32_t h = (int32_t)dim0;
+            HIP_TRY(hipMemcpyAsync(size0->ptr, &h, sizeof h, hipMemcpyHostToDevice, st));
+            HIP_TRY(hipStreamSynchronize(st));
+            t->levels[0] = COMET_D;
+            t->pos[0] = size0; t->pos_len[0] = 1;
+            t->crd[0].reset(); t->crd_len[0] = 0;
+            t->pos[1] = dense; t->pos_len[1] = dim0 + 1;
+        }
     }
+    t->fmt = classify(order, t->levels);
     comet_status rs = build_schedule(*t, st);   // synchronises: the temporaries above may go
     if (rs != COMET_OK) return rs;
     *out = guard.release();
     return COMET_OK;
+}
+
+comet_status comet_tensor_reorder(const comet_tensor *X, const int32_t *mode_order, comet_tensor **out,
+                                  void *stream) {
+    if (!out) return COMET_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!X || !mode_order) return COMET_ERR_INVALID_ARG;
+    return restore(X, mode_order, Target::ALL_CU, out, (hipStream_t)stream);
+}
+
+comet_status comet_tensor_convert(const comet_tensor *X, const int32_t *mode_order, const comet_level_t *levels,
+                                  comet_tensor **out, void *stream) {
+    if (!out) return COMET_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!X || !mode_order || !levels) return COMET_ERR_INVALID_ARG;
+    int32_t lv[COMET_MAX_ORDER] = {0, 0, 0, 0};
+    if (X->order < 2 || X->order > 3) return COMET_ERR_UNSUPPORTED;
+    for (int l = 0; l < X->order; ++l) lv[l] = (int32_t)levels[l];
+    Target target;
+    switch (classify(X->order, lv)) {
+    case Format::DCSR: case Format::CSF3: target = Target::ALL_CU; break;
+    case Format::CSR: target = Target::CSR; break;
+    case Format::COO2: case Format::COO3: target = Target::COO; break;
+    default: return COMET_ERR_UNSUPPORTED;
+    }
+    return restore(X, mode_order, target, out, (hipStream_t)stream);
 }
 
 // ---- SpMV / SpMM: the last level is compressed; rows come from a dense or compressed root -------

@@ -80,6 +80,12 @@ hipError_t reorder_scan_flags(void *temp, size_t *temp_bytes, const uint64_t *fl
 // coordinates (order 3).  *err |= 1 if two nonzeros share all coordinates.
 hipError_t reorder_mark_heads(const uint64_t *keys, int64_t n, const KeyLayout &lay, int order, uint64_t *flags,
                               int32_t *err, hipStream_t st);
+// Sorted coordinate list out of the keys (crd[l][p] = field l), and the dense-root pos array of a CSR matrix
+// out of its compressed rows (out has dim0 + 1 entries).
+hipError_t reorder_unpack_keys(const uint64_t *keys, int64_t n, const KeyLayout &lay, int order, const CuLevels &out,
+                               hipStream_t st);
+hipError_t reorder_dense_pos(const int32_t *crd0, int64_t nroot, const int32_t *pos1, int64_t dim0, int64_t n,
+                             int32_t *out, hipStream_t st);
 hipError_t reorder_cut_levels(const uint64_t *keys, const uint64_t *flags, const uint64_t *before, int64_t n,
                               const KeyLayout &lay, int order, const CuLevels &out, hipStream_t st);
 

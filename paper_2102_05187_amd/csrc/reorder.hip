@@ -121,7 +121,44 @@ __global__ void __launch_bounds__(256) k_cut_levels(const uint64_t *__restrict__
     }
 }
 
+// Coordinate-list output: level l of nonzero p is field l of its key.
+__global__ void __launch_bounds__(256) k_unpack_keys(const uint64_t *__restrict__ keys, int64_t n, KeyLayout lay, int order,
+                                                     CuLevels out) {
+    int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (p >= n) return;
+    const uint64_t k = keys[p];
+    for (int l = 0; l < order; ++l) out.crd[l][p] = (int32_t)((k >> lay.shift[l]) & lay.mask[l]);
+}
+
+// Dense root level: pos[r] = number of nonzeros in rows < r, from the compressed rows (sorted row
+// coordinates crd0[0..nroot) with first positions pos1[0..nroot]).
+__global__ void __launch_bounds__(256) k_dense_pos(const int32_t *__restrict__ crd0, int64_t nroot,
+                                                   const int32_t *__restrict__ pos1, int64_t dim0, int64_t n,
+                                                   int32_t *__restrict__ out) {
+    int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (r > dim0) return;
+    int64_t lo = 0, hi = nroot;                  // first stored row with coordinate >= r
+    while (lo < hi) {
+        int64_t mid = lo + ((hi - lo) >> 1);
+        if (crd0[mid] < r) lo = mid + 1; else hi = mid;
+    }
+    out[r] = lo < nroot ? pos1[lo] : (int32_t)n;
+}
+
 }  // namespace
+
+hipError_t reorder_unpack_keys(const uint64_t *keys, int64_t n, const KeyLayout &lay, int order, const CuLevels &out,
+                               hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_unpack_keys, dim3(blocks_for(n, 256)), dim3(256), 0, st, keys, n, lay, order, out);
+    return hipGetLastError();
+}
+
+hipError_t reorder_dense_pos(const int32_t *crd0, int64_t nroot, const int32_t *pos1, int64_t dim0, int64_t n,
+                             int32_t *out, hipStream_t st) {
+    hipLaunchKernelGGL(k_dense_pos, dim3(blocks_for(dim0 + 1, 256)), dim3(256), 0, st, crd0, nroot, pos1, dim0, n, out);
+    return hipGetLastError();
+}
 
 hipError_t reorder_pack_keys(const CoordSource &src, const KeyLayout &lay, uint64_t *keys, hipStream_t st) {
     if (src.nnz <= 0) return hipSuccess;

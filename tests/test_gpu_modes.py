@@ -65,8 +65,10 @@ def check_levels(T, want):
     assert T.levels() == list(want.tags)
     assert T.dims() == list(want.dims)
     for l in range(len(want.dims)):
-        assert_index_equal(np_(T.pos(l)), np_(want.pos[l]), "pos[%d]" % l)
-        assert_index_equal(np_(T.crd(l)), np_(want.crd[l]), "crd[%d]" % l)
+        for what, got, ref in (("pos", T.pos(l), want.pos[l]), ("crd", T.crd(l), want.crd[l])):
+            assert (got is None) == (ref is None), "%s[%d] present on one side only" % (what, l)
+            if ref is not None:
+                assert_index_equal(np_(got), np_(ref), "%s[%d]" % (what, l))
     assert np.array_equal(np_(T.vals()), np_(want.vals))      # values are moved, never recomputed
 
 
@@ -167,6 +169,63 @@ def test_matrix_conversion_and_transpose(comet, name, layout):
     torch.cuda.synchronize()
     ref, absum = oracle.spmv(np_(cols), np_(rows), np_(vals), (ncols, nrows), np_(x))
     assert_values_close(np_(y), ref, absum, "transposed spmv %s" % name)
+
+
+@pytest.mark.parametrize("target", ["csr", "dcsr", "coo"])
+@pytest.mark.parametrize("layout", ["csr", "dcsr", "coo_shuffled"])
+@pytest.mark.parametrize("name", ["zipf_rows", "edge_lengths", "hypersparse", "empty", "single"])
+def test_matrix_format_conversion(comet, name, layout, target):
+    """COO (in any order) / CSR / DCSR to CSR / DCSR / sorted COO, straight and transposed: level arrays
+    bit for bit against the packers, then a product through the converted handle against the oracle."""
+    (nrows, ncols), (rows, cols, vals) = MATRIX_CASES[name]
+    say("convert case=%s %s -> %s nnz=%d" % (name, layout, target, vals.numel()))
+    if layout == "csr":
+        X = comet.from_levels(fmt.pack_csr(nrows, ncols, rows, cols, vals).to("cuda"))
+    elif layout == "dcsr":
+        X = comet.from_levels(fmt.pack_dcsr(nrows, ncols, rows, cols, vals).to("cuda"))
+    else:
+        p = torch.randperm(vals.numel(), generator=torch.Generator().manual_seed(13))
+        X = comet.from_levels(fmt.pack_coo((nrows, ncols), (rows[p], cols[p]), vals[p]).to("cuda"), flags=0)
+    tags = {"csr": [0, 1], "dcsr": [1, 1], "coo": [2, 3]}[target]
+    pack = {"csr": fmt.pack_csr, "dcsr": fmt.pack_dcsr,
+            "coo": lambda a, b, r, c, v: fmt.pack_coo((a, b), (r, c), v)}[target]
+    T = comet.comet_tensor_convert(X, (0, 1), tags)
+    check_levels(T, pack(nrows, ncols, rows, cols, vals))
+    keys = np.lexsort(np.stack([np_(rows), np_(cols)])) if vals.numel() else np.zeros(0, dtype=np.int64)
+    perm = torch.from_numpy(keys)
+    Tt = comet.comet_tensor_convert(X, (1, 0), tags)
+    check_levels(Tt, pack(ncols, nrows, cols[perm], rows[perm], vals[perm]))
+    assert Tt.mode_of_level() == [1, 0]
+    if target != "coo":
+        x = gen.dense_operand(25, 0, (ncols,))
+        y = comet.comet_spmv(T, dev(x))
+        torch.cuda.synchronize()
+        ref, absum = oracle.spmv(np_(rows), np_(cols), np_(vals), (nrows, ncols), np_(x))
+        assert_values_close(np_(y), ref, absum, "spmv through converted %s" % target)
+
+
+@pytest.mark.parametrize("name", ["zipf_ttv", "mode_of_two", "empty", "single"])
+def test_tensor_to_sorted_coordinate_list(comet, name):
+    dims, (i, j, k, vals) = TENSOR_CASES[name]
+    X = source_handle(comet, dims, (i, j, k), vals, "csf")
+    for perm in ((0, 1, 2), (2, 0, 1)):
+        T = comet.comet_tensor_convert(X, perm, [2, 3, 3])
+        (a, b, c), sv = sorted_by((i, j, k), vals, perm)
+        check_levels(T, fmt.pack_coo([dims[m] for m in perm], (a, b, c), sv))
+        if name != "empty":                      # and it is accepted as a validated sorted list again
+            v = gen.dense_operand(26, 0, (dims[perm[2]],))
+            Y = comet.comet_ttv(T, perm[2], dev(v))
+            # the result follows the handle's level order: pairs of (mode perm[0], mode perm[1])
+            co = (i, j, k)
+            ref = oracle.ttv(np_(co[perm[0]]), np_(co[perm[1]]), np_(co[perm[2]]), np_(vals),
+                             [dims[m] for m in perm], np_(v))
+            torch.cuda.synchronize()
+            assert_index_equal(np_(Y.crd(0)), ref["i"], "coo result crd0")
+            assert_index_equal(np_(Y.crd(1)), ref["j"], "coo result crd1")
+            assert_values_close(np_(Y.vals()), ref["vals"], ref["abs"], "ttv on converted coo")
+    with pytest.raises(comet.CometError) as e:
+        comet.comet_tensor_convert(X, (0, 1, 2), [0, 1, 1])
+    assert e.value.status == 4
 
 
 def test_reorder_errors(comet):
