@@ -26,7 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-ALL_OPS = ["spmm", "spmv", "ttv", "ttv_coo", "ttm", "mttkrp16", "mttkrp64", "ttv_m0", "ttm_m0", "mttkrp16_m1"]
+ALL_OPS = ["spmm", "spmv", "ttv", "ttv_coo", "ttm", "mttkrp16", "mttkrp64", "ttv_m0", "ttm_m0", "mttkrp16_m1", "spmm_dcsr"]
 # "<op>_m<n>": the same operation along / for mode n of the same tensor, on the storage that
 # comet_tensor_reorder builds for it (first-mode TTV and TTM are the forms Section 8.2 writes out)
 
@@ -166,12 +166,12 @@ def run_op(op, args, comet, dev):
         desc = "SpMV CSR %dx%d, %d nnz (10 per row)" % (n, n, nnz)
         extra = {"nnz": nnz, "rows": n}
         keep = dict(A=A, L=L, x=x, y=y)
-    elif op == "spmm":
+    elif op in ("spmm", "spmm_dcsr"):
         c = gen.config_spmm(seed=0, device=dev, scale=sc, R=32)
         rows, cols, vals = c["coo"]
         n = c["dims"][0]
         R = 32
-        L = fmt.pack_csr(n, n, rows, cols, vals)
+        L = fmt.pack_csr(n, n, rows, cols, vals) if op == "spmm" else fmt.pack_dcsr(n, n, rows, cols, vals)
         A = comet.from_levels(L).set_variant(args.variant)
         B, C = c["B"], torch.empty((n, R), dtype=torch.float64, device=dev)
         fn = lambda: comet.comet_spmm(A, B, C)
@@ -179,7 +179,7 @@ def run_op(op, args, comet, dev):
         touched = count_distinct(cols)
         flops = 2 * R * nnz
         nbytes = 12 * nnz + (4 + 8 * R) * n + 8 * R * touched
-        desc = "SpMM CSR %dx%d, %d nnz, Zipf(1.8) rows capped at 10000, B %dx%d" % (n, n, nnz, n, R)
+        desc = "SpMM %s %dx%d, %d nnz, Zipf(1.8) rows capped at 10000, B %dx%d" % ("CSR" if op == "spmm" else "DCSR", n, n, nnz, n, R)
         extra = {"nnz": nnz, "rows": n, "R": R, "touched_B_rows": touched, "gather_bytes": 8 * R * nnz,
                  "touched_row_bytes": 8 * R * touched}
         keep = dict(A=A, L=L, B=B, C=C, coo=(rows, cols, vals), n=n)

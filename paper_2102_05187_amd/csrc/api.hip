@@ -546,9 +546,13 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
     const int64_t nseg = A->pos_len[1] - 1, nnz = A->nvals;
     const int32_t *rowmap = nullptr;
     if (A->fmt == Format::DCSR) {
-        // rows absent from the root level hold no nonzeros: clear the result, then scatter rows
+        // Rows absent from the root level hold no nonzeros and must come out as zeros.  Every stored row is
+        // written by the kernels below (also one without nonzeros), so when most rows are stored only
+        // the gaps between them are cleared; otherwise, or when there is nothing to run, the whole result.
         rowmap = A->crd_i(0);
-        HIP_TRY(comet::fill_zero_f64(out, A->dims[0] * R, st));
+        const int64_t nstored = A->crd_len[0];
+        if (nnz > 0 && nstored * 2 >= A->dims[0]) HIP_TRY(comet::zero_unstored_rows(rowmap, nstored, A->dims[0], R, out, st));
+        else HIP_TRY(comet::fill_zero_f64(out, A->dims[0] * R, st));
     }
     if (nnz == 0) {
         if (A->fmt == Format::CSR) HIP_TRY(comet::fill_zero_f64(out, A->dims[0] * R, st));
