@@ -166,6 +166,21 @@ def run_op(op, args, comet, dev):
         desc = "SpMV CSR %dx%d, %d nnz (10 per row)" % (n, n, nnz)
         extra = {"nnz": nnz, "rows": n}
         keep = dict(A=A, L=L, x=x, y=y)
+    elif op == "spmv_large":
+        # the SpMM matrix with one dense column: x (8 MB) does not fit in LDS, gathers go through L1 / L2
+        c = gen.config_spmm(seed=0, device=dev, scale=sc, R=1)
+        rows, cols, vals = c["coo"]
+        n = c["dims"][0]
+        L = fmt.pack_csr(n, n, rows, cols, vals)
+        A = comet.from_levels(L).set_variant(args.variant)
+        x, y = c["B"].reshape(-1).contiguous(), torch.empty(n, dtype=torch.float64, device=dev)
+        fn = lambda: comet.comet_spmv(A, x, y)
+        nnz = vals.numel()
+        flops = 2 * nnz
+        nbytes = 12 * nnz + 12 * n + 8 * n
+        desc = "SpMV CSR %dx%d, %d nnz, Zipf(1.8) rows capped at 10000" % (n, n, nnz)
+        extra = {"nnz": nnz, "rows": n}
+        keep = dict(A=A, L=L, x=x, y=y)
     elif op in ("spmm", "spmm_dcsr"):
         c = gen.config_spmm(seed=0, device=dev, scale=sc, R=32)
         rows, cols, vals = c["coo"]

@@ -130,7 +130,7 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
                             for (int q = 0; q < V; ++q) first[q] = sacc[q];
                             first_row = tmr; ht = 1;
                         } else {
-                            grp_store_row<L, V, WIDE>(M, tmr, R, j, sacc);
+                            grp_store_row_stream<L, V, WIDE>(M, tmr, R, j, sacc);
                         }
 #pragma unroll
                         for (int q = 0; q < V; ++q) sacc[q] = 0.0;
