@@ -365,3 +365,52 @@ def test_empty_slices_and_fibers_are_accepted_and_contribute_nothing(comet):
         refM, absM = oracle.mttkrp(coords[:, 0], coords[:, 1], coords[:, 2], vals, dims, np_(B), np_(C))
         assert_values_close(np_(M), refM, absM, "mttkrp with an empty slice")
         assert bool((M[1] == 0).all()) and bool((M[2] == 0).all())
+
+
+def test_operations_replay_from_a_captured_graph(comet):
+    """After a first (allocating) call every operation only enqueues kernels, so it can be captured into a
+    HIP graph; each replay -- with eager work and synchronisations in between -- must reproduce the eager
+    result bit for bit (the kernels use no atomics and clear their scratch themselves)."""
+    (n, m), (rows, cols, vals) = MATRIX_CASES["zipf_rows"]
+    A = comet.from_levels(fmt.pack_csr(n, m, rows, cols, vals).to("cuda"))
+    dims, (i, j, k, tv) = TENSOR_CASES["zipf_mttkrp"]
+    X = comet.from_levels(fmt.pack_csf3(dims, i, j, k, tv).to("cuda"))
+    R = 16
+    B = dev(gen.dense_operand(41, 0, (m, R)))
+    x = dev(gen.dense_operand(41, 1, (m,)))
+    U = dev(gen.dense_operand(41, 2, (dims[2], R)))
+    Fb, Fc = dev(gen.dense_operand(41, 3, (dims[1], R))), U
+    v = dev(gen.dense_operand(41, 4, (dims[2],)))
+    C = torch.empty((n, R), dtype=torch.float64, device="cuda")
+    y = torch.empty(n, dtype=torch.float64, device="cuda")
+    M = torch.empty((dims[0], R), dtype=torch.float64, device="cuda")
+    Yv = comet.comet_ttv(X, 2, v)
+    Ym = comet.comet_ttm(X, 2, U)
+
+    def run_all():
+        comet.comet_spmm(A, B, C)
+        comet.comet_spmv(A, x, y)
+        comet.comet_ttv(X, 2, v, Yv)
+        comet.comet_ttm(X, 2, U, Ym)
+        comet.comet_mttkrp(X, 0, [None, Fb, Fc], M)
+
+    run_all()                                    # first calls: scratch gets allocated here
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (C, y, M, Yv.vals(), Ym.vals())]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run_all()                                # warm-up on the capture stream
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        run_all()
+    for rep in range(3):
+        for t in (C, y, M):
+            t.fill_(float("nan"))                # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = (C, y, M, Yv.vals(), Ym.vals())
+        for a, b in zip(got, want):
+            assert torch.equal(a, b), "replay %d differs from the eager result" % rep
