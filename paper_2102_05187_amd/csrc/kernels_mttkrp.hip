@@ -81,7 +81,9 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
     for (int q = 0; q < V; ++q) { facc[q] = 0.0; sacc[q] = 0.0; first[q] = 0.0; }
     int ht = 0, first_row = -1, first_fid = -1, last_is_tail = 1;
 
-    constexpr int G = StepGroup<V>::value, NG = SB / G;
+    // narrow rows: two steps per pipeline group instead of four keeps the kernel under 128 registers
+    // (four wavefronts per SIMD instead of three), which is worth more here than the deeper gather queue
+    constexpr int G = V <= 2 ? 2 : StepGroup<V>::value, NG = SB / G;
     for (int sb = 0; sb < WI / SB; ++sb) {
         const int64_t i0 = gb + SB * sb + 4 * j;
         LaneItems nxt;
