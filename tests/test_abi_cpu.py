@@ -59,3 +59,17 @@ def test_binding_refuses_host_tensors():
     with pytest.raises(TypeError):
         comet.comet_tensor_create([2, 2], [0, 1], [torch.tensor([2], dtype=torch.int32), torch.tensor([0, 1, 2], dtype=torch.int32)],
                                   [None, torch.tensor([0, 1], dtype=torch.int32)], torch.ones(2, dtype=torch.float64))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build runs on one GPU only: `bench.py --gpus N` with N > 1 must say so and exit without
+    touching a GPU (this also holds under a multi-rank launcher, via WORLD_SIZE)."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode == 2
+    assert "one GPU" in res.stderr
+    assert res.stdout.strip() == ""
+    env = dict(os.environ, WORLD_SIZE="2")
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py")], capture_output=True, text=True, env=env)
+    assert res.returncode == 2 and "one GPU" in res.stderr
