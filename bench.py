@@ -36,21 +36,29 @@ def log(*a):
 
 
 def time_steps(fn, steps, warmup):
-    """Mean and median milliseconds of `steps` calls of fn, bracketed by events on the current stream."""
+    """Mean milliseconds of `steps` back-to-back calls of fn (one event pair around the whole run, on the
+    current stream, synchronised on both sides), then per-call median / min from a second, separately
+    timed run with an event pair per call (those events would otherwise sit between the timed calls)."""
     import torch
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    first, last = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    first.record()
+    for _ in range(steps):
+        fn()
+    last.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    total = first.elapsed_time(last) / steps
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
     for a, b in evs:
         a.record()
         fn()
         b.record()
     torch.cuda.synchronize()
-    wall = (time.perf_counter() - t0) * 1e3 / steps
     per = sorted(a.elapsed_time(b) for a, b in evs)
-    total = evs[0][0].elapsed_time(evs[-1][1]) / steps
     return {"mean_ms": total, "median_ms": per[len(per) // 2], "min_ms": per[0], "wall_ms": wall}
 
 
