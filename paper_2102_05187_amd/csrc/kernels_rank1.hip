@@ -267,15 +267,25 @@ __global__ void __launch_bounds__(1024) k_stream_rank1_ldsvec(const int32_t *__r
         int base_id;
         if constexpr (COO) {
             constexpr int kRows = kChunk / 64, kBatch = 4;
-            unsigned long long hm[kRows], hx[kRows];     // run starts; the same with items past the end counted as starts
+            // run starts of a row of 64 items (hm), and the same with items past the end counted as starts (hx);
+            // the mask of run ENDS of row r-1 is written as soon as row r is known, so only one row is kept
+            unsigned long long hx_prev = 0ull;
+            bool first_is_head = false;
             const int runs_before = chunk_begin[c];
-            // all coordinate loads of the chunk are issued together; the predecessor of an item comes from the
-            // neighbouring lane (wave_shr:1), of lane 0 from the previous row (or the item before the chunk)
+            // the coordinate loads of a batch of rows are issued together; the predecessor of an item comes from
+            // the neighbouring lane (wave_shr:1), of lane 0 from the previous row (or the item before the chunk)
             const int64_t inext = cbeg + kChunk;
             int before0 = -2, before1 = -2, after0 = -1, after1 = -1;
             if (cbeg > 0) { before0 = c0[cbeg - 1]; before1 = c1[cbeg - 1]; }
             if (inext < nnz) { after0 = c0[inext]; after1 = c1[inext]; }
             int running = runs_before;
+            // item e ends a run when item e+1 starts one or lies past the end of the list
+            auto write_ends = [&](int r, unsigned long long hx_r, unsigned long long nextbit) {
+                const int64_t left = nnz - (cbeg + 64 * r);          // items of this row that exist
+                const unsigned long long exist = left >= 64 ? ~0ull : (left <= 0 ? 0ull : ((1ull << left) - 1ull));
+                const unsigned long long tmask = ((hx_r >> 1) | (nextbit << 63)) & exist;
+                if (lane == 0) *reinterpret_cast<unsigned long long *>(bits + 2 * r) = tmask;
+            };
 #pragma unroll
             for (int rb = 0; rb < kRows; rb += kBatch) {          // batches of rows keep the register count down
                 int a0[kBatch], a1[kBatch];
@@ -292,28 +302,22 @@ __global__ void __launch_bounds__(1024) k_stream_rank1_ldsvec(const int32_t *__r
                     const int p0 = dpp_i<0x138, 0xf>(before0, a0[q]);
                     const int p1 = dpp_i<0x138, 0xf>(before1, a1[q]);
                     const bool differs = a0[q] != p0 || a1[q] != p1;
-                    hm[r] = __ballot(differs && i < nnz);
-                    hx[r] = __ballot(differs);
+                    const unsigned long long hm = __ballot(differs && i < nnz);
+                    const unsigned long long hx = __ballot(differs);
                     before0 = __builtin_amdgcn_readlane(a0[q], 63);
                     before1 = __builtin_amdgcn_readlane(a1[q], 63);
-                    if ((hm[r] >> lane) & 1ull) {
-                        const int id = running + __popcll(hm[r] & lt_mask);
+                    if ((hm >> lane) & 1ull) {
+                        const int id = running + __popcll(hm & lt_mask);
                         y0[id] = a0[q]; y1[id] = a1[q];
                     }
-                    running += __popcll(hm[r]);
+                    running += __popcll(hm);
+                    if (r == 0) first_is_head = (hm & 1ull) != 0ull;
+                    else write_ends(r - 1, hx_prev, hx & 1ull);
+                    hx_prev = hx;
                 }
             }
-            const bool next_head = after0 != before0 || after1 != before1;
-#pragma unroll
-            for (int r = 0; r < kRows; ++r) {
-            // item e ends a run when item e+1 starts one or lies past the end of the list
-                const unsigned long long nextbit = r + 1 < kRows ? (hx[r + 1] & 1ull) : (next_head ? 1ull : 0ull);
-                const int64_t left = nnz - (cbeg + 64 * r);          // items of this row that exist
-                const unsigned long long exist = left >= 64 ? ~0ull : (left <= 0 ? 0ull : ((1ull << left) - 1ull));
-                const unsigned long long tmask = ((hx[r] >> 1) | (nextbit << 63)) & exist;
-                if (lane == 0) *reinterpret_cast<unsigned long long *>(bits + 2 * r) = tmask;
-            }
-            base_id = runs_before - ((hm[0] & 1ull) ? 0 : 1);        // the run that holds the chunk's first item
+            write_ends(kRows - 1, hx_prev, (after0 != before0 || after1 != before1) ? 1ull : 0ull);
+            base_id = runs_before - (first_is_head ? 0 : 1);          // the run that holds the chunk's first item
         } else {
             if (lane < 32) bits[lane] = 0u;
             __builtin_amdgcn_wave_barrier();
