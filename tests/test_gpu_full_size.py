@@ -206,3 +206,59 @@ def test_first_mode_ttv_config(comet, ttv_config):
     ref = oracle.ttv_mode((np_(c2[idx]), np_(c0[idx]), np_(c1[idx])), np_(Xr.vals()[idx]), dims, 0, np_(v))
     assert len(ref["vals"]) == fids.numel()
     assert_values_close(np_(Y.vals()[fids]), ref["vals"], ref["abs"], "first-mode ttv sampled fibers")
+
+
+def test_first_mode_ttm_config(comet):
+    """TTM along the first mode at the benchmark size (the form Section 8.2 writes out), on the tensor
+    re-stored in the order (1, 2, 0); sampled output fibers against the oracle."""
+    c = gen.config_ttm(seed=0, device=DEV, R=16)
+    i, j, k, vals = c["coo"]
+    dims = c["dims"]
+    X = comet.from_levels(fmt.pack_csf3(dims, i, j, k, vals))
+    Xr = comet.comet_tensor_reorder(X, (1, 2, 0))
+    torch.cuda.synchronize()
+    say("first-mode ttm full size nnz=%d fibers=%d" % (vals.numel(), Xr.crd(1).numel()))
+    U = gen.dense_operand(0, 8, (dims[0], 16), DEV)
+    Y = comet.comet_ttm(Xr, 0, U)
+    torch.cuda.synchronize()
+    assert Y.levels() == [1, 1, 0] and Y.dims() == [dims[1], dims[2], 16] and Y.mode_of_level()[:2] == [1, 2]
+    c0, c1, c2, _ = _expand_csf(Xr)
+    pos3 = Xr.pos(2).to(torch.int64)
+    lens = pos3[1:] - pos3[:-1]
+    heavy = torch.topk(lens, 4).indices.cpu()
+    fids = sample_ids(lens.numel(), 3000, heavy, 7)
+    idx, which = ranges_to_index(pos3[fids], pos3[fids + 1])
+    ref = oracle.ttm_mode((np_(c2[idx]), np_(c0[idx]), np_(c1[idx])), np_(Xr.vals()[idx]), dims, 0, np_(U))
+    assert len(ref["vals"]) == fids.numel()
+    assert_values_close(np_(Y.vals().reshape(-1, 16)[fids]), ref["vals"], ref["abs"], "first-mode ttm sampled fibers")
+
+
+def test_second_mode_mttkrp_config(comet):
+    """MTTKRP for the second mode at the benchmark size, on the tensor re-stored in the order (1, 0, 2);
+    sampled output rows (the heaviest slices among them) against the oracle."""
+    R = 16
+    c = gen.config_mttkrp(seed=0, device=DEV, R=R)
+    i, j, k, vals = c["coo"]
+    dims = c["dims"]
+    X = comet.from_levels(fmt.pack_csf3(dims, i, j, k, vals))
+    Xr = comet.comet_tensor_reorder(X, (1, 0, 2))
+    del X
+    torch.cuda.synchronize()
+    F = [gen.dense_operand(0, 8 + m, (dims[m], R), DEV) for m in range(3)]
+    M = torch.full((dims[1], R), float("nan"), dtype=torch.float64, device=DEV)
+    comet.comet_mttkrp(Xr, 1, [F[0], None, F[2]], M)
+    torch.cuda.synchronize()
+    pos2, pos3 = Xr.pos(1).to(torch.int64), Xr.pos(2).to(torch.int64)
+    first, last = pos3[pos2[:-1]], pos3[pos2[1:]]
+    heavy = torch.topk(last - first, 2).indices.cpu()
+    sids = sample_ids(first.numel(), 500, heavy, 8)
+    idx, which = ranges_to_index(first[sids], last[sids])
+    say("second-mode mttkrp full size: oracle on %d nonzeros of %d sampled slices" % (idx.numel(), sids.numel()))
+    c0, c1, c2, _ = _expand_csf(Xr)            # level coordinates: (mode 1, mode 0, mode 2)
+    ref, absum = oracle.mttkrp(np_(which), np_(c1[idx]), np_(c2[idx]), np_(Xr.vals()[idx]),
+                               (sids.numel(), dims[0], dims[2]), np_(F[0]), np_(F[2]))
+    rows = Xr.crd(0).to(torch.int64)[sids]
+    assert_values_close(np_(M[rows]), ref, absum, "second-mode mttkrp sampled slices")
+    stored = torch.zeros(dims[1], dtype=torch.bool, device=DEV)
+    stored[Xr.crd(0).to(torch.int64)] = True
+    assert bool((M[~stored] == 0.0).all()) and not bool(torch.isnan(M).any())
