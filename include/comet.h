@@ -138,10 +138,12 @@ comet_status comet_tensor_info(const comet_tensor *t, comet_tensor_info_t *info)
  *   out         host; receives a new handle that owns all its arrays (nothing is shared with X) and
  *               reports the order in comet_tensor_info_t::mode_of_level.  Its dims are per level.
  *
- * Work: one key/value radix sort of the nonzeros on the device plus a few streaming passes;
- * temporary device memory of about 40 bytes per nonzero.  Synchronises with `stream`.
+ * Work: one key/value radix sort of the nonzeros on the device plus a few streaming passes (two
+ * sorts when the bit widths of the three mode sizes add up to more than 64, as for tensors whose
+ * modes all run into the millions); temporary device memory of about 40 to 60 bytes per nonzero.
+ * Synchronises with `stream`.
  * Errors: COMET_ERR_INVALID_ARG if mode_order is not a permutation; COMET_ERR_UNSUPPORTED if the
- * bit widths of the mode sizes add up to more than 64 or the format is not listed above;
+ * format is not listed above;
  * COMET_ERR_BAD_FORMAT if two nonzeros have the same coordinates (coordinates out of range are not
  * detected here: use COMET_VALIDATE at creation for sorted input).
  */

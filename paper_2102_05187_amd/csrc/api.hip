@@ -386,7 +386,9 @@ static comet_status restore(const comet_tensor *X, const int32_t *mode_order, Ta
         bits[l] = bit_width(X->dims[s]);
         total_bits += bits[l];
     }
-    if (total_bits > 64) return COMET_ERR_UNSUPPORTED;           // the packed coordinate must fit one key
+    // Up to 64 bits the whole coordinate is one sort key; beyond that (three large modes) the root level's
+    // coordinate is kept apart and the sort takes two stable passes.
+    const bool wide = total_bits > 64;
     for (int l = order - 1, sh = 0; l >= 0; --l) {
         lay.shift[l] = sh;
         lay.mask[l] = bits[l] >= 64 ? ~uint64_t(0) : (uint64_t(1) << bits[l]) - 1;
@@ -407,7 +409,8 @@ static comet_status restore(const comet_tensor *X, const int32_t *mode_order, Ta
 
     const int64_t n = X->nvals;
     int64_t nmid = 0, nroot = 0;        // order 3: #(root,middle) prefixes and #root coordinates; order 2: nroot only
-    DevRef keys, flags, before;
+    DevRef keys, rootc, flags, before;
+    const uint32_t *rootp = nullptr;    // sorted root coordinates when the key is wide
     if (n > 0) {
         DevRef raw = comet::dev_alloc(sizeof(uint64_t) * n);
         keys = comet::dev_alloc(sizeof(uint64_t) * n);
@@ -416,16 +419,46 @@ static comet_status restore(const comet_tensor *X, const int32_t *mode_order, Ta
         before = comet::dev_alloc(sizeof(uint64_t) * n);
         DevRef err = comet::dev_alloc(sizeof(int32_t));
         if (!raw || !keys || !t->vals || !flags || !before || !err) return COMET_ERR_ALLOC;
-        HIP_TRY(comet::reorder_pack_keys(src, lay, (uint64_t *)raw->ptr, st));
-        size_t tb = 0;
-        HIP_TRY(comet::reorder_sort_pairs(nullptr, &tb, (const uint64_t *)raw->ptr, (uint64_t *)keys->ptr, X->vals_d(),
-                                          (double *)t->vals->ptr, n, total_bits, st));
-        DevRef temp = comet::dev_alloc(tb);
-        if (!temp) return COMET_ERR_ALLOC;
-        HIP_TRY(comet::reorder_sort_pairs(temp->ptr, &tb, (const uint64_t *)raw->ptr, (uint64_t *)keys->ptr, X->vals_d(),
-                                          (double *)t->vals->ptr, n, total_bits, st));
+        DevRef temp;
+        if (!wide) {
+            HIP_TRY(comet::reorder_pack_keys(src, lay, (uint64_t *)raw->ptr, nullptr, st));
+            size_t tb = 0;
+            HIP_TRY(comet::reorder_sort_pairs(nullptr, &tb, (const uint64_t *)raw->ptr, (uint64_t *)keys->ptr, X->vals_d(),
+                                              (double *)t->vals->ptr, n, total_bits, st));
+            temp = comet::dev_alloc(tb);
+            if (!temp) return COMET_ERR_ALLOC;
+            HIP_TRY(comet::reorder_sort_pairs(temp->ptr, &tb, (const uint64_t *)raw->ptr, (uint64_t *)keys->ptr, X->vals_d(),
+                                              (double *)t->vals->ptr, n, total_bits, st));
+        } else {
+            // pass 1: order by (middle, last) carrying the nonzero's number; pass 2: stable order by root
+            DevRef root_raw = comet::dev_alloc(sizeof(uint32_t) * n), root_1 = comet::dev_alloc(sizeof(uint32_t) * n);
+            DevRef idx_a = comet::dev_alloc(sizeof(uint32_t) * n), idx_b = comet::dev_alloc(sizeof(uint32_t) * n);
+            rootc = comet::dev_alloc(sizeof(uint32_t) * n);
+            if (!root_raw || !root_1 || !idx_a || !idx_b || !rootc) return COMET_ERR_ALLOC;
+            uint64_t *lo_raw = (uint64_t *)raw->ptr, *lo_tmp = (uint64_t *)keys->ptr;
+            HIP_TRY(comet::reorder_pack_keys(src, lay, lo_raw, (uint32_t *)root_raw->ptr, st));
+            HIP_TRY(comet::reorder_iota((uint32_t *)idx_a->ptr, n, st));
+            size_t tb1 = 0, tb2 = 0;
+            HIP_TRY(comet::reorder_sort_lo(nullptr, &tb1, lo_raw, lo_tmp, (const uint32_t *)idx_a->ptr, (uint32_t *)idx_b->ptr, n,
+                                           bits[1] + bits[2], st));
+            HIP_TRY(comet::reorder_sort_hi(nullptr, &tb2, (const uint32_t *)root_1->ptr, (uint32_t *)rootc->ptr,
+                                           (const uint32_t *)idx_b->ptr, (uint32_t *)idx_a->ptr, n, bits[0], st));
+            temp = comet::dev_alloc(tb1 > tb2 ? tb1 : tb2);
+            if (!temp) return COMET_ERR_ALLOC;
+            HIP_TRY(comet::reorder_sort_lo(temp->ptr, &tb1, lo_raw, lo_tmp, (const uint32_t *)idx_a->ptr, (uint32_t *)idx_b->ptr, n,
+                                           bits[1] + bits[2], st));
+            HIP_TRY(comet::reorder_gather_u32((const uint32_t *)root_raw->ptr, (const uint32_t *)idx_b->ptr,
+                                              (uint32_t *)root_1->ptr, n, st));
+            HIP_TRY(comet::reorder_sort_hi(temp->ptr, &tb2, (const uint32_t *)root_1->ptr, (uint32_t *)rootc->ptr,
+                                           (const uint32_t *)idx_b->ptr, (uint32_t *)idx_a->ptr, n, bits[0], st));
+            // idx_a = final order; bring the (middle, last) keys and the values into it
+            HIP_TRY(comet::reorder_gather_pairs(lo_raw, X->vals_d(), (const uint32_t *)idx_a->ptr, lo_tmp,
+                                                (double *)t->vals->ptr, n, st));
+            HIP_TRY(hipStreamSynchronize(st));  // the index and root scratch arrays go out of scope here
+            rootp = (const uint32_t *)rootc->ptr;
+        }
         HIP_TRY(hipMemsetAsync(err->ptr, 0, sizeof(int32_t), st));
-        HIP_TRY(comet::reorder_mark_heads((const uint64_t *)keys->ptr, n, lay, order, (uint64_t *)flags->ptr,
+        HIP_TRY(comet::reorder_mark_heads((const uint64_t *)keys->ptr, rootp, n, lay, order, (uint64_t *)flags->ptr,
                                           (int32_t *)err->ptr, st));
         size_t sb = 0;
         HIP_TRY(comet::reorder_scan_flags(nullptr, &sb, (const uint64_t *)flags->ptr, (uint64_t *)before->ptr, n, st));
@@ -465,7 +498,7 @@ static comet_status restore(const comet_tensor *X, const int32_t *mode_order, Ta
         int32_t h[2] = {0, (int32_t)n};
         HIP_TRY(hipMemcpyAsync(t->pos[0]->ptr, h, sizeof h, hipMemcpyHostToDevice, st));
         HIP_TRY(hipStreamSynchronize(st));
-        if (n > 0) HIP_TRY(comet::reorder_unpack_keys((const uint64_t *)keys->ptr, n, lay, order, lv, st));
+        if (n > 0) HIP_TRY(comet::reorder_unpack_keys((const uint64_t *)keys->ptr, rootp, n, lay, order, lv, st));
     } else {
         const int64_t count[3] = {nroot, order == 3 ? nmid : n, n};   // positions per level (order 2 uses [0], [1])
         for (int l = 0; l < order; ++l) {
@@ -484,7 +517,7 @@ static comet_status restore(const comet_tensor *X, const int32_t *mode_order, Ta
             HIP_TRY(hipStreamSynchronize(st));
         }
         if (n > 0) {
-            HIP_TRY(comet::reorder_cut_levels((const uint64_t *)keys->ptr, (const uint64_t *)flags->ptr,
+            HIP_TRY(comet::reorder_cut_levels((const uint64_t *)keys->ptr, rootp, (const uint64_t *)flags->ptr,
                                               (const uint64_t *)before->ptr, n, lay, order, lv, st));
         } else {
             for (int l = 1; l < order; ++l) HIP_TRY(hipMemsetAsync(lv.pos[l], 0, sizeof(int32_t), st));

@@ -70,7 +70,19 @@ struct CuLevels {
     int32_t *pos[3] = {nullptr, nullptr, nullptr};
     int32_t *crd[3] = {nullptr, nullptr, nullptr};
 };
-hipError_t reorder_pack_keys(const CoordSource &src, const KeyLayout &lay, uint64_t *keys, hipStream_t st);
+// keys[p] = packed coordinates of nonzero p.  When the three bit fields do not fit 64 bits (`root` non-null)
+// the key holds the middle and last level only and the root level's coordinate goes to root[p].
+hipError_t reorder_pack_keys(const CoordSource &src, const KeyLayout &lay, uint64_t *keys, uint32_t *root, hipStream_t st);
+// Pieces of the two-pass sort for keys wider than 64 bits (stable radix sorts; temp == nullptr only sets
+// *temp_bytes): order by (middle, last) carrying the nonzero's number, then by root carrying that order.
+hipError_t reorder_iota(uint32_t *out, int64_t n, hipStream_t st);
+hipError_t reorder_sort_lo(void *temp, size_t *temp_bytes, const uint64_t *keys_in, uint64_t *keys_out,
+                           const uint32_t *idx_in, uint32_t *idx_out, int64_t n, int key_bits, hipStream_t st);
+hipError_t reorder_sort_hi(void *temp, size_t *temp_bytes, const uint32_t *keys_in, uint32_t *keys_out,
+                           const uint32_t *idx_in, uint32_t *idx_out, int64_t n, int key_bits, hipStream_t st);
+hipError_t reorder_gather_u32(const uint32_t *src, const uint32_t *idx, uint32_t *out, int64_t n, hipStream_t st);
+hipError_t reorder_gather_pairs(const uint64_t *keys, const double *vals, const uint32_t *idx, uint64_t *keys_out,
+                                double *vals_out, int64_t n, hipStream_t st);
 // Both follow the two-call convention: temp == nullptr only sets *temp_bytes.
 hipError_t reorder_sort_pairs(void *temp, size_t *temp_bytes, const uint64_t *keys_in, uint64_t *keys_out,
                               const double *vals_in, double *vals_out, int64_t n, int key_bits, hipStream_t st);
@@ -78,15 +90,16 @@ hipError_t reorder_scan_flags(void *temp, size_t *temp_bytes, const uint64_t *fl
                               hipStream_t st);
 // flags: low half counts new (root, middle) prefixes (new rows for order 2), high half new root
 // coordinates (order 3).  *err |= 1 if two nonzeros share all coordinates.
-hipError_t reorder_mark_heads(const uint64_t *keys, int64_t n, const KeyLayout &lay, int order, uint64_t *flags,
-                              int32_t *err, hipStream_t st);
+// `root` (sorted like keys) is null unless the keys are the wide form described at reorder_pack_keys.
+hipError_t reorder_mark_heads(const uint64_t *keys, const uint32_t *root, int64_t n, const KeyLayout &lay, int order,
+                              uint64_t *flags, int32_t *err, hipStream_t st);
 // Sorted coordinate list out of the keys (crd[l][p] = field l), and the dense-root pos array of a CSR matrix
 // out of its compressed rows (out has dim0 + 1 entries).
-hipError_t reorder_unpack_keys(const uint64_t *keys, int64_t n, const KeyLayout &lay, int order, const CuLevels &out,
-                               hipStream_t st);
+hipError_t reorder_unpack_keys(const uint64_t *keys, const uint32_t *root, int64_t n, const KeyLayout &lay, int order,
+                               const CuLevels &out, hipStream_t st);
 hipError_t reorder_dense_pos(const int32_t *crd0, int64_t nroot, const int32_t *pos1, int64_t dim0, int64_t n,
                              int32_t *out, hipStream_t st);
-hipError_t reorder_cut_levels(const uint64_t *keys, const uint64_t *flags, const uint64_t *before, int64_t n,
-                              const KeyLayout &lay, int order, const CuLevels &out, hipStream_t st);
+hipError_t reorder_cut_levels(const uint64_t *keys, const uint32_t *root, const uint64_t *flags, const uint64_t *before,
+                              int64_t n, const KeyLayout &lay, int order, const CuLevels &out, hipStream_t st);
 
 }  // namespace comet

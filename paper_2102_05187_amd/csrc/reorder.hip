@@ -31,7 +31,8 @@ __device__ inline int32_t owner_of(const int32_t *__restrict__ pos, int32_t n, i
     return lo;
 }
 
-__global__ void __launch_bounds__(256) k_pack_keys(CoordSource src, KeyLayout lay, uint64_t *__restrict__ keys) {
+__global__ void __launch_bounds__(256) k_pack_keys(CoordSource src, KeyLayout lay, uint64_t *__restrict__ keys,
+                                                   uint32_t *__restrict__ root) {
     int64_t p64 = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p64 >= src.nnz) return;
     int32_t p = (int32_t)p64;
@@ -58,15 +59,39 @@ __global__ void __launch_bounds__(256) k_pack_keys(CoordSource src, KeyLayout la
     }
     }
     uint64_t key = 0;
-    for (int l = 0; l < src.order; ++l) key |= c[lay.src_level[l]] << lay.shift[l];
+    for (int l = root ? 1 : 0; l < src.order; ++l) key |= c[lay.src_level[l]] << lay.shift[l];
     keys[p] = key;
+    if (root) root[p] = (uint32_t)c[lay.src_level[0]];
+}
+
+// Coordinate of the root level of sorted nonzero p: a field of the key, or (wide keys) a separate array.
+__device__ __forceinline__ uint64_t root_of(const uint64_t *__restrict__ keys, const uint32_t *__restrict__ root,
+                                            int64_t p, int shift0) {
+    return root ? (uint64_t)root[p] : keys[p] >> shift0;
+}
+
+__global__ void __launch_bounds__(256) k_iota(uint32_t *__restrict__ out, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) out[i] = (uint32_t)i;
+}
+__global__ void __launch_bounds__(256) k_gather_u32(const uint32_t *__restrict__ src, const uint32_t *__restrict__ idx,
+                                                    uint32_t *__restrict__ out, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) out[i] = src[idx[i]];
+}
+__global__ void __launch_bounds__(256) k_gather_pairs(const uint64_t *__restrict__ keys, const double *__restrict__ vals,
+                                                      const uint32_t *__restrict__ idx, uint64_t *__restrict__ keys_out,
+                                                      double *__restrict__ vals_out, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) { const uint32_t s = idx[i]; keys_out[i] = keys[s]; vals_out[i] = vals[s]; }
 }
 
 // flags[p] = (first nonzero of a new root coordinate ? 1 << 32 : 0) | (first nonzero of a new
 // (root, middle) prefix ? 1 : 0); for order 2 only the low half is used (new row).  Equal
 // neighbouring keys mean one coordinate stored twice: *err is set.
-__global__ void __launch_bounds__(256) k_mark_heads(const uint64_t *__restrict__ keys, int64_t n, KeyLayout lay,
-                                                    int order, uint64_t *__restrict__ flags, int32_t *err) {
+__global__ void __launch_bounds__(256) k_mark_heads(const uint64_t *__restrict__ keys, const uint32_t *__restrict__ rootc,
+                                                    int64_t n, KeyLayout lay, int order, uint64_t *__restrict__ flags,
+                                                    int32_t *err) {
     int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p >= n) return;
     uint64_t k = keys[p];
@@ -75,20 +100,21 @@ __global__ void __launch_bounds__(256) k_mark_heads(const uint64_t *__restrict__
         f = order == 3 ? ((uint64_t(1) << 32) | 1u) : 1u;
     } else {
         uint64_t q = keys[p - 1];
-        if (q == k) atomicOr(err, 1);
+        const bool root = root_of(keys, rootc, p, lay.shift[0]) != root_of(keys, rootc, p - 1, lay.shift[0]);
+        if (q == k && !root) atomicOr(err, 1);
         if (order == 3) {
-            bool root = (k >> lay.shift[0]) != (q >> lay.shift[0]);
-            bool mid  = (k >> lay.shift[1]) != (q >> lay.shift[1]);
+            const bool mid = root || (k >> lay.shift[1]) != (q >> lay.shift[1]);
             f = (root ? (uint64_t(1) << 32) : 0) | (mid ? 1u : 0u);
         } else {
-            f = (k >> lay.shift[0]) != (q >> lay.shift[0]) ? 1u : 0u;
+            f = root ? 1u : 0u;
         }
     }
     flags[p] = f;
 }
 
 // `before[p]` = exclusive prefix sum of flags.  Writes the new levels (see CuLevels).
-__global__ void __launch_bounds__(256) k_cut_levels(const uint64_t *__restrict__ keys, const uint64_t *__restrict__ flags,
+__global__ void __launch_bounds__(256) k_cut_levels(const uint64_t *__restrict__ keys, const uint32_t *__restrict__ rootc,
+                                                    const uint64_t *__restrict__ flags,
                                                     const uint64_t *__restrict__ before, int64_t n, KeyLayout lay,
                                                     int order, CuLevels out) {
     int64_t p64 = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -104,7 +130,7 @@ __global__ void __launch_bounds__(256) k_cut_levels(const uint64_t *__restrict__
             out.pos[2][lo] = p;
         }
         if (f >> 32) {
-            out.crd[0][hi] = (int32_t)(k >> lay.shift[0]);
+            out.crd[0][hi] = (int32_t)root_of(keys, rootc, p64, lay.shift[0]);
             out.pos[1][hi] = lo;
         }
         if (p64 == n - 1) {
@@ -114,7 +140,7 @@ __global__ void __launch_bounds__(256) k_cut_levels(const uint64_t *__restrict__
         }
     } else {
         if (f & 1u) {
-            out.crd[0][lo] = (int32_t)(k >> lay.shift[0]);
+            out.crd[0][lo] = (int32_t)root_of(keys, rootc, p64, lay.shift[0]);
             out.pos[1][lo] = p;
         }
         if (p64 == n - 1) out.pos[1][lo + (int32_t)(f & 1u)] = (int32_t)n;
@@ -122,12 +148,13 @@ __global__ void __launch_bounds__(256) k_cut_levels(const uint64_t *__restrict__
 }
 
 // Coordinate-list output: level l of nonzero p is field l of its key.
-__global__ void __launch_bounds__(256) k_unpack_keys(const uint64_t *__restrict__ keys, int64_t n, KeyLayout lay, int order,
-                                                     CuLevels out) {
+__global__ void __launch_bounds__(256) k_unpack_keys(const uint64_t *__restrict__ keys, const uint32_t *__restrict__ rootc,
+                                                     int64_t n, KeyLayout lay, int order, CuLevels out) {
     int64_t p = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (p >= n) return;
     const uint64_t k = keys[p];
-    for (int l = 0; l < order; ++l) out.crd[l][p] = (int32_t)((k >> lay.shift[l]) & lay.mask[l]);
+    out.crd[0][p] = (int32_t)root_of(keys, rootc, p, lay.shift[0]);
+    for (int l = 1; l < order; ++l) out.crd[l][p] = (int32_t)((k >> lay.shift[l]) & lay.mask[l]);
 }
 
 // Dense root level: pos[r] = number of nonzeros in rows < r, from the compressed rows (sorted row
@@ -147,10 +174,10 @@ __global__ void __launch_bounds__(256) k_dense_pos(const int32_t *__restrict__ c
 
 }  // namespace
 
-hipError_t reorder_unpack_keys(const uint64_t *keys, int64_t n, const KeyLayout &lay, int order, const CuLevels &out,
-                               hipStream_t st) {
+hipError_t reorder_unpack_keys(const uint64_t *keys, const uint32_t *root, int64_t n, const KeyLayout &lay, int order,
+                               const CuLevels &out, hipStream_t st) {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_unpack_keys, dim3(blocks_for(n, 256)), dim3(256), 0, st, keys, n, lay, order, out);
+    hipLaunchKernelGGL(k_unpack_keys, dim3(blocks_for(n, 256)), dim3(256), 0, st, keys, root, n, lay, order, out);
     return hipGetLastError();
 }
 
@@ -160,9 +187,40 @@ hipError_t reorder_dense_pos(const int32_t *crd0, int64_t nroot, const int32_t *
     return hipGetLastError();
 }
 
-hipError_t reorder_pack_keys(const CoordSource &src, const KeyLayout &lay, uint64_t *keys, hipStream_t st) {
+hipError_t reorder_pack_keys(const CoordSource &src, const KeyLayout &lay, uint64_t *keys, uint32_t *root, hipStream_t st) {
     if (src.nnz <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_pack_keys, dim3(blocks_for(src.nnz, 256)), dim3(256), 0, st, src, lay, keys);
+    hipLaunchKernelGGL(k_pack_keys, dim3(blocks_for(src.nnz, 256)), dim3(256), 0, st, src, lay, keys, root);
+    return hipGetLastError();
+}
+
+hipError_t reorder_iota(uint32_t *out, int64_t n, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_iota, dim3(blocks_for(n, 256)), dim3(256), 0, st, out, n);
+    return hipGetLastError();
+}
+
+hipError_t reorder_sort_lo(void *temp, size_t *temp_bytes, const uint64_t *keys_in, uint64_t *keys_out,
+                           const uint32_t *idx_in, uint32_t *idx_out, int64_t n, int key_bits, hipStream_t st) {
+    return rocprim::radix_sort_pairs(temp, *temp_bytes, keys_in, keys_out, idx_in, idx_out, (size_t)n, 0u,
+                                     (unsigned)key_bits, st);
+}
+
+hipError_t reorder_sort_hi(void *temp, size_t *temp_bytes, const uint32_t *keys_in, uint32_t *keys_out,
+                           const uint32_t *idx_in, uint32_t *idx_out, int64_t n, int key_bits, hipStream_t st) {
+    return rocprim::radix_sort_pairs(temp, *temp_bytes, keys_in, keys_out, idx_in, idx_out, (size_t)n, 0u,
+                                     (unsigned)key_bits, st);
+}
+
+hipError_t reorder_gather_u32(const uint32_t *src, const uint32_t *idx, uint32_t *out, int64_t n, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_gather_u32, dim3(blocks_for(n, 256)), dim3(256), 0, st, src, idx, out, n);
+    return hipGetLastError();
+}
+
+hipError_t reorder_gather_pairs(const uint64_t *keys, const double *vals, const uint32_t *idx, uint64_t *keys_out,
+                                double *vals_out, int64_t n, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_gather_pairs, dim3(blocks_for(n, 256)), dim3(256), 0, st, keys, vals, idx, keys_out, vals_out, n);
     return hipGetLastError();
 }
 
@@ -172,10 +230,10 @@ hipError_t reorder_sort_pairs(void *temp, size_t *temp_bytes, const uint64_t *ke
                                      (unsigned)key_bits, st);
 }
 
-hipError_t reorder_mark_heads(const uint64_t *keys, int64_t n, const KeyLayout &lay, int order, uint64_t *flags,
-                              int32_t *err, hipStream_t st) {
+hipError_t reorder_mark_heads(const uint64_t *keys, const uint32_t *root, int64_t n, const KeyLayout &lay, int order,
+                              uint64_t *flags, int32_t *err, hipStream_t st) {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_mark_heads, dim3(blocks_for(n, 256)), dim3(256), 0, st, keys, n, lay, order, flags, err);
+    hipLaunchKernelGGL(k_mark_heads, dim3(blocks_for(n, 256)), dim3(256), 0, st, keys, root, n, lay, order, flags, err);
     return hipGetLastError();
 }
 
@@ -185,10 +243,10 @@ hipError_t reorder_scan_flags(void *temp, size_t *temp_bytes, const uint64_t *fl
                                    rocprim::plus<uint64_t>(), st);
 }
 
-hipError_t reorder_cut_levels(const uint64_t *keys, const uint64_t *flags, const uint64_t *before, int64_t n,
-                              const KeyLayout &lay, int order, const CuLevels &out, hipStream_t st) {
+hipError_t reorder_cut_levels(const uint64_t *keys, const uint32_t *root, const uint64_t *flags, const uint64_t *before,
+                              int64_t n, const KeyLayout &lay, int order, const CuLevels &out, hipStream_t st) {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_cut_levels, dim3(blocks_for(n, 256)), dim3(256), 0, st, keys, flags, before, n, lay, order,
+    hipLaunchKernelGGL(k_cut_levels, dim3(blocks_for(n, 256)), dim3(256), 0, st, keys, root, flags, before, n, lay, order,
                        out);
     return hipGetLastError();
 }
