@@ -5,6 +5,8 @@ densities, ranks (odd ones too), formats and mode orders from a counter-based ge
 chunk, lane-group and segment boundaries fall in many different relative positions.  Every element is
 compared with the oracle (index arrays bit for bit, values with the tolerance of tests/util.py).
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -15,6 +17,9 @@ from synth import generate as gen
 from util import assert_index_equal, assert_values_close, np_
 
 pytestmark = pytest.mark.gpu
+
+# number of seeded blocks per test; raise it (COMET_SWEEP_BLOCKS=200) for a longer soak of the same code
+BLOCKS = int(os.environ.get("COMET_SWEEP_BLOCKS", "10"))
 
 
 @pytest.fixture(scope="module")
@@ -66,7 +71,7 @@ def random_tensor(rng, seed):
     return dims, (i, j, k, vals)
 
 
-@pytest.mark.parametrize("block", range(10))
+@pytest.mark.parametrize("block", range(BLOCKS))
 def test_random_matrices(comet, block):
     rng = np.random.default_rng(1000 + block)
     for case in range(20):
@@ -94,7 +99,7 @@ def test_random_matrices(comet, block):
             assert_values_close(np_(C), ref, absum, "spmm sweep %d/%d" % (block, case))
 
 
-@pytest.mark.parametrize("block", range(10))
+@pytest.mark.parametrize("block", range(BLOCKS))
 def test_random_tensors(comet, block):
     rng = np.random.default_rng(2000 + block)
     for case in range(15):
