@@ -162,7 +162,8 @@ constexpr int64_t kSmallProblemNnz = int64_t(4) << 20;
 // (device allocations are; sub-views handed in by a caller may not be).
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// Rank-R tiled kernels address operand rows with 32-bit byte offsets: the operand must be < 4 GiB.
+// The rank-R tiled kernel addresses operand rows with 32-bit offsets counted in doubles: the operand must
+// hold fewer than 2^32 values (32 GiB).  The MTTKRP kernel forms 64-bit addresses and passes dense_rows = 0.
 // Small rank-1 problems whose segments are all short go to the group-per-segment kernel when the
 // choice is left open: one launch with no tile tables or fix-up pass, which is what matters while the
 // whole product takes a few microseconds (measured: 2 us against 12 us at 4096 rows x 10 nonzeros,
@@ -173,7 +174,7 @@ bool use_tiled(const comet_tensor *t, int64_t R, const void *dense, int64_t dens
     if (t->variant == 0 && R == 1 && t->sched.max_seg_len > 0 && t->sched.max_seg_len <= kShortSegment &&
         t->sched.nnz <= kSmallProblemNnz)
         return false;
-    if (R > 1 && dense_rows * R * 8 >= (int64_t(1) << 32) - 4096) return false;
+    if (R > 1 && dense_rows * R >= (int64_t(1) << 32) - 4096) return false;
     const int leaf = t->order - 1;
     if (!aligned16(t->crd_i(leaf)) || !aligned16(t->vals_d()) || !aligned16(dense)) return false;
     return true;
@@ -717,7 +718,7 @@ comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *
     hipStream_t st = (hipStream_t)stream;
     const int64_t nslice = X->pos_len[1] - 1;
     const bool tiled = X->nvals > 0 &&
-                       use_tiled(X, R, B, X->dims[1] > X->dims[2] ? X->dims[1] : X->dims[2]) && aligned16(C) &&
+                       use_tiled(X, R, B) && aligned16(C) &&
                        comet::stream_mttkrp_supports_rank(R);
     // Rows of M whose index is not stored at the root level receive no contribution.  The tiled kernel
     // writes every stored slice's row itself (a slice without nonzeros is cleared in its slice pass), so

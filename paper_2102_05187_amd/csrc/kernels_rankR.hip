@@ -14,7 +14,7 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
                                                       void *scratch) {
     constexpr int NW = 256 / L;                // walkers per tile
     constexpr int WI = kTile / NW;             // items per walker
-    using RL = RecLayout<L, 2>;                // record = {row byte offset, tail id} + value
+    using RL = RecLayout<L, 2>;                // record = {row offset in doubles, tail id} + value
     constexpr int SB = RL::SB;
     __shared__ __attribute__((aligned(16))) int32_t ts[kTile];
     __shared__ __attribute__((aligned(16))) int32_t rec_all[NW * RL::kStride];
@@ -34,7 +34,7 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
     st.ht = 0; st.first_id = -1;
     int32_t *rec = rec_all + g * RL::kStride;
     const unsigned R8 = 8u * (unsigned)R;
-    const unsigned slot = lane_slot_bytes<L, WIDE>(j);
+    const unsigned slot = lane_slot_doubles<L, WIDE>(j), Ru = (unsigned)R;
     char *outb = reinterpret_cast<char *>(out);
 
     constexpr int G = StepGroup<V>::value, NG = SB / G;
@@ -45,9 +45,9 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
         {
             const int4 t4 = *reinterpret_cast<const int4 *>(ts + (i0 - tb));
             *reinterpret_cast<int4 *>(rec + 8 * j) =
-                make_int4((int)((unsigned)cur.cr[0] * R8), t4.x, (int)((unsigned)cur.cr[1] * R8), t4.y);
+                make_int4((int)((unsigned)cur.cr[0] * Ru), t4.x, (int)((unsigned)cur.cr[1] * Ru), t4.y);
             *reinterpret_cast<int4 *>(rec + 8 * j + 4) =
-                make_int4((int)((unsigned)cur.cr[2] * R8), t4.z, (int)((unsigned)cur.cr[3] * R8), t4.w);
+                make_int4((int)((unsigned)cur.cr[2] * Ru), t4.z, (int)((unsigned)cur.cr[3] * Ru), t4.w);
             *reinterpret_cast<double2 *>(rec + RL::kVal + 8 * j) = make_double2(cur.va[0], cur.va[1]);
             *reinterpret_cast<double2 *>(rec + RL::kVal + 8 * j + 4) = make_double2(cur.va[2], cur.va[3]);
         }

@@ -90,14 +90,14 @@ __device__ __forceinline__ void build_tail_map_from_pos(int32_t *ts, const int32
 // ---- rank-R walk: a group of L lanes (4 or 8) walks a run of consecutive items --------------------
 // The 256 threads of a tile form 256/L lane groups ("walkers"); walker g owns the 16*L consecutive
 // items [tb + 16*L*g, +16*L).  Every 4*L items (a super-block) each lane loads four consecutive
-// (crd, val) pairs with 16-byte loads, looks up their tail ids, turns crd into the byte offset of
+// (crd, val) pairs with 16-byte loads, looks up their tail ids, turns crd into the offset of
 // the operand row, and writes one small record per item into the walker's private LDS area.  The
 // group then takes the items one at a time: every lane reads the current item's record with a
 // broadcast LDS read (no cross-lane VALU work), adds its own 16-byte slot, and gathers its share of
 // the operand row Dn[crd, :] -- contiguous 16-byte pieces (WIDE, R a multiple of 2L: lane j takes
 // ranks 2L*q+2j, 2L*q+2j+1) or 8-byte pieces (lane j takes ranks L*q+j) -- so a load instruction
 // reads each gathered row as one contiguous run of 16*L bytes.  Gathers run G steps ahead of the
-// FMAs (double-buffered in registers).  Row offsets are 32-bit, so an operand must be < 4 GiB.
+// FMAs (double-buffered in registers).  Row offsets are 32-bit counts of doubles, so an operand must hold fewer than 2^32 values.
 template <int L, int NI>
 struct RecLayout {                                     // per-walker record area, in 4-byte words
     static constexpr int SB = 4 * L;                   // items per super-block
@@ -190,26 +190,25 @@ struct WalkState {
     int ht, first_id;
 };
 
-// This lane's share of the dense row that starts `off` bytes into Dn (off already includes the
-// lane's own slot).
+// This lane's share of the dense row that starts `off` doubles into Dn (off already includes the
+// lane's own slot).  Offsets are 32-bit counts of doubles, so an operand may hold up to 2^32 values
+// (32 GiB); the sum with the q-th piece is formed in 64 bits.
 template <int L, int V, bool WIDE>
 __device__ __forceinline__ void grp_load_row_off(const double *__restrict__ Dn, unsigned off, int R, int j, double *d) {
-    const char *base = reinterpret_cast<const char *>(Dn);
+    const double *base = Dn + (size_t)off;
     if constexpr (WIDE) {
 #pragma unroll
         for (int q = 0; q < V / 2; ++q) {
-            const double2 x = *reinterpret_cast<const double2 *>(base + (size_t)(off + (unsigned)(16 * L * q)));
+            const double2 x = *reinterpret_cast<const double2 *>(base + 2 * L * q);
             d[2 * q] = x.x; d[2 * q + 1] = x.y;
         }
     } else {
 #pragma unroll
-        for (int q = 0; q < V; ++q) {
-            d[q] = L * q + j < R ? *reinterpret_cast<const double *>(base + (size_t)(off + (unsigned)(8 * L * q))) : 0.0;
-        }
+        for (int q = 0; q < V; ++q) d[q] = L * q + j < R ? base[L * q] : 0.0;
     }
 }
 template <int L, bool WIDE>
-__device__ __forceinline__ unsigned lane_slot_bytes(int j) { return WIDE ? 16u * j : 8u * j; }
+__device__ __forceinline__ unsigned lane_slot_doubles(int j) { return WIDE ? 2u * j : (unsigned)j; }
 
 // Close the first segment end of every walker of the tile and publish the tile summary.
 // wopen[(g*L + j)*V + q] holds walker g's open sum, wht[g] its has_tail flag (both already written

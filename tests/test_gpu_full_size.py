@@ -262,3 +262,20 @@ def test_second_mode_mttkrp_config(comet):
     stored = torch.zeros(dims[1], dtype=torch.bool, device=DEV)
     stored[Xr.crd(0).to(torch.int64)] = True
     assert bool((M[~stored] == 0.0).all()) and not bool(torch.isnan(M).any())
+
+
+def test_spmm_with_an_operand_beyond_4_gib(comet):
+    """The dense operand is 4.6 GB: row offsets inside it do not fit 32-bit byte offsets (the kernels count
+    them in doubles).  Every output row against the oracle."""
+    nrows, ncols, R = 100_000, 9_000_000, 64
+    lens = torch.full((nrows,), 8, dtype=torch.int64, device=DEV)
+    lens[::1000] = 3000
+    rows, cols, vals = gen.matrix_from_row_lengths(nrows, ncols, lens, 5, DEV)
+    say("spmm with a %.1f GB operand, nnz=%d" % (ncols * R * 8 / 1e9, vals.numel()))
+    assert int(cols.max()) * R * 8 > (1 << 32)
+    A = comet.from_levels(fmt.pack_csr(nrows, ncols, rows, cols, vals))
+    B = gen.dense_operand(5, 0, (ncols, R), DEV)
+    C = comet.comet_spmm(A, B)
+    torch.cuda.synchronize()
+    ref, absum = oracle.spmm(np_(rows), np_(cols), np_(vals), (nrows, ncols), np_(B))
+    assert_values_close(np_(C), ref, absum, "spmm, operand beyond 4 GiB")
