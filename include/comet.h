@@ -192,7 +192,8 @@ comet_status comet_ttv(const comet_tensor *X, int mode, const double *v, comet_t
  *   X     order-3 handle, [CU,CU,CU].      mode  as for comet_ttv (the mode of the last level).
  *   U     device, [size of the contracted mode x R] row-major, 1 <= R <= 1024.
  *   Y     as for comet_ttv; the result is [CU,CU,D] with dims (I, J, R): levels 0/1 shared
- *         with X, a dense last level of size R, vals of [#fibers x R] row-major. */
+ *         with X, a dense last level of size R, vals of [#fibers x R] row-major (#fibers x R
+ *         may exceed 2^31: no int32 array indexes the positions of a dense last level). */
 comet_status comet_ttm(const comet_tensor *X, int mode, const double *U, int64_t R,
                        comet_tensor **Y, void *stream);
 

@@ -134,10 +134,11 @@ class Tensor:
         _check(_lib().comet_tensor_info(self.handle, ctypes.byref(inf)), "comet_tensor_info")
         return inf
 
-    def _wrap(self, ptr, n, typestr, dtype):
+    def _wrap(self, ptr, n, typestr, dtype, copy=True):
         if not ptr or n == 0:
             return torch.empty(0, dtype=dtype, device="cuda")
-        return torch.as_tensor(_DeviceView(ptr, n, typestr, self), device="cuda").clone()
+        view = torch.as_tensor(_DeviceView(ptr, n, typestr, self), device="cuda")
+        return view.clone() if copy else view
 
     def levels(self) -> List[int]:
         inf = self.info()
@@ -169,9 +170,10 @@ class Tensor:
             return None
         return self._wrap(inf.crd[l], inf.crd_len[l], "<i4", torch.int32)
 
-    def vals(self) -> torch.Tensor:
+    def vals(self, copy: bool = True) -> torch.Tensor:
+        """The value array; copy=False returns a view of the library's memory (valid while the handle lives)."""
         inf = self.info()
-        return self._wrap(inf.vals, inf.nvals, "<f8", torch.float64)
+        return self._wrap(inf.vals, inf.nvals, "<f8", torch.float64, copy)
 
     def set_variant(self, variant: int) -> "Tensor":
         _check(_lib().comet_tensor_set_variant(self.handle, variant), "comet_tensor_set_variant")

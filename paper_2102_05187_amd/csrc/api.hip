@@ -659,7 +659,8 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
             HIP_TRY(hipStreamSynchronize(st));
             y->pos_len[2] = 1;
         }
-        if (nout * R >= (int64_t(1) << 31)) return COMET_ERR_UNSUPPORTED;
+        // positions of a dense last level are never stored in an int32 array, so only the values of a
+        // level that some pos array indexes are limited to 2^31; the TTM result may be larger
         y->nvals = nout * R;
         y->vals = comet::dev_alloc(sizeof(double) * y->nvals);
         if (!y->vals) return COMET_ERR_ALLOC;

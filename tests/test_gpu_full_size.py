@@ -279,3 +279,27 @@ def test_spmm_with_an_operand_beyond_4_gib(comet):
     torch.cuda.synchronize()
     ref, absum = oracle.spmm(np_(rows), np_(cols), np_(vals), (nrows, ncols), np_(B))
     assert_values_close(np_(C), ref, absum, "spmm, operand beyond 4 GiB")
+
+
+def test_ttm_result_with_more_than_2_31_values(comet):
+    """38.9 M fibers x R = 64 gives 2.49 * 10^9 result values (19.9 GB): more than an int32 position can
+    count, which is fine for a dense last level.  Sampled fibers against the oracle."""
+    R = 64
+    c = gen.config_mttkrp(seed=0, device=DEV, R=R)
+    i, j, k, vals = c["coo"]
+    dims = c["dims"]
+    L = fmt.pack_csf3(dims, i, j, k, vals)
+    X = comet.from_levels(L)
+    U = c["C"]
+    Y = comet.comet_ttm(X, 2, U)
+    torch.cuda.synchronize()
+    nfib = int(L.crd[1].numel())
+    say("ttm with %d fibers x %d = %d result values" % (nfib, R, nfib * R))
+    assert nfib * R > (1 << 31) and Y.dims() == [dims[0], dims[1], R]
+    fids, idx, which = _fiber_sample(L, 2000, 9)
+    fids = torch.unique(torch.cat([fids, torch.tensor([nfib - 1, nfib - 2], device=DEV)]))   # rows past 2^31 values
+    pos3 = L.pos[2].to(torch.int64)
+    idx, which = ranges_to_index(pos3[fids], pos3[fids + 1])
+    ref = oracle.ttm(np_(i[idx]), np_(j[idx]), np_(k[idx]), np_(vals[idx]), dims, np_(U))
+    got = Y.vals(copy=False).reshape(-1, R)[fids]
+    assert_values_close(np_(got), ref["vals"], ref["abs"], "ttm sampled fibers of a result beyond 2^31 values")
