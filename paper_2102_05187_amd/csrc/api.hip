@@ -88,6 +88,13 @@ comet_status build_schedule(comet_tensor &t, hipStream_t st) {
         rs = read_i32((const int32_t *)mx->ptr, 1, &h, st);
         if (rs != COMET_OK) return rs;
         sc.empty_segments = h;
+        if (t.levels[0] == COMET_CU) {
+            HIP_TRY(hipMemsetAsync(mx->ptr, 0, sizeof(int32_t), st));
+            HIP_TRY(comet::max_coordinate_gap(t.crd_i(0), t.crd_len[0], t.dims[0], (int32_t *)mx->ptr, st));
+            rs = read_i32((const int32_t *)mx->ptr, 1, &h, st);
+            if (rs != COMET_OK) return rs;
+            sc.max_root_gap = h;
+        }
         if (t.fmt == Format::CSF3) {
             HIP_TRY(hipMemsetAsync(mx->ptr, 0, sizeof(int32_t), st));
             HIP_TRY(comet::max_parent_span(t.pos_i(1), t.pos_len[1] - 1, t.pos_i(2), (int32_t *)mx->ptr, st));
@@ -157,6 +164,14 @@ comet_status ensure_scratch(const comet_tensor *t, size_t bytes) {
 
 constexpr int64_t kShortSegment = 256;
 constexpr int64_t kSmallProblemNnz = int64_t(4) << 20;
+
+// Clearing only the rows between the stored root coordinates beats clearing the whole dense result when
+// most rows are stored -- but one thread clears one gap, so a long gap (say, an empty lower half) must
+// not be left to it.
+bool gaps_are_short(const comet_tensor *t, int64_t R) {
+    const int64_t nstored = t->crd_len[0];
+    return nstored * 2 >= t->dims[0] && t->sched.max_root_gap >= 0 && t->sched.max_root_gap * R <= 4096;
+}
 
 // The tiled kernels read crd / vals with 16-byte vector loads, so the arrays must be 16-byte aligned
 // (device allocations are; sub-views handed in by a caller may not be).
@@ -585,7 +600,7 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
         // the gaps between them are cleared; otherwise, or when there is nothing to run, the whole result.
         rowmap = A->crd_i(0);
         const int64_t nstored = A->crd_len[0];
-        if (nnz > 0 && nstored * 2 >= A->dims[0]) HIP_TRY(comet::zero_unstored_rows(rowmap, nstored, A->dims[0], R, out, st));
+        if (nnz > 0 && gaps_are_short(A, R)) HIP_TRY(comet::zero_unstored_rows(rowmap, nstored, A->dims[0], R, out, st));
         else HIP_TRY(comet::fill_zero_f64(out, A->dims[0] * R, st));
     }
     if (nnz == 0) {
@@ -724,7 +739,7 @@ comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *
     // Rows of M whose index is not stored at the root level receive no contribution.  The tiled kernel
     // writes every stored slice's row itself (a slice without nonzeros is cleared in its slice pass), so
     // when most rows are stored only the gaps between them are cleared; otherwise all of M is.
-    if (tiled && nslice * 2 >= X->dims[0]) HIP_TRY(comet::zero_unstored_rows(X->crd_i(0), nslice, X->dims[0], R, M, st));
+    if (tiled && gaps_are_short(X, R)) HIP_TRY(comet::zero_unstored_rows(X->crd_i(0), nslice, X->dims[0], R, M, st));
     else HIP_TRY(comet::fill_zero_f64(M, X->dims[0] * R, st));
     if (X->nvals == 0) return COMET_OK;
     if (tiled) {

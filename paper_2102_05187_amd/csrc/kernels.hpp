@@ -29,6 +29,8 @@ hipError_t build_run_base(const int32_t *c0, const int32_t *c1, int64_t nnz, int
                           int32_t *run_base /* [ntiles+1] */, hipStream_t st);
 hipError_t max_segment_length(const int32_t *pos, int64_t nseg, int32_t *out_max, hipStream_t st);
 hipError_t count_empty_segments(const int32_t *pos, int64_t nseg, int32_t *out_count, hipStream_t st);
+// Longest run of coordinates of [0, dim) that do not occur in the sorted list idx[0..n) (*out_max zeroed by the caller).
+hipError_t max_coordinate_gap(const int32_t *idx, int64_t n, int64_t dim, int32_t *out_max, hipStream_t st);
 hipError_t max_parent_span(const int32_t *parent_pos, int64_t nparent, const int32_t *leaf_pos, int32_t *out_max,
                            hipStream_t st);
 

@@ -63,6 +63,7 @@ struct Schedule {
     int64_t empty_segments = -1;  // leaf segments without a nonzero (-1 = unknown)
     int64_t max_seg_len = 0;      // longest leaf segment, in nonzeros (0 = unknown)
     int64_t max_parent_len = 0;   // CSF3: most nonzeros under one slice (0 = unknown)
+    int64_t max_root_gap = -1;    // compressed root level: longest run of absent root coordinates (-1 = unknown)
 };
 
 }  // namespace comet

@@ -220,6 +220,27 @@ hipError_t max_segment_length(const int32_t *pos, int64_t nseg, int32_t *out_max
     return hipGetLastError();
 }
 
+// longest run of coordinates absent from the sorted list idx[0..n) inside [0, dim)
+__global__ void __launch_bounds__(256) k_max_gap(const int32_t *__restrict__ idx, int64_t n, int64_t dim,
+                                                 int32_t *__restrict__ out) {
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int32_t m = 0;
+    for (int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; s <= n; s += stride) {
+        const int64_t lo = s == 0 ? 0 : (int64_t)idx[s - 1] + 1;
+        const int64_t hi = s == n ? dim : (int64_t)idx[s];
+        const int32_t l = (int32_t)(hi > lo ? hi - lo : 0);
+        m = l > m ? l : m;
+    }
+    if (m > 0) atomicMax(out, m);
+}
+
+hipError_t max_coordinate_gap(const int32_t *idx, int64_t n, int64_t dim, int32_t *out_max, hipStream_t st) {
+    int64_t want = (n + 1 + 255) / 256;
+    unsigned grid = (unsigned)(want > 2048 ? 2048 : want);
+    hipLaunchKernelGGL(k_max_gap, dim3(grid), dim3(256), 0, st, idx, n, dim, out_max);
+    return hipGetLastError();
+}
+
 // most leaf positions under one parent segment: max over s of pos_leaf[pos_par[s+1]] - pos_leaf[pos_par[s]]
 __global__ void __launch_bounds__(256) k_max_parent_span(const int32_t *__restrict__ ppos, int64_t nparent,
                                                          const int32_t *__restrict__ lpos, int32_t *__restrict__ out) {
