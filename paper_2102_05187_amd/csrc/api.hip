@@ -189,6 +189,9 @@ bool use_tiled(const comet_tensor *t, int64_t R, const void *dense, int64_t dens
     if (t->variant == 0 && R == 1 && t->sched.max_seg_len > 0 && t->sched.max_seg_len <= kShortSegment &&
         t->sched.nnz <= kSmallProblemNnz)
         return false;
+    // Far more (empty) segments than nonzeros -- a hypersparse matrix kept in CSR: a tile would spend its
+    // time clearing the rows of the empty segments it covers; one thread or lane group per row does that evenly.
+    if (t->variant == 0 && t->sched.empty_segments > 16 * t->sched.nnz + 4096) return false;
     if (R > 1 && dense_rows * R >= (int64_t(1) << 32) - 4096) return false;
     const int leaf = t->order - 1;
     if (!aligned16(t->crd_i(leaf)) || !aligned16(t->vals_d()) || !aligned16(dense)) return false;
