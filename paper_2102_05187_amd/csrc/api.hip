@@ -183,11 +183,16 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // choice is left open: one launch with no tile tables or fix-up pass, which is what matters while the
 // whole product takes a few microseconds (measured: 2 us against 12 us at 4096 rows x 10 nonzeros,
 // level with the tiled kernel from about 4M nonzeros on, far behind it once one segment is long).
-bool use_tiled(const comet_tensor *t, int64_t R, const void *dense, int64_t dense_rows = 0) {
+// `serial` = the most nonzeros one thread of the simple kernel would walk alone (longest leaf segment, or
+// for MTTKRP the most nonzeros under one slice); 0 = unknown.
+bool use_tiled(const comet_tensor *t, int64_t R, const void *dense, int64_t dense_rows, int64_t serial) {
     if (t->variant == 1) return false;
     if (!comet::stream_supports_rank(R)) return false;
-    if (t->variant == 0 && R == 1 && t->sched.max_seg_len > 0 && t->sched.max_seg_len <= kShortSegment &&
-        t->sched.nnz <= kSmallProblemNnz)
+    if (t->variant == 0 && R == 1 && serial > 0 && serial <= kShortSegment && t->sched.nnz <= kSmallProblemNnz)
+        return false;
+    // The same for rank R: a thread per (segment, column) walks its short segment alone (4 against 17 us at
+    // 4096 rows x 10 nonzeros, R = 32; level with the tiled kernel at about 10M multiply-adds).
+    if (t->variant == 0 && R > 1 && serial > 0 && serial <= 64 && t->sched.nnz * R <= (int64_t(8) << 20))
         return false;
     // Far more (empty) segments than nonzeros -- a hypersparse matrix kept in CSR: a tile would spend its
     // time clearing the rows of the empty segments it covers; one thread or lane group per row does that evenly.
@@ -610,7 +615,7 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
         if (A->fmt == Format::CSR) HIP_TRY(comet::fill_zero_f64(out, A->dims[0] * R, st));
         return COMET_OK;
     }
-    if (use_tiled(A, R, Dn, A->dims[1])) {
+    if (use_tiled(A, R, Dn, A->dims[1], A->sched.max_seg_len)) {
         size_t need = comet::stream_scratch_bytes(R == 1 ? A->sched.nchunks : A->sched.ntiles, R);
         comet_status rs = ensure_scratch(A, need);
         if (rs != COMET_OK) return rs;
@@ -687,7 +692,7 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
     double *yv = (double *)y->vals->ptr;
     if (X->nvals > 0) {
         if (csf) {
-            if (use_tiled(X, R, Dn, X->dims[2])) {
+            if (use_tiled(X, R, Dn, X->dims[2], X->sched.max_seg_len)) {
                 rs = ensure_scratch(X, comet::stream_scratch_bytes(R == 1 ? X->sched.nchunks : X->sched.ntiles, R));
                 if (rs != COMET_OK) return rs;
                 HIP_TRY(comet::stream_segreduce(X->sched, X->pos_i(2), X->crd_i(2), X->vals_d(), nullptr, Dn, X->dims[2], R,
@@ -697,7 +702,7 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
                                                 nullptr, Dn, R, yv, st));
             }
         } else {
-            if (use_tiled(X, 1, Dn) && comet::stream_supports_coo()) {
+            if (use_tiled(X, 1, Dn, 0, 0) && comet::stream_supports_coo()) {
                 rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.nchunks, 1));
                 if (rs != COMET_OK) return rs;
                 HIP_TRY(comet::stream_ttv_coo(X->sched, X->crd_i(0), X->crd_i(1), X->crd_i(2), X->vals_d(), Dn, X->dims[2],
@@ -737,7 +742,7 @@ comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *
     hipStream_t st = (hipStream_t)stream;
     const int64_t nslice = X->pos_len[1] - 1;
     const bool tiled = X->nvals > 0 &&
-                       use_tiled(X, R, B) && aligned16(C) &&
+                       use_tiled(X, R, B, 0, X->sched.max_parent_len) && aligned16(C) &&
                        comet::stream_mttkrp_supports_rank(R);
     // Rows of M whose index is not stored at the root level receive no contribution.  The tiled kernel
     // writes every stored slice's row itself (a slice without nonzeros is cleared in its slice pass), so
