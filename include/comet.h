@@ -103,7 +103,7 @@ typedef struct {
  * The call also builds the per-tensor schedule (nonzero-balanced tile tables used by the
  * kernels; load imbalance is what Section 8.3 identifies as the main source of slowdown), which
  * is why it synchronises.  Accepted tuples: [D,CU] (CSR), [CU,CU] (DCSR), [CN,S] and [CN,S,S]
- * (COO), [CU,CU,CU] (CSF); results of TTV/TTM may additionally be [CU,CU,D].
+ * (COO), [CU,CU,CU] (CSF); results of TTV/TTM may additionally be [CU,CU,D] or [CN,S,D].
  */
 comet_status comet_tensor_create(comet_tensor **out, int order,
                                  const int64_t *dims, const comet_level_t *levels,
@@ -189,7 +189,10 @@ comet_status comet_ttv(const comet_tensor *X, int mode, const double *v, comet_t
 
 /* SpTTM, Y = X x_mode U :  y_ijr = sum_k x_ijk u_kr   (Section 8.2, SpTTM; R takes the place
  * of the contracted mode).
- *   X     order-3 handle, [CU,CU,CU].      mode  as for comet_ttv (the mode of the last level).
+ *   X     order-3 handle, [CU,CU,CU] or sorted [CN,S,S].   mode  as for comet_ttv (the mode of the
+ *         last level).  For a coordinate list the first call builds a compressed copy of X inside the
+ *         handle (one device sort, about 16 more bytes per nonzero, kept until X is destroyed) and
+ *         synchronises; the result is then [CN,S,D]: the distinct (i,j) as for comet_ttv, R values each.
  *   U     device, [size of the contracted mode x R] row-major, 1 <= R <= 1024.
  *   Y     as for comet_ttv; the result is [CU,CU,D] with dims (I, J, R): levels 0/1 shared
  *         with X, a dense last level of size R, vals of [#fibers x R] row-major (#fibers x R
@@ -200,7 +203,8 @@ comet_status comet_ttm(const comet_tensor *X, int mode, const double *U, int64_t
 /* MTTKRP, M = X_(mode) (C (.) B) :  m_ir = sum_jk x_ijk b_jr c_kr.  The paper names the operation
  * (Section 8.3) without defining it; this is the usual definition with the output indexed by
  * the mode stored in the root level.
- *   X        order-3 handle, [CU,CU,CU].
+ *   X        order-3 handle, [CU,CU,CU] or sorted [CN,S,S] (which works through a compressed copy
+ *            built on the first call, as described at comet_ttm).
  *   mode     output mode (numbered as in the original tensor); must be the mode stored in the root
  *            level -- 0 unless the handle comes from comet_tensor_reorder, e.g. {1,0,2} for mode 1
  *            -- else COMET_ERR_UNSUPPORTED.

@@ -28,6 +28,7 @@ Format classify(int order, const int32_t *lv) {
         if (lv[0] == COMET_CN && lv[1] == COMET_S && lv[2] == COMET_S) return Format::COO3;
         if (lv[0] == COMET_CU && lv[1] == COMET_CU && lv[2] == COMET_CU) return Format::CSF3;
         if (lv[0] == COMET_CU && lv[1] == COMET_CU && lv[2] == COMET_D) return Format::CSF3_DENSE_LEAF;
+        if (lv[0] == COMET_CN && lv[1] == COMET_S && lv[2] == COMET_D) return Format::COO3_DENSE_LEAF;
     }
     return Format::OTHER;
 }
@@ -635,6 +636,18 @@ comet_status comet_spmm(const comet_tensor *A, const double *B, int64_t R, doubl
     return matrix_product(A, B, R, C, (hipStream_t)stream);
 }
 
+// The compressed copy of a sorted coordinate list (same level order), built on first use.
+static comet_status ensure_shadow(const comet_tensor *X, hipStream_t st) {
+    comet_tensor *m = const_cast<comet_tensor *>(X);
+    if (m->shadow) return COMET_OK;
+    comet_tensor *s = nullptr;
+    comet_status rs = restore(X, X->mode_of_level, Target::ALL_CU, &s, st);
+    if (rs != COMET_OK) return rs;
+    s->variant = X->variant;
+    m->shadow.reset(s);
+    return COMET_OK;
+}
+
 // ---- TTV / TTM along the mode stored in the last level ------------------------------------------
 static comet_status leaf_contract(const comet_tensor *X, int mode, const double *Dn, int64_t R, int kind,
                                   comet_tensor **Y, hipStream_t st) {
@@ -642,7 +655,7 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
     if (X->order != 3) return COMET_ERR_UNSUPPORTED;
     if (R < 1 || R > 1024) return COMET_ERR_UNSUPPORTED;
     const bool csf = X->fmt == Format::CSF3, coo = X->fmt == Format::COO3;
-    if (!csf && !(coo && kind == 1)) return COMET_ERR_UNSUPPORTED;
+    if (!csf && !coo) return COMET_ERR_UNSUPPORTED;
     if (mode < 0 || mode >= 3) return COMET_ERR_INVALID_ARG;
     if (mode != X->mode_of_level[2]) return COMET_ERR_UNSUPPORTED;   // re-store with comet_tensor_reorder first
     bool fresh = false;
@@ -651,7 +664,15 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
     comet_tensor *y = *Y;
     std::unique_ptr<comet_tensor> guard(fresh ? y : nullptr);
     if (fresh) *Y = nullptr;
-    const int64_t nout = csf ? X->crd_len[1] : X->sched.nruns;    // stored (i,j) pairs
+    // TTM on a coordinate list runs on its compressed copy; the result lists the distinct (i,j) like TTV's
+    const comet_tensor *S = nullptr;
+    if (coo && kind == 2) {
+        rs = ensure_shadow(X, st);
+        if (rs != COMET_OK) return rs;
+        S = X->shadow.get();
+        const_cast<comet_tensor *>(S)->variant = X->variant;      // the kernel family chosen for X applies to its copy
+    }
+    const int64_t nout = csf ? X->crd_len[1] : (S ? S->crd_len[1] : X->sched.nruns);    // stored (i,j) pairs
     if (fresh) {
         y->order = kind == 1 ? 2 : 3;
         y->dims[0] = X->dims[0]; y->dims[1] = X->dims[1];
@@ -666,8 +687,9 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
             y->levels[0] = COMET_CN; y->levels[1] = COMET_S;
             y->pos[0] = comet::dev_alloc(2 * sizeof(int32_t));
             y->crd[0] = comet::dev_alloc(sizeof(int32_t) * nout);
-            y->crd[1] = comet::dev_alloc(sizeof(int32_t) * nout);
+            y->crd[1] = S ? S->crd[1] : comet::dev_alloc(sizeof(int32_t) * nout);   // the copy's fiber coordinates as they are
             if (!y->pos[0] || !y->crd[0] || !y->crd[1]) return COMET_ERR_ALLOC;
+            if (S) HIP_TRY(comet::expand_parent_coords(S->pos_i(1), S->crd_len[0], S->crd_i(0), nout, (int32_t *)y->crd[0]->ptr, st));
             int32_t h[2] = {0, (int32_t)nout};
             HIP_TRY(hipMemcpyAsync(y->pos[0]->ptr, h, sizeof h, hipMemcpyHostToDevice, st));
             HIP_TRY(hipStreamSynchronize(st));
@@ -691,14 +713,15 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
     }
     double *yv = (double *)y->vals->ptr;
     if (X->nvals > 0) {
-        if (csf) {
-            if (use_tiled(X, R, Dn, X->dims[2], X->sched.max_seg_len)) {
-                rs = ensure_scratch(X, comet::stream_scratch_bytes(R == 1 ? X->sched.nchunks : X->sched.ntiles, R));
+        if (csf || S) {
+            const comet_tensor *C = csf ? X : S;                 // the compressed storage the kernels walk
+            if (use_tiled(C, R, Dn, C->dims[2], C->sched.max_seg_len)) {
+                rs = ensure_scratch(C, comet::stream_scratch_bytes(R == 1 ? C->sched.nchunks : C->sched.ntiles, R));
                 if (rs != COMET_OK) return rs;
-                HIP_TRY(comet::stream_segreduce(X->sched, X->pos_i(2), X->crd_i(2), X->vals_d(), nullptr, Dn, X->dims[2], R,
-                                                yv, X->scratch->ptr, st));
+                HIP_TRY(comet::stream_segreduce(C->sched, C->pos_i(2), C->crd_i(2), C->vals_d(), nullptr, Dn, C->dims[2], R,
+                                                yv, C->scratch->ptr, st));
             } else {
-                HIP_TRY(comet::simple_segreduce(X->pos_i(2), X->crd_i(2), X->vals_d(), X->pos_len[2] - 1, X->nvals,
+                HIP_TRY(comet::simple_segreduce(C->pos_i(2), C->crd_i(2), C->vals_d(), C->pos_len[2] - 1, C->nvals,
                                                 nullptr, Dn, R, yv, st));
             }
         } else {
@@ -732,6 +755,13 @@ comet_status comet_ttm(const comet_tensor *X, int mode, const double *U, int64_t
 comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *factors, int64_t R, double *M,
                           void *stream) {
     if (!X || !factors || !M) return COMET_ERR_INVALID_ARG;
+    if (X->fmt == Format::COO3) {
+        // a sorted coordinate list: the slice / fiber structure comes from its compressed copy
+        comet_status rs = ensure_shadow(X, (hipStream_t)stream);
+        if (rs != COMET_OK) return rs;
+        X->shadow->variant = X->variant;
+        X = X->shadow.get();
+    }
     if (X->fmt != Format::CSF3) return COMET_ERR_UNSUPPORTED;
     if (mode < 0 || mode >= 3) return COMET_ERR_INVALID_ARG;
     if (mode != X->mode_of_level[0]) return COMET_ERR_UNSUPPORTED;   // re-store with comet_tensor_reorder first

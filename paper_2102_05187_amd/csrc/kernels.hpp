@@ -99,6 +99,9 @@ hipError_t reorder_mark_heads(const uint64_t *keys, const uint32_t *root, int64_
 // out of its compressed rows (out has dim0 + 1 entries).
 hipError_t reorder_unpack_keys(const uint64_t *keys, const uint32_t *root, int64_t n, const KeyLayout &lay, int order,
                                const CuLevels &out, hipStream_t st);
+// out[f] = crd0[s] for the parent s of position f (pos1[s] <= f < pos1[s+1]), f in [0, nchild).
+hipError_t expand_parent_coords(const int32_t *pos1, int64_t nparent, const int32_t *crd0, int64_t nchild, int32_t *out,
+                                hipStream_t st);
 hipError_t reorder_dense_pos(const int32_t *crd0, int64_t nroot, const int32_t *pos1, int64_t dim0, int64_t n,
                              int32_t *out, hipStream_t st);
 hipError_t reorder_cut_levels(const uint64_t *keys, const uint32_t *root, const uint64_t *flags, const uint64_t *before,

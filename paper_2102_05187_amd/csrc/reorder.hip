@@ -172,7 +172,21 @@ __global__ void __launch_bounds__(256) k_dense_pos(const int32_t *__restrict__ c
     out[r] = lo < nroot ? pos1[lo] : (int32_t)n;
 }
 
+__global__ void __launch_bounds__(256) k_expand_parent(const int32_t *__restrict__ pos1, int32_t nparent,
+                                                       const int32_t *__restrict__ crd0, int64_t nchild,
+                                                       int32_t *__restrict__ out) {
+    int64_t f = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (f < nchild) out[f] = crd0[owner_of(pos1, nparent, (int32_t)f)];
+}
+
 }  // namespace
+
+hipError_t expand_parent_coords(const int32_t *pos1, int64_t nparent, const int32_t *crd0, int64_t nchild, int32_t *out,
+                                hipStream_t st) {
+    if (nchild <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_expand_parent, dim3(blocks_for(nchild, 256)), dim3(256), 0, st, pos1, (int32_t)nparent, crd0, nchild, out);
+    return hipGetLastError();
+}
 
 hipError_t reorder_unpack_keys(const uint64_t *keys, const uint32_t *root, int64_t n, const KeyLayout &lay, int order,
                                const CuLevels &out, hipStream_t st) {

@@ -38,7 +38,7 @@ inline DevRef dev_alloc(size_t bytes) {
     return std::make_shared<DevArray>(p, bytes, true);
 }
 
-enum class Format { CSR, DCSR, COO2, COO3, CSF3, CSF3_DENSE_LEAF, OTHER };
+enum class Format { CSR, DCSR, COO2, COO3, CSF3, CSF3_DENSE_LEAF, COO3_DENSE_LEAF, OTHER };
 
 // Items per tile of the nonzero-tiled kernels (a multiple of every per-wave chunk they use).
 constexpr int kTile = 4096;
@@ -84,6 +84,10 @@ struct comet_tensor {
     // scratch owned by the handle (carry buffers of the tiled kernels), grown on demand
     comet::DevRef scratch;
     size_t scratch_bytes = 0;
+
+    // a sorted coordinate list keeps a compressed ([CU,CU,CU]) copy of itself for the operations whose
+    // kernels need the fiber / slice structure (TTM, MTTKRP); built on their first use
+    std::unique_ptr<comet_tensor> shadow;
 
     // results of TTV / TTM remember what produced them so the handle can be reused
     const comet_tensor *result_of = nullptr;

@@ -229,6 +229,37 @@ def test_mttkrp(comet, name, R, variant):
     assert_values_close(np_(M), ref, absum, "mttkrp %s R=%d" % (name, R))
 
 
+@pytest.mark.parametrize("variant", VARIANTS)
+@pytest.mark.parametrize("R", [1, 16, 24])
+@pytest.mark.parametrize("name", ["zipf_ttm", "zipf_mttkrp", "mode_of_two", "single_slice", "long_fiber", "empty", "single"])
+def test_ttm_and_mttkrp_on_a_sorted_coordinate_list(comet, name, R, variant):
+    """[CN,S,S] input: TTM returns the distinct (i,j) as a coordinate list with a dense last level
+    ([CN,S,D]); MTTKRP fills the dense matrix.  Both against the oracle, index arrays bit for bit."""
+    dims, (i, j, k, vals) = TENSOR_CASES[name]
+    say("coo ttm/mttkrp case=%s R=%d variant=%d nnz=%d" % (name, R, variant, vals.numel()))
+    X = comet.from_levels(fmt.pack_coo(dims, (i, j, k), vals).to("cuda")).set_variant(variant)
+    U = gen.dense_operand(51, 0, (dims[2], R))
+    Y = comet.comet_ttm(X, 2, dev(U))
+    torch.cuda.synchronize()
+    ref = oracle.ttm(np_(i), np_(j), np_(k), np_(vals), dims, np_(U))
+    assert Y.levels() == [2, 3, 0] and Y.dims() == [dims[0], dims[1], R]
+    assert_index_equal(np_(Y.pos(0)), np.array([0, len(ref["i"])]), "pos")
+    assert_index_equal(np_(Y.crd(0)), ref["i"], "crd1")
+    assert_index_equal(np_(Y.crd(1)), ref["j"], "crd2")
+    assert_index_equal(np_(Y.pos(2)), np.array([R]), "dense level size")
+    assert_values_close(np_(Y.vals()).reshape(-1, R), ref["vals"], ref["abs"], "coo ttm %s" % name)
+    first = Y.vals()
+    comet.comet_ttm(X, 2, dev(U), Y)             # reuse of the result handle
+    torch.cuda.synchronize()
+    assert torch.equal(first, Y.vals())
+    B = gen.dense_operand(51, 1, (dims[1], R))
+    M = torch.full((dims[0], R), float("nan"), dtype=torch.float64, device="cuda")
+    comet.comet_mttkrp(X, 0, [None, dev(B), dev(U)], M)
+    torch.cuda.synchronize()
+    refm, absm = oracle.mttkrp(np_(i), np_(j), np_(k), np_(vals), dims, np_(B), np_(U))
+    assert_values_close(np_(M), refm, absm, "coo mttkrp %s" % name)
+
+
 def test_mttkrp_rank_one_is_ttv_twice_on_the_gpu(comet):
     """The sparse TTV result is itself a [CU,CU] matrix handle, so SpMV applies to it."""
     dims, (i, j, k, vals) = TENSOR_CASES["zipf_mttkrp"]
