@@ -162,13 +162,14 @@ comet_status comet_tensor_convert(const comet_tensor *X, const int32_t *mode_ord
                                   comet_tensor **out, void *stream);
 
 /* SpMV, y = A x :  y_i = sum_j a_ij x_j   (Section 8.2, SpMV).
- *   A   order-2 handle, [D,CU] or [CU,CU].
+ *   A   order-2 handle, [D,CU] or [CU,CU]; a coordinate list [CN,S] is accepted too and works
+ *       through a compressed copy built inside the handle on the first call (see comet_ttm).
  *   x   device, [dims[1]].          y   device, [dims[0]]; every entry is overwritten
  *                                       (rows without stored nonzeros become 0). */
 comet_status comet_spmv(const comet_tensor *A, const double *x, double *y, void *stream);
 
 /* SpMM, C = A B :  c_ir = sum_j a_ij b_jr   (Section 8.2, SpMM; the paper's example program).
- *   A   order-2 handle, [D,CU] or [CU,CU].
+ *   A   order-2 handle, [D,CU], [CU,CU] or (through a compressed copy) [CN,S].
  *   B   device, [dims[1] x R] row-major.   C   device, [dims[0] x R] row-major, overwritten.
  *   R   number of dense columns, 1 <= R <= 1024. */
 comet_status comet_spmm(const comet_tensor *A, const double *B, int64_t R, double *C, void *stream);

@@ -596,9 +596,28 @@ comet_status comet_tensor_convert(const comet_tensor *X, const int32_t *mode_ord
     return restore(X, mode_order, target, out, (hipStream_t)stream);
 }
 
+// The compressed copy of a sorted coordinate list (same level order), built on first use.
+static comet_status ensure_shadow(const comet_tensor *X, hipStream_t st) {
+    comet_tensor *m = const_cast<comet_tensor *>(X);
+    if (m->shadow) return COMET_OK;
+    comet_tensor *s = nullptr;
+    comet_status rs = restore(X, X->mode_of_level, Target::ALL_CU, &s, st);
+    if (rs != COMET_OK) return rs;
+    s->variant = X->variant;
+    m->shadow.reset(s);
+    return COMET_OK;
+}
+
 // ---- SpMV / SpMM: the last level is compressed; rows come from a dense or compressed root -------
 static comet_status matrix_product(const comet_tensor *A, const double *Dn, int64_t R, double *out, hipStream_t st) {
     if (!A || !Dn || !out) return COMET_ERR_INVALID_ARG;
+    if (A->fmt == Format::COO2) {
+        // a coordinate list [CN,S]: rows come from its compressed ([CU,CU]) copy, built on the first call
+        comet_status rs = ensure_shadow(A, st);
+        if (rs != COMET_OK) return rs;
+        A->shadow->variant = A->variant;
+        A = A->shadow.get();
+    }
     if (A->fmt != Format::CSR && A->fmt != Format::DCSR) return COMET_ERR_UNSUPPORTED;
     if (R < 1 || R > 1024) return COMET_ERR_UNSUPPORTED;
     const int64_t nseg = A->pos_len[1] - 1, nnz = A->nvals;
@@ -634,18 +653,6 @@ comet_status comet_spmv(const comet_tensor *A, const double *x, double *y, void 
 
 comet_status comet_spmm(const comet_tensor *A, const double *B, int64_t R, double *C, void *stream) {
     return matrix_product(A, B, R, C, (hipStream_t)stream);
-}
-
-// The compressed copy of a sorted coordinate list (same level order), built on first use.
-static comet_status ensure_shadow(const comet_tensor *X, hipStream_t st) {
-    comet_tensor *m = const_cast<comet_tensor *>(X);
-    if (m->shadow) return COMET_OK;
-    comet_tensor *s = nullptr;
-    comet_status rs = restore(X, X->mode_of_level, Target::ALL_CU, &s, st);
-    if (rs != COMET_OK) return rs;
-    s->variant = X->variant;
-    m->shadow.reset(s);
-    return COMET_OK;
 }
 
 // ---- TTV / TTM along the mode stored in the last level ------------------------------------------

@@ -103,6 +103,28 @@ def test_spmm(comet, name, layout, R, variant):
     assert_values_close(np_(C), ref, absum, "spmm %s R=%d" % (name, R))
 
 
+@pytest.mark.parametrize("R", [1, 16])
+@pytest.mark.parametrize("name", ["zipf_rows", "edge_lengths", "hypersparse", "empty", "single"])
+def test_products_of_a_coordinate_list_matrix(comet, name, R):
+    """[CN,S] input works through the compressed copy the handle builds for itself."""
+    (I, J), (rows, cols, vals) = MATRIX_CASES[name]
+    A = comet.from_levels(fmt.pack_coo((I, J), (rows, cols), vals).to("cuda"))
+    if R == 1:
+        x = gen.dense_operand(61, 0, (J,))
+        y = torch.full((I,), float("nan"), dtype=torch.float64, device="cuda")
+        comet.comet_spmv(A, dev(x), y)
+        torch.cuda.synchronize()
+        ref, absum = oracle.spmv(np_(rows), np_(cols), np_(vals), (I, J), np_(x))
+        assert_values_close(np_(y), ref, absum, "coo spmv %s" % name)
+    else:
+        B = gen.dense_operand(61, 1, (J, R))
+        C = torch.full((I, R), float("nan"), dtype=torch.float64, device="cuda")
+        comet.comet_spmm(A, dev(B), C)
+        torch.cuda.synchronize()
+        ref, absum = oracle.spmm(np_(rows), np_(cols), np_(vals), (I, J), np_(B))
+        assert_values_close(np_(C), ref, absum, "coo spmm %s" % name)
+
+
 def test_spmm_of_ones_gives_row_sums_in_every_column(comet):
     """The paper's example program: B filled with 1.0."""
     (I, J), (rows, cols, vals) = MATRIX_CASES["zipf_rows"]
