@@ -139,6 +139,11 @@ def test_random_tensors(comet, block):
             assert_index_equal(np_(Yc.crd(0)), ref["i"], "coo ttv crd1")
             assert_index_equal(np_(Yc.crd(1)), ref["j"], "coo ttv crd2")
             assert_values_close(np_(Yc.vals()), ref["vals"], ref["abs"], "coo ttv sweep %d/%d" % (block, case))
+            Yt = comet.comet_ttm(Xc, 2, dev(U))
+            torch.cuda.synchronize()
+            assert_index_equal(np_(Yt.crd(0)), refm["i"], "coo ttm crd1")
+            assert_index_equal(np_(Yt.crd(1)), refm["j"], "coo ttm crd2")
+            assert_values_close(np_(Yt.vals()).reshape(-1, R), refm["vals"], refm["abs"], "coo ttm sweep %d/%d" % (block, case))
         # MTTKRP for mode `mode`
         Xr = (X if (mode == 0 and source == "csf") else comet.comet_tensor_reorder(X, (mode, a, b))).set_variant(variant)
         F = [gen.dense_operand(seed, 2 + m, (dims[m], R)) for m in range(3)]
@@ -147,3 +152,7 @@ def test_random_tensors(comet, block):
         torch.cuda.synchronize()
         refk, absk = oracle.mttkrp_mode(coords, np_(vals), dims, mode, [np_(f) for f in F])
         assert_values_close(np_(M), refk, absk, "mttkrp sweep %d/%d" % (block, case))
+        if mode == 0 and source == "coo":        # the coordinate list itself, through its compressed copy
+            M2 = comet.comet_mttkrp(X.set_variant(variant), 0, [None, dev(F[1]), dev(F[2])])
+            torch.cuda.synchronize()
+            assert_values_close(np_(M2), refk, absk, "coo mttkrp sweep %d/%d" % (block, case))
