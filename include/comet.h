@@ -19,9 +19,11 @@
  *     by arrays that violate the format (and were not validated) are not detected.
  *   - A tensor handle owns per-tensor scratch memory: at most one operation per handle may
  *     be in flight at a time (operations on one stream are ordered and therefore safe).  The
- *     scratch is allocated by the first operation of a given rank R on the handle (a device
- *     allocation, so that first call cannot be captured into a HIP graph); later calls with the
- *     same or a smaller R allocate nothing, clear what they reuse with kernels, and can be captured.
+ *     scratch is allocated by comet_tensor_reserve, or else by the first operation that needs more
+ *     than the handle holds (a device allocation, so that call cannot be captured into a HIP
+ *     graph); calls that fit into what is there allocate nothing, clear what they reuse with
+ *     kernels, and can be captured.  Scratch only grows and is never freed before the handle is
+ *     destroyed, so an address that earlier work or a captured graph uses stays valid.
  */
 #ifndef COMET_H
 #define COMET_H
@@ -114,8 +116,17 @@ comet_status comet_tensor_create(comet_tensor **out, int order,
 
 /* Release a handle and everything the library allocated for it (borrowed arrays are left
  * alone).  Level arrays that a TTV/TTM result shares with its input stay valid until the last
- * handle that uses them is destroyed.  NULL is accepted. */
+ * handle that uses them is destroyed.  Waits for the streams the handle's operations were enqueued
+ * on (for the whole device if they were more than four, or the null stream).  NULL is accepted. */
 comet_status comet_tensor_destroy(comet_tensor *t);
+
+/* Allocate now everything that operations of rank <= R on this handle would otherwise allocate on
+ * their first call: the carry / partial-sum scratch of the kernels and, for a coordinate list
+ * ([CN,S], [CN,S,S]), the compressed copy that SpMV / SpMM / TTM / MTTKRP work through (one device
+ * sort; synchronises with `stream`).  Afterwards those operations allocate nothing, except the
+ * result handle of comet_ttv / comet_ttm when *Y is NULL.  R = 1 covers SpMV and TTV.
+ * Errors: COMET_ERR_INVALID_ARG (null handle, R outside 1..1024), COMET_ERR_ALLOC. */
+comet_status comet_tensor_reserve(comet_tensor *t, int64_t R, void *stream);
 
 /* Fill *info (host) with the handle's description; pointers inside are device pointers that
  * stay valid until the handle is destroyed. */
@@ -220,7 +231,9 @@ comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *
 const char *comet_status_string(comet_status s);
 
 /* Choose the kernel family used by later operations on this handle: 0 = automatic,
- * 1 = the simple one-lane-group-per-segment kernels, 2 = the nonzero-tiled streaming kernels.
+ * 1 = the simple one-lane-group-per-segment kernels, 2 = the nonzero-tiled streaming kernels with
+ * all their specialisations, 3 = the nonzero-tiled kernels in their plain per-tile form only (no
+ * operand staging in LDS, no heavy-row sweep): the baseline the specialisations are measured against.
  * For testing and measurement; results are the same up to summation order. */
 comet_status comet_tensor_set_variant(comet_tensor *t, int variant);
 

@@ -27,7 +27,7 @@ _STATUS_NAMES = {0: "COMET_OK", 1: "COMET_ERR_INVALID_ARG", 2: "COMET_ERR_BAD_FO
 
 EXPORTS = ["comet_tensor_create", "comet_tensor_destroy", "comet_tensor_info", "comet_spmv", "comet_spmm",
            "comet_ttv", "comet_ttm", "comet_mttkrp", "comet_status_string", "comet_tensor_set_variant",
-           "comet_tensor_reorder", "comet_tensor_convert"]
+           "comet_tensor_reorder", "comet_tensor_convert", "comet_tensor_reserve"]
 
 
 class CometError(RuntimeError):
@@ -65,6 +65,7 @@ def _lib():
         lib.comet_tensor_destroy.argtypes = [vp]
         lib.comet_tensor_info.argtypes = [vp, ctypes.POINTER(_Info)]
         lib.comet_spmv.argtypes = [vp, vp, vp, vp]
+        lib.comet_tensor_reserve.argtypes = [vp, i64, vp]
         lib.comet_spmm.argtypes = [vp, vp, i64, vp, vp]
         lib.comet_ttv.argtypes = [vp, ci, vp, ctypes.POINTER(vp), vp]
         lib.comet_ttm.argtypes = [vp, ci, vp, i64, ctypes.POINTER(vp), vp]
@@ -174,6 +175,10 @@ class Tensor:
         """The value array; copy=False returns a view of the library's memory (valid while the handle lives)."""
         inf = self.info()
         return self._wrap(inf.vals, inf.nvals, "<f8", torch.float64, copy)
+
+    def reserve(self, R: int, stream=None) -> "Tensor":
+        _check(_lib().comet_tensor_reserve(self.handle, int(R), _stream(stream)), "comet_tensor_reserve")
+        return self
 
     def set_variant(self, variant: int) -> "Tensor":
         _check(_lib().comet_tensor_set_variant(self.handle, variant), "comet_tensor_set_variant")

@@ -57,7 +57,18 @@ def build(verbose: bool = False, only_changed: bool = False) -> str:
 
 
 def build_if_missing() -> str:
-    return LIB_PATH if os.path.exists(LIB_PATH) else build()
+    """The built library if there is one (tests, the smoke check and the benchmark load what is built), else
+    build it.  A library older than a source or header is still used -- the build step is explicit -- but
+    that is said loudly, since results then come from stale code."""
+    if os.path.exists(LIB_PATH):
+        deps = sources() + glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(os.path.join(_HERE, "..", "include", "*.h"))
+        newest = max(deps, key=os.path.getmtime)
+        if os.path.getmtime(LIB_PATH) < os.path.getmtime(newest):
+            import sys
+            print("WARNING: %s is older than %s -- run `python -m paper_2102_05187_amd.build` to rebuild" % (
+                os.path.basename(LIB_PATH), os.path.relpath(newest, _HERE)), file=sys.stderr, flush=True)
+        return LIB_PATH
+    return build()
 
 
 if __name__ == "__main__":

@@ -153,14 +153,25 @@ comet_status validate_on_device(const comet_tensor &t, hipStream_t st) {
     return h ? COMET_ERR_BAD_FORMAT : COMET_OK;
 }
 
+// Grow-only: a buffer that is too small is retired (kept alive until the handle is destroyed), never freed
+// inside an operation -- earlier work, or a captured graph, may still hold its address.
 comet_status ensure_scratch(const comet_tensor *t, size_t bytes) {
-    comet_tensor *m = const_cast<comet_tensor *>(t);
-    if (m->scratch && m->scratch_bytes >= bytes) return COMET_OK;
-    m->scratch.reset();
-    m->scratch = comet::dev_alloc(bytes);
-    if (!m->scratch) { m->scratch_bytes = 0; return COMET_ERR_ALLOC; }
-    m->scratch_bytes = bytes;
+    if (t->scratch && t->scratch_bytes >= bytes) return COMET_OK;
+    comet::DevRef fresh = comet::dev_alloc(bytes);
+    if (!fresh) return COMET_ERR_ALLOC;
+    if (t->scratch) t->retired_scratch.push_back(t->scratch);
+    t->scratch = fresh;
+    t->scratch_bytes = bytes;
     return COMET_OK;
+}
+
+// Remember the stream an operation was enqueued on, so that destroy can wait for it.
+void note_stream(const comet_tensor *t, hipStream_t st) {
+    if (!st) { t->used_null_stream = true; return; }
+    for (int q = 0; q < t->n_used_streams && q < 4; ++q)
+        if (t->used_streams[q] == (void *)st) return;
+    if (t->n_used_streams < 4) t->used_streams[t->n_used_streams] = (void *)st;
+    t->n_used_streams += 1;
 }
 
 constexpr int64_t kShortSegment = 256;
@@ -186,7 +197,8 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // level with the tiled kernel from about 4M nonzeros on, far behind it once one segment is long).
 // `serial` = the most nonzeros one thread of the simple kernel would walk alone (longest leaf segment, or
 // for MTTKRP the most nonzeros under one slice); 0 = unknown.
-bool use_tiled(const comet_tensor *t, int64_t R, const void *dense, int64_t dense_rows, int64_t serial) {
+bool use_tiled(const comet_tensor *t, int64_t R, const void *dense, const void *result, int64_t dense_rows,
+               int64_t serial) {
     if (t->variant == 1) return false;
     if (!comet::stream_supports_rank(R)) return false;
     if (t->variant == 0 && R == 1 && serial > 0 && serial <= kShortSegment && t->sched.nnz <= kSmallProblemNnz)
@@ -200,7 +212,7 @@ bool use_tiled(const comet_tensor *t, int64_t R, const void *dense, int64_t dens
     if (t->variant == 0 && t->sched.empty_segments > 16 * t->sched.nnz + 4096) return false;
     if (R > 1 && dense_rows * R >= (int64_t(1) << 32) - 4096) return false;
     const int leaf = t->order - 1;
-    if (!aligned16(t->crd_i(leaf)) || !aligned16(t->vals_d()) || !aligned16(dense)) return false;
+    if (!aligned16(t->crd_i(leaf)) || !aligned16(t->vals_d()) || !aligned16(dense) || !aligned16(result)) return false;
     return true;
 }
 
@@ -343,11 +355,48 @@ comet_status comet_tensor_create(comet_tensor **out, int order, const int64_t *d
     return COMET_OK;
 }
 
+// Work that uses the handle's arrays may still be in flight: wait for the streams its operations were
+// enqueued on (the whole device only if there were more of them than the handle remembers, or the null stream).
 comet_status comet_tensor_destroy(comet_tensor *t) {
     if (!t) return COMET_OK;
-    (void)hipDeviceSynchronize();
+    if (t->used_null_stream || t->n_used_streams > 4) {
+        (void)hipDeviceSynchronize();
+    } else {
+        for (int q = 0; q < t->n_used_streams; ++q)
+            if (hipStreamSynchronize((hipStream_t)t->used_streams[q]) != hipSuccess) { (void)hipGetLastError(); (void)hipDeviceSynchronize(); break; }
+    }
     delete t;
     return COMET_OK;
+}
+
+static comet_status ensure_shadow(const comet_tensor *X, hipStream_t st);
+
+// Scratch that operations of rank <= R may ask for on this handle.
+static size_t scratch_need(const comet_tensor *t, int64_t R) {
+    size_t need = 0;
+    if (t->sched.nchunks > 0) need = comet::stream_scratch_bytes(t->sched.nchunks, 1);
+    if (t->sched.ntiles > 0 && comet::stream_supports_rank(R)) {
+        const size_t b = comet::stream_scratch_bytes(t->sched.ntiles, R);
+        if (b > need) need = b;
+    }
+    return need;
+}
+
+comet_status comet_tensor_reserve(comet_tensor *t, int64_t R, void *stream) {
+    if (!t || R < 1 || R > 1024) return COMET_ERR_INVALID_ARG;
+    const int64_t Rt = R > 128 ? 128 : R;     // ranks above 128 run on kernels that need no scratch
+    const comet_tensor *target = t;
+    if (t->fmt == Format::COO2 || t->fmt == Format::COO3) {
+        comet_status rs = ensure_shadow(t, (hipStream_t)stream);
+        if (rs != COMET_OK) return rs;
+        target = t->shadow.get();
+        if (t->fmt == Format::COO3) {               // TTV runs on the coordinate list itself
+            const size_t own = scratch_need(t, 1);
+            if (own) { rs = ensure_scratch(t, own); if (rs != COMET_OK) return rs; }
+        }
+    }
+    const size_t need = scratch_need(target, Rt);
+    return need ? ensure_scratch(target, need) : COMET_OK;
 }
 
 comet_status comet_tensor_info(const comet_tensor *t, comet_tensor_info_t *info) {
@@ -369,7 +418,7 @@ comet_status comet_tensor_info(const comet_tensor *t, comet_tensor_info_t *info)
 }
 
 comet_status comet_tensor_set_variant(comet_tensor *t, int variant) {
-    if (!t || variant < 0 || variant > 2) return COMET_ERR_INVALID_ARG;
+    if (!t || variant < 0 || variant > 3) return COMET_ERR_INVALID_ARG;
     t->variant = variant;
     return COMET_OK;
 }
@@ -598,20 +647,23 @@ comet_status comet_tensor_convert(const comet_tensor *X, const int32_t *mode_ord
 
 // The compressed copy of a sorted coordinate list (same level order), built on first use.
 static comet_status ensure_shadow(const comet_tensor *X, hipStream_t st) {
-    comet_tensor *m = const_cast<comet_tensor *>(X);
-    if (m->shadow) return COMET_OK;
+    if (X->shadow) return COMET_OK;
     comet_tensor *s = nullptr;
     comet_status rs = restore(X, X->mode_of_level, Target::ALL_CU, &s, st);
     if (rs != COMET_OK) return rs;
     s->variant = X->variant;
-    m->shadow.reset(s);
+    X->shadow.reset(s);
     return COMET_OK;
 }
 
 // ---- SpMV / SpMM: the last level is compressed; rows come from a dense or compressed root -------
-static comet_status matrix_product(const comet_tensor *A, const double *Dn, int64_t R, double *out, hipStream_t st) {
+// ext_scratch != nullptr: the caller supplies the carry scratch (ext_bytes of it) and nothing may be allocated.
+static comet_status matrix_product(const comet_tensor *A, const double *Dn, int64_t R, double *out, hipStream_t st,
+                                   void *ext_scratch = nullptr, size_t ext_bytes = 0) {
     if (!A || !Dn || !out) return COMET_ERR_INVALID_ARG;
+    note_stream(A, st);
     if (A->fmt == Format::COO2) {
+        if (ext_scratch) return COMET_ERR_UNSUPPORTED;      // the compressed copy would have to be allocated
         // a coordinate list [CN,S]: rows come from its compressed ([CU,CU]) copy, built on the first call
         comet_status rs = ensure_shadow(A, st);
         if (rs != COMET_OK) return rs;
@@ -621,6 +673,9 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
     if (A->fmt != Format::CSR && A->fmt != Format::DCSR) return COMET_ERR_UNSUPPORTED;
     if (R < 1 || R > 1024) return COMET_ERR_UNSUPPORTED;
     const int64_t nseg = A->pos_len[1] - 1, nnz = A->nvals;
+    const bool tiled = nnz > 0 && use_tiled(A, R, Dn, out, A->dims[1], A->sched.max_seg_len);
+    const size_t need = tiled ? comet::stream_scratch_bytes(R == 1 ? A->sched.nchunks : A->sched.ntiles, R) : 0;
+    if (ext_scratch && need > ext_bytes) return COMET_ERR_UNSUPPORTED;       // before anything is enqueued
     const int32_t *rowmap = nullptr;
     if (A->fmt == Format::DCSR) {
         // Rows absent from the root level hold no nonzeros and must come out as zeros.  Every stored row is
@@ -635,12 +690,15 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
         if (A->fmt == Format::CSR) HIP_TRY(comet::fill_zero_f64(out, A->dims[0] * R, st));
         return COMET_OK;
     }
-    if (use_tiled(A, R, Dn, A->dims[1], A->sched.max_seg_len)) {
-        size_t need = comet::stream_scratch_bytes(R == 1 ? A->sched.nchunks : A->sched.ntiles, R);
-        comet_status rs = ensure_scratch(A, need);
-        if (rs != COMET_OK) return rs;
+    if (tiled) {
+        void *scr = ext_scratch;
+        if (!ext_scratch) {
+            comet_status rs = ensure_scratch(A, need);
+            if (rs != COMET_OK) return rs;
+            scr = A->scratch->ptr;
+        }
         HIP_TRY(comet::stream_segreduce(A->sched, A->pos_i(1), A->crd_i(1), A->vals_d(), rowmap, Dn, A->dims[1], R, out,
-                                        A->scratch->ptr, st));
+                                        scr, A->variant == 3, st));
         return COMET_OK;
     }
     HIP_TRY(comet::simple_segreduce(A->pos_i(1), A->crd_i(1), A->vals_d(), nseg, nnz, rowmap, Dn, R, out, st));
@@ -659,6 +717,7 @@ comet_status comet_spmm(const comet_tensor *A, const double *B, int64_t R, doubl
 static comet_status leaf_contract(const comet_tensor *X, int mode, const double *Dn, int64_t R, int kind,
                                   comet_tensor **Y, hipStream_t st) {
     if (!X || !Dn || !Y) return COMET_ERR_INVALID_ARG;
+    note_stream(X, st);
     if (X->order != 3) return COMET_ERR_UNSUPPORTED;
     if (R < 1 || R > 1024) return COMET_ERR_UNSUPPORTED;
     const bool csf = X->fmt == Format::CSF3, coo = X->fmt == Format::COO3;
@@ -677,7 +736,7 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
         rs = ensure_shadow(X, st);
         if (rs != COMET_OK) return rs;
         S = X->shadow.get();
-        const_cast<comet_tensor *>(S)->variant = X->variant;      // the kernel family chosen for X applies to its copy
+        X->shadow->variant = X->variant;                          // the kernel family chosen for X applies to its copy
     }
     const int64_t nout = csf ? X->crd_len[1] : (S ? S->crd_len[1] : X->sched.nruns);    // stored (i,j) pairs
     if (fresh) {
@@ -722,22 +781,22 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
     if (X->nvals > 0) {
         if (csf || S) {
             const comet_tensor *C = csf ? X : S;                 // the compressed storage the kernels walk
-            if (use_tiled(C, R, Dn, C->dims[2], C->sched.max_seg_len)) {
+            if (use_tiled(C, R, Dn, yv, C->dims[2], C->sched.max_seg_len)) {
                 rs = ensure_scratch(C, comet::stream_scratch_bytes(R == 1 ? C->sched.nchunks : C->sched.ntiles, R));
                 if (rs != COMET_OK) return rs;
                 HIP_TRY(comet::stream_segreduce(C->sched, C->pos_i(2), C->crd_i(2), C->vals_d(), nullptr, Dn, C->dims[2], R,
-                                                yv, C->scratch->ptr, st));
+                                                yv, C->scratch->ptr, C->variant == 3, st));
             } else {
                 HIP_TRY(comet::simple_segreduce(C->pos_i(2), C->crd_i(2), C->vals_d(), C->pos_len[2] - 1, C->nvals,
                                                 nullptr, Dn, R, yv, st));
             }
         } else {
-            if (use_tiled(X, 1, Dn, 0, 0) && comet::stream_supports_coo()) {
+            if (use_tiled(X, 1, Dn, yv, 0, 0) && comet::stream_supports_coo()) {
                 rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.nchunks, 1));
                 if (rs != COMET_OK) return rs;
                 HIP_TRY(comet::stream_ttv_coo(X->sched, X->crd_i(0), X->crd_i(1), X->crd_i(2), X->vals_d(), Dn, X->dims[2],
                                               (int32_t *)y->crd[0]->ptr, (int32_t *)y->crd[1]->ptr, yv,
-                                              X->scratch->ptr, st));
+                                              X->scratch->ptr, X->variant == 3, st));
             } else {
                 HIP_TRY(comet::simple_ttv_coo(X->crd_i(0), X->crd_i(1), X->crd_i(2), X->vals_d(), X->nvals, comet::kTile,
                                               X->sched.ntiles, (const int32_t *)X->sched.run_base->ptr, Dn,
@@ -762,6 +821,7 @@ comet_status comet_ttm(const comet_tensor *X, int mode, const double *U, int64_t
 comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *factors, int64_t R, double *M,
                           void *stream) {
     if (!X || !factors || !M) return COMET_ERR_INVALID_ARG;
+    note_stream(X, (hipStream_t)stream);
     if (X->fmt == Format::COO3) {
         // a sorted coordinate list: the slice / fiber structure comes from its compressed copy
         comet_status rs = ensure_shadow(X, (hipStream_t)stream);
@@ -779,7 +839,7 @@ comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *
     hipStream_t st = (hipStream_t)stream;
     const int64_t nslice = X->pos_len[1] - 1;
     const bool tiled = X->nvals > 0 &&
-                       use_tiled(X, R, B, 0, X->sched.max_parent_len) && aligned16(C) &&
+                       use_tiled(X, R, B, M, 0, X->sched.max_parent_len) && aligned16(C) &&
                        comet::stream_mttkrp_supports_rank(R);
     // Rows of M whose index is not stored at the root level receive no contribution.  The tiled kernel
     // writes every stored slice's row itself (a slice without nonzeros is cleared in its slice pass), so

@@ -1,5 +1,7 @@
 // Rank-1 kernels of the nonzero-tiled family (SpMV, TTV on CSF and on sorted coordinate lists), the
 // carry fix-up kernels shared by all of them, and the host entry points of the family.
+#include <atomic>
+
 #include "stream_common.hpp"
 
 namespace comet {
@@ -537,10 +539,15 @@ static hipError_t allow_full_lds() {
     return status;
 }
 
-// COMET_NO_LDS_VECTOR=1 keeps rank-1 operations on the L1-gather kernel (for measurements).
-static bool no_lds_vector() {
-    static int v = [] { const char *e = getenv("COMET_NO_LDS_VECTOR"); return e ? atoi(e) : 0; }();
-    return v != 0;
+int current_device_cu_count() {
+    static std::atomic<int> cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return 256; }
+    if (dev >= 0 && dev < 64 && cached[dev].load() > 0) return cached[dev].load();
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) { (void)hipGetLastError(); n = 256; }
+    if (dev >= 0 && dev < 64) cached[dev].store(n);
+    return n;
 }
 
 bool stream_supports_rank(int64_t R) { return R >= 1 && R <= 128; }
@@ -560,16 +567,16 @@ size_t stream_scratch_bytes(int64_t ntiles, int64_t R) {
 
 hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                             const int32_t *rowmap, const double *Dn, int64_t dense_rows, int64_t R, double *out,
-                            void *scratch, hipStream_t st) {
+                            void *scratch, bool plain, hipStream_t st) {
     if (sc.ntiles <= 0) return hipSuccess;
     if (!stream_supports_rank(R)) return hipErrorNotSupported;
     const int32_t *sb = (const int32_t *)sc.seg_begin->ptr;
     hipError_t e = hipSuccess;
     if (R == 1) {
         const size_t lds_bytes = (size_t)((dense_rows + 1) & ~(int64_t)1) * 8 + 16 * 128 + 16 * 8 + 16 * 4;
-        if (sc.empty_segments == 0 && sc.chunk_seg_begin && sc.nchunks >= 16 && lds_bytes <= 160 * 1024 && !no_lds_vector()) {
+        if (sc.empty_segments == 0 && sc.chunk_seg_begin && sc.nchunks >= 16 && lds_bytes <= 160 * 1024 && !plain) {
             // the dense vector fits in LDS and every segment holds a nonzero: wavefront-per-chunk kernel
-            static int ncu = [] { hipDeviceProp_t p; return hipGetDeviceProperties(&p, 0) == hipSuccess ? p.multiProcessorCount : 256; }();
+            const int ncu = current_device_cu_count();
             const int64_t want = (sc.nchunks + 15) / 16;
             const unsigned grid = (unsigned)(want < ncu ? want : ncu);
             const int32_t *csb = (const int32_t *)sc.chunk_seg_begin->ptr;
@@ -606,13 +613,13 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
 
 hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *c1, const int32_t *c2,
                           const double *vals, const double *v, int64_t dense_rows, int32_t *y0, int32_t *y1, double *yv,
-                          void *scratch, hipStream_t st) {
+                          void *scratch, bool plain, hipStream_t st) {
     if (sc.ntiles <= 0) return hipSuccess;
     // a run of equal (c0, c1) holds at most one nonzero per coordinate of the last mode
     const int64_t max_run = dense_rows;
     const size_t lds_bytes = (size_t)((dense_rows + 1) & ~(int64_t)1) * 8 + 16 * 128 + 16 * 8 + 16 * 4;
-    if (sc.chunk_run_base && sc.nchunks >= 16 && lds_bytes <= 160 * 1024 && !no_lds_vector()) {
-        static int ncu = [] { hipDeviceProp_t p; return hipGetDeviceProperties(&p, 0) == hipSuccess ? p.multiProcessorCount : 256; }();
+    if (sc.chunk_run_base && sc.nchunks >= 16 && lds_bytes <= 160 * 1024 && !plain) {
+        const int ncu = current_device_cu_count();
         const int64_t want = (sc.nchunks + 15) / 16;
         const unsigned grid = (unsigned)(want < ncu ? want : ncu);
         hipError_t e = allow_full_lds<k_stream_rank1_ldsvec<false, true>>();

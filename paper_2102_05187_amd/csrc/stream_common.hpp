@@ -28,8 +28,6 @@
 //           k_fixup_level / k_stream_fixup   carry resolution
 #pragma once
 
-#include <cstdlib>
-
 #include "stream_kernels.hpp"
 
 namespace comet {
@@ -254,14 +252,8 @@ __device__ __forceinline__ void finish_tile_walkers(const double *wopen, const i
 
 }  // namespace
 
-// Lane-group width of the rank-R kernels: 8 by default; COMET_LANES=4 selects the quad mapping
-// (for measurements).  Ranks up to 8 always use quads.
-inline int lanes_per_item(int64_t R) {
-    static int forced = [] { const char *e = getenv("COMET_LANES"); return e ? atoi(e) : 0; }();
-    if (R <= 8) return 4;
-    if (forced == 4 && R <= 64) return 4;
-    return 8;
-}
+// Lane-group width of the rank-R kernels: 8 lanes, quads for ranks up to 8.
+inline int lanes_per_item(int64_t R) { return R <= 8 ? 4 : 8; }
 
 // Calls F<L, V, WIDE>(args...) for the specialisation that covers rank R.
 #define COMET_DISPATCH_RANK(F, R, ...)                                                     \
@@ -269,14 +261,8 @@ inline int lanes_per_item(int64_t R) {
         const int r_ = (int)(R);                                                           \
         if (lanes_per_item(r_) == 4) {                                                     \
             if (r_ == 8)  return F<4, 2, true>(__VA_ARGS__);                               \
-            if (r_ == 16) return F<4, 4, true>(__VA_ARGS__);                               \
-            if (r_ == 32) return F<4, 8, true>(__VA_ARGS__);                               \
-            if (r_ == 64) return F<4, 16, true>(__VA_ARGS__);                              \
             if (r_ <= 4)  return F<4, 1, false>(__VA_ARGS__);                              \
-            if (r_ <= 8)  return F<4, 2, false>(__VA_ARGS__);                              \
-            if (r_ <= 16) return F<4, 4, false>(__VA_ARGS__);                              \
-            if (r_ <= 32) return F<4, 8, false>(__VA_ARGS__);                              \
-            return F<4, 16, false>(__VA_ARGS__);                                           \
+            return F<4, 2, false>(__VA_ARGS__);                                            \
         }                                                                                  \
         if (r_ == 16)  return F<8, 2, true>(__VA_ARGS__);                                  \
         if (r_ == 32)  return F<8, 4, true>(__VA_ARGS__);                                  \

@@ -22,14 +22,19 @@ size_t stream_scratch_bytes(int64_t ntiles, int64_t R);
 
 // out[row(s), :] = sum_{p in segment s} vals[p] * Dn[crd[p], :],  row(s) = rowmap ? rowmap[s] : s.
 // Every segment of the level is written (empty ones with zeros).  dense_rows = number of rows of Dn.
+// plain = true keeps rank-1 work on the per-tile kernel that gathers the vector through L1 (measurement
+// baseline) instead of the kernel that stages it in LDS.
 hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                             const int32_t *rowmap, const double *Dn, int64_t dense_rows, int64_t R, double *out,
-                            void *scratch, hipStream_t st);
+                            void *scratch, bool plain, hipStream_t st);
 
 // Sorted COO [CN,S,S]: one output (i, j, value) per run of equal (c0, c1).
 hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *c1, const int32_t *c2,
                           const double *vals, const double *v, int64_t dense_rows, int32_t *y0, int32_t *y1, double *yv,
-                          void *scratch, hipStream_t st);
+                          void *scratch, bool plain, hipStream_t st);
+
+// Number of compute units of the current device (cached per device).
+int current_device_cu_count();
 
 // M[crd1[s], :] = sum_{f in slice s} B[crd2[f], :] * (sum_{p in fiber f} vals[p] * C[crd3[p], :]).
 // M must have been cleared for rows that have no stored slice.

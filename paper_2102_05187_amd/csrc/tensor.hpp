@@ -81,13 +81,22 @@ struct comet_tensor {
     comet::Schedule sched;
     int variant = 0;
 
-    // scratch owned by the handle (carry buffers of the tiled kernels), grown on demand
-    comet::DevRef scratch;
-    size_t scratch_bytes = 0;
+    // Scratch owned by the handle (carry buffers of the tiled kernels and the partial sums of the heavy-row
+    // sweep).  It only ever grows: when an operation needs more than there is, a larger buffer is allocated
+    // and the old one is kept until the handle is destroyed, so work that was enqueued (or captured into a
+    // HIP graph) with the old address never sees freed memory.  `mutable`: operations take the handle as
+    // const and still manage this cache (one operation per handle at a time, see comet.h).
+    mutable comet::DevRef scratch;
+    mutable size_t scratch_bytes = 0;
+    mutable std::vector<comet::DevRef> retired_scratch;
+    // streams the handle's operations were enqueued on (a few are remembered; destroy waits for them)
+    mutable void *used_streams[4] = {nullptr, nullptr, nullptr, nullptr};
+    mutable int  n_used_streams = 0;      // > 4: too many to remember, destroy waits for the whole device
+    mutable bool used_null_stream = false;
 
     // a sorted coordinate list keeps a compressed ([CU,CU,CU]) copy of itself for the operations whose
     // kernels need the fiber / slice structure (TTM, MTTKRP); built on their first use
-    std::unique_ptr<comet_tensor> shadow;
+    mutable std::unique_ptr<comet_tensor> shadow;
 
     // results of TTV / TTM remember what produced them so the handle can be reused
     const comet_tensor *result_of = nullptr;

@@ -1,10 +1,15 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
 
-The oracle cannot evaluate 10^8-nonzero tensors element by element within the test budget, so each
-case checks (a) sampled output rows / fibers / slices -- random ones plus the heaviest one, which is
-cut over the most kernel tiles -- against the oracle run on exactly the nonzeros that feed them, and
-(b) properties that hold at any size: index outputs bit-identical to the expected structure, rows
-without stored nonzeros exactly zero.
+SpMM, TTV (both formats), TTM and MTTKRP at rank 16 are compared with the oracle on EVERY output element
+(the oracle walks all 18.5 M - 150 M nonzeros; tens of seconds of host time each).  The cases whose oracle run
+would take minutes (MTTKRP at rank 64, the re-stored modes, the results beyond 2^31 values) check sampled
+output rows / fibers / slices -- random ones plus the heaviest, which are cut over the most kernel tiles --
+against the oracle run on exactly the nonzeros that feed them.  Every case also checks what holds at any
+size: index outputs bit-identical to the expected structure, rows without stored nonzeros exactly zero.
+
+The oracle is always fed from the seeded generator's own coordinate list (i, j, k, vals), never from
+anything the library produced: a re-stored tensor is first compared, as a whole, with a torch sort of the
+packed original coordinates, and the oracle then gets the original nonzeros in that order.
 """
 import numpy as np
 import pytest
@@ -47,27 +52,62 @@ def sample_ids(n, count, must, seed):
     return ids.to(DEV)
 
 
-def test_spmm_config(comet):
+@pytest.fixture(scope="module")
+def spmm_config():
     c = gen.config_spmm(seed=0, device=DEV, R=32)
     rows, cols, vals = c["coo"]
     n = c["dims"][0]
-    say("spmm full size nnz=%d" % vals.numel())
-    L = fmt.pack_csr(n, n, rows, cols, vals)
+    say("spmm full size nnz=%d: oracle over every nonzero" % vals.numel())
+    ref, absum = oracle.spmm(np_(rows), np_(cols), np_(vals), (n, n), np_(c["B"]))
+    say("  oracle done")
+    return c, ref, absum
+
+
+@pytest.mark.parametrize("layout", ["csr", "dcsr"])
+def test_spmm_config(comet, spmm_config, layout):
+    """Every element of C at the headline size, for the matrix stored [D,CU] and [CU,CU]."""
+    c, ref, absum = spmm_config
+    rows, cols, vals = c["coo"]
+    n = c["dims"][0]
+    L = (fmt.pack_csr if layout == "csr" else fmt.pack_dcsr)(n, n, rows, cols, vals)
     A = comet.from_levels(L)
-    C = comet.comet_spmm(A, c["B"])
+    C = torch.full((n, 32), float("nan"), dtype=torch.float64, device=DEV)
+    comet.comet_spmm(A, c["B"], C)
     torch.cuda.synchronize()
-    pos = L.pos[1].to(torch.int64)
-    lens = pos[1:] - pos[:-1]
-    heavy = torch.topk(lens, 4).indices.cpu()
-    ids = sample_ids(n, 3000, heavy, 1)
-    idx, which = ranges_to_index(pos[ids], pos[ids + 1])
-    ref, absum = oracle.spmm(np_(which), np_(cols[idx]), np_(vals[idx]), (ids.numel(), n), np_(c["B"]))
-    assert_values_close(np_(C[ids]), ref, absum, "spmm sampled rows")
+    assert_values_close(np_(C), ref, absum, "spmm %s, every row" % layout)
+
+
+def test_spmv_on_the_spmm_matrix(comet, spmm_config):
+    """SpMV at a size where it is not launch-bound: the headline matrix with one dense column (x is 8 MB, so
+    the gathers go through L1 / L2 rather than LDS).  Every element of y."""
+    c, _, _ = spmm_config
+    rows, cols, vals = c["coo"]
+    n = c["dims"][0]
+    x = c["B"][:, 0].contiguous()
+    A = comet.from_levels(fmt.pack_csr(n, n, rows, cols, vals))
+    y = torch.full((n,), float("nan"), dtype=torch.float64, device=DEV)
+    comet.comet_spmv(A, x, y)
+    torch.cuda.synchronize()
+    ref, absum = oracle.spmv(np_(rows), np_(cols), np_(vals), (n, n), np_(x))
+    assert_values_close(np_(y), ref, absum, "spmv on the spmm matrix, every row")
 
 
 @pytest.fixture(scope="module")
 def ttv_config():
     return gen.config_ttv(seed=0, device=DEV)
+
+
+_TTV_REF = {}
+
+
+def _ttv_reference(c):
+    """The oracle's TTV of the whole 50 M-nonzero tensor (computed once, shared by the CSF and COO cases)."""
+    if "ref" not in _TTV_REF:
+        i, j, k, vals = c["coo"]
+        say("  oracle ttv over all %d nonzeros" % vals.numel())
+        _TTV_REF["ref"] = oracle.ttv(np_(i), np_(j), np_(k), np_(vals), c["dims"], np_(c["v"]))
+        say("  oracle done")
+    return _TTV_REF["ref"]
 
 
 def _fiber_sample(L, count, seed):
@@ -89,18 +129,15 @@ def test_ttv_csf_config(comet, ttv_config):
     torch.cuda.synchronize()
     for l in range(2):                    # structure: the result's levels are the input's, bit for bit
         assert torch.equal(Y.pos(l), L.pos[l]) and torch.equal(Y.crd(l), L.crd[l])
-    fids, idx, which = _fiber_sample(L, 4000, 2)
-    # the sampled fibers have distinct (i,j) in increasing order, so the oracle's pair list is `fids`
-    ref = oracle.ttv(np_(i[idx]), np_(j[idx]), np_(k[idx]), np_(vals[idx]), c["dims"], np_(c["v"]))
-    assert len(ref["vals"]) == fids.numel()
-    assert_values_close(np_(Y.vals()[fids]), ref["vals"], ref["abs"], "ttv sampled fibers")
+    ref = _ttv_reference(c)
+    assert len(ref["vals"]) == L.crd[1].numel()
+    assert_values_close(np_(Y.vals()), ref["vals"], ref["abs"], "ttv csf, every fiber")
 
 
 def test_ttv_coo_config(comet, ttv_config):
     c = ttv_config
     i, j, k, vals = c["coo"]
     Lc = fmt.pack_coo(c["dims"], (i, j, k), vals)
-    Ls = fmt.pack_csf3(c["dims"], i, j, k, vals)
     say("ttv coo full size nnz=%d" % vals.numel())
     X = comet.from_levels(Lc)
     Y = comet.comet_ttv(X, 2, c["v"])
@@ -110,9 +147,9 @@ def test_ttv_coo_config(comet, ttv_config):
     head[1:] = (i[1:] != i[:-1]) | (j[1:] != j[:-1])
     assert torch.equal(Y.crd(0), i[head].to(torch.int32)) and torch.equal(Y.crd(1), j[head].to(torch.int32))
     assert Y.pos(0).tolist() == [0, int(head.sum())]
-    fids, idx, which = _fiber_sample(Ls, 4000, 3)
-    ref = oracle.ttv(np_(i[idx]), np_(j[idx]), np_(k[idx]), np_(vals[idx]), c["dims"], np_(c["v"]))
-    assert_values_close(np_(Y.vals()[fids]), ref["vals"], ref["abs"], "ttv coo sampled runs")
+    ref = _ttv_reference(c)
+    assert np.array_equal(np_(Y.crd(0)), ref["i"]) and np.array_equal(np_(Y.crd(1)), ref["j"])
+    assert_values_close(np_(Y.vals()), ref["vals"], ref["abs"], "ttv coo, every run")
 
 
 def test_ttm_config(comet):
@@ -126,10 +163,19 @@ def test_ttm_config(comet):
     for l in range(2):
         assert torch.equal(Y.pos(l), L.pos[l]) and torch.equal(Y.crd(l), L.crd[l])
     assert Y.pos(2).tolist() == [16] and Y.levels() == [1, 1, 0]
-    fids, idx, which = _fiber_sample(L, 3000, 4)
-    ref = oracle.ttm(np_(i[idx]), np_(j[idx]), np_(k[idx]), np_(vals[idx]), c["dims"], np_(c["U"]))
-    got = Y.vals().reshape(-1, 16)[fids]
-    assert_values_close(np_(got), ref["vals"], ref["abs"], "ttm sampled fibers")
+    say("  oracle ttm over all %d nonzeros" % vals.numel())
+    ref = oracle.ttm(np_(i), np_(j), np_(k), np_(vals), c["dims"], np_(c["U"]))
+    say("  oracle done")
+    assert ref["vals"].shape == (L.crd[1].numel(), 16)
+    assert_values_close(np_(Y.vals()).reshape(-1, 16), ref["vals"], ref["abs"], "ttm, every fiber")
+    del Y, X
+    # the same tensor as a sorted coordinate list: the result lists the distinct (i,j) and carries the same values
+    Xc = comet.from_levels(fmt.pack_coo(c["dims"], (i, j, k), vals))
+    Yc = comet.comet_ttm(Xc, 2, c["U"])
+    torch.cuda.synchronize()
+    assert Yc.levels() == [2, 3, 0] and Yc.pos(0).tolist() == [0, ref["i"].size]
+    assert np.array_equal(np_(Yc.crd(0)), ref["i"]) and np.array_equal(np_(Yc.crd(1)), ref["j"])
+    assert_values_close(np_(Yc.vals()).reshape(-1, 16), ref["vals"], ref["abs"], "ttm on a coordinate list, every fiber")
 
 
 @pytest.mark.parametrize("R", [16, 64])
@@ -143,17 +189,29 @@ def test_mttkrp_config(comet, R):
     M = torch.full((dims[0], R), float("nan"), dtype=torch.float64, device=DEV)
     comet.comet_mttkrp(X, 0, [None, c["B"], c["C"]], M)
     torch.cuda.synchronize()
-    pos2, pos3 = L.pos[1].to(torch.int64), L.pos[2].to(torch.int64)
-    first = pos3[pos2[:-1]]
-    last = pos3[pos2[1:]]
-    heavy = torch.topk(last - first, 2).indices.cpu()       # the Zipf head slices: cut over thousands of tiles
-    sids = sample_ids(first.numel(), 600, heavy, 5)
-    idx, which = ranges_to_index(first[sids], last[sids])
-    say("  oracle on %d nonzeros of %d sampled slices" % (idx.numel(), sids.numel()))
-    ref, absum = oracle.mttkrp(np_(which), np_(j[idx]), np_(k[idx]), np_(vals[idx]), (sids.numel(), dims[1], dims[2]),
-                               np_(c["B"]), np_(c["C"]))
-    rows = L.crd[0].to(torch.int64)[sids]
-    assert_values_close(np_(M[rows]), ref, absum, "mttkrp sampled slices R=%d" % R)
+    if R == 16:
+        say("  oracle mttkrp over all %d nonzeros" % vals.numel())
+        ref, absum = oracle.mttkrp(np_(i), np_(j), np_(k), np_(vals), dims, np_(c["B"]), np_(c["C"]))
+        say("  oracle done")
+        assert_values_close(np_(M), ref, absum, "mttkrp R=16, every row")
+        # the same tensor as a sorted coordinate list (works through a compressed copy inside the handle)
+        Xc = comet.from_levels(fmt.pack_coo(dims, (i, j, k), vals))
+        Mc = torch.full((dims[0], R), float("nan"), dtype=torch.float64, device=DEV)
+        comet.comet_mttkrp(Xc, 0, [None, c["B"], c["C"]], Mc)
+        torch.cuda.synchronize()
+        assert_values_close(np_(Mc), ref, absum, "mttkrp R=16 on a coordinate list, every row")
+    else:
+        pos2, pos3 = L.pos[1].to(torch.int64), L.pos[2].to(torch.int64)
+        first = pos3[pos2[:-1]]
+        last = pos3[pos2[1:]]
+        heavy = torch.topk(last - first, 2).indices.cpu()       # the Zipf head slices: cut over thousands of tiles
+        sids = sample_ids(first.numel(), 600, heavy, 5)
+        idx, which = ranges_to_index(first[sids], last[sids])
+        say("  oracle on %d nonzeros of %d sampled slices" % (idx.numel(), sids.numel()))
+        ref, absum = oracle.mttkrp(np_(which), np_(j[idx]), np_(k[idx]), np_(vals[idx]), (sids.numel(), dims[1], dims[2]),
+                                   np_(c["B"]), np_(c["C"]))
+        rows = L.crd[0].to(torch.int64)[sids]
+        assert_values_close(np_(M[rows]), ref, absum, "mttkrp sampled slices R=%d" % R)
     # rows whose index is not stored at the root level receive nothing
     stored = torch.zeros(dims[0], dtype=torch.bool, device=DEV)
     stored[L.crd[0].to(torch.int64)] = True
@@ -169,6 +227,38 @@ def _expand_csf(T):
     c1 = T.crd(1).to(torch.int64)[fib_of_nnz]
     c0 = T.crd(0).to(torch.int64)[slice_of_fib][fib_of_nnz]
     return c0, c1, T.crd(2).to(torch.int64), fib_of_nnz
+
+
+def _sorted_original(coords, vals, dims, order):
+    """The generator's nonzeros sorted by the level order `order` (a torch sort of the packed key): the
+    per-level coordinate arrays, the values, the order itself, and the packed keys.  Nothing here comes
+    from the library."""
+    a, b, c = (coords[m].to(torch.int64) for m in order)
+    key = (a * dims[order[1]] + b) * dims[order[2]] + c
+    skey, perm = torch.sort(key)
+    assert bool((skey[1:] > skey[:-1]).all())
+    return (a[perm], b[perm], c[perm]), vals[perm], perm, skey
+
+
+def _assert_restored(Xr, ref_levels, ref_vals, skey, dims, order):
+    """Every coordinate and value of the re-stored handle against the sorted original, plus its structure:
+    fibers and slices start exactly where the sorted original changes its (root, middle) / root prefix."""
+    c0, c1, c2, _ = _expand_csf(Xr)
+    assert torch.equal((c0 * dims[order[1]] + c1) * dims[order[2]] + c2, skey)
+    assert torch.equal(Xr.vals(), ref_vals)
+    fkey = skey // dims[order[2]]
+    fhead = torch.ones_like(fkey, dtype=torch.bool)
+    fhead[1:] = fkey[1:] != fkey[:-1]
+    fstart = torch.nonzero(fhead).flatten()
+    pos3 = Xr.pos(2).to(torch.int64)
+    assert pos3.numel() == fstart.numel() + 1 and torch.equal(pos3[:-1], fstart) and int(pos3[-1]) == skey.numel()
+    skey2 = fkey[fstart] // dims[order[1]]
+    shead = torch.ones_like(skey2, dtype=torch.bool)
+    shead[1:] = skey2[1:] != skey2[:-1]
+    sstart = torch.nonzero(shead).flatten()
+    pos2 = Xr.pos(1).to(torch.int64)
+    assert pos2.numel() == sstart.numel() + 1 and torch.equal(pos2[:-1], sstart) and int(pos2[-1]) == fstart.numel()
+    return fstart, sstart
 
 
 def test_first_mode_ttv_config(comet, ttv_config):
@@ -222,13 +312,17 @@ def test_first_mode_ttm_config(comet):
     Y = comet.comet_ttm(Xr, 0, U)
     torch.cuda.synchronize()
     assert Y.levels() == [1, 1, 0] and Y.dims() == [dims[1], dims[2], 16] and Y.mode_of_level()[:2] == [1, 2]
-    c0, c1, c2, _ = _expand_csf(Xr)
-    pos3 = Xr.pos(2).to(torch.int64)
-    lens = pos3[1:] - pos3[:-1]
-    heavy = torch.topk(lens, 4).indices.cpu()
-    fids = sample_ids(lens.numel(), 3000, heavy, 7)
-    idx, which = ranges_to_index(pos3[fids], pos3[fids + 1])
-    ref = oracle.ttm_mode((np_(c2[idx]), np_(c0[idx]), np_(c1[idx])), np_(Xr.vals()[idx]), dims, 0, np_(U))
+    # the re-stored tensor as a whole against a sort of the generator's own coordinates ...
+    order = (1, 2, 0)
+    lv, svals, perm, skey = _sorted_original((i, j, k), vals, dims, order)
+    fstart, _ = _assert_restored(Xr, lv, svals, skey, dims, order)
+    # ... and the oracle on the ORIGINAL nonzeros of sampled output fibers (positions in the sorted original)
+    fend = torch.cat([fstart[1:], torch.tensor([skey.numel()], device=DEV)])
+    heavy = torch.topk(fend - fstart, 4).indices.cpu()
+    fids = sample_ids(fstart.numel(), 3000, heavy, 7)
+    idx, which = ranges_to_index(fstart[fids], fend[fids])
+    src = perm[idx]
+    ref = oracle.ttm_mode((np_(i[src]), np_(j[src]), np_(k[src])), np_(vals[src]), dims, 0, np_(U))
     assert len(ref["vals"]) == fids.numel()
     assert_values_close(np_(Y.vals().reshape(-1, 16)[fids]), ref["vals"], ref["abs"], "first-mode ttm sampled fibers")
 
@@ -248,19 +342,26 @@ def test_second_mode_mttkrp_config(comet):
     M = torch.full((dims[1], R), float("nan"), dtype=torch.float64, device=DEV)
     comet.comet_mttkrp(Xr, 1, [F[0], None, F[2]], M)
     torch.cuda.synchronize()
-    pos2, pos3 = Xr.pos(1).to(torch.int64), Xr.pos(2).to(torch.int64)
-    first, last = pos3[pos2[:-1]], pos3[pos2[1:]]
+    # the re-stored tensor as a whole against a sort of the generator's own coordinates ...
+    order = (1, 0, 2)
+    lv, svals, perm, skey = _sorted_original((i, j, k), vals, dims, order)
+    fstart, sstart = _assert_restored(Xr, lv, svals, skey, dims, order)
+    del skey, svals
+    # ... and the oracle on the ORIGINAL nonzeros of sampled output rows (slices of the sorted original)
+    first = fstart[sstart]
+    last = torch.cat([first[1:], torch.tensor([vals.numel()], device=DEV)])
     heavy = torch.topk(last - first, 2).indices.cpu()
     sids = sample_ids(first.numel(), 500, heavy, 8)
     idx, which = ranges_to_index(first[sids], last[sids])
     say("second-mode mttkrp full size: oracle on %d nonzeros of %d sampled slices" % (idx.numel(), sids.numel()))
-    c0, c1, c2, _ = _expand_csf(Xr)            # level coordinates: (mode 1, mode 0, mode 2)
-    ref, absum = oracle.mttkrp(np_(which), np_(c1[idx]), np_(c2[idx]), np_(Xr.vals()[idx]),
-                               (sids.numel(), dims[0], dims[2]), np_(F[0]), np_(F[2]))
-    rows = Xr.crd(0).to(torch.int64)[sids]
+    src = perm[idx]
+    rows = j[src[torch.searchsorted(which, torch.arange(sids.numel(), device=DEV))]].to(torch.int64)   # mode-1 index of each sampled slice
+    # a private numbering of the sampled rows keeps the oracle's output small: row `which` stands for j = rows[which]
+    ref, absum = oracle.mttkrp_mode((np_(i[src]), np_(which), np_(k[src])), np_(vals[src]),
+                                    (dims[0], sids.numel(), dims[2]), 1, [np_(F[0]), None, np_(F[2])])
     assert_values_close(np_(M[rows]), ref, absum, "second-mode mttkrp sampled slices")
     stored = torch.zeros(dims[1], dtype=torch.bool, device=DEV)
-    stored[Xr.crd(0).to(torch.int64)] = True
+    stored[torch.unique(j)] = True
     assert bool((M[~stored] == 0.0).all()) and not bool(torch.isnan(M).any())
 
 

@@ -15,7 +15,8 @@ from util import assert_index_equal, assert_values_close, np_
 
 pytestmark = pytest.mark.gpu
 
-VARIANTS = [1, 2, 0]       # 1 = simple kernels, 2 = tiled wherever specialised, 0 = the library's own choice
+# 1 = simple kernels, 2 = tiled with every specialisation, 3 = tiled in the plain per-tile form, 0 = the library's own choice
+VARIANTS = [1, 2, 3, 0]
 
 
 @pytest.fixture(scope="module")

@@ -193,6 +193,37 @@ def test_hand_example_level_walk():
     assert np.all(seen == 1)
 
 
+def test_hand_example_compressed_levels():
+    """The hand-written [CU,CU,CU] arrays of the example pin both the oracle's expected-structure helper and
+    the packer that feeds the GPU tests, array by array."""
+    t = json.load(open(GOLD))["tensor"]
+    c, want = t["coo"], t["csf"]
+    # expected structure of a sparse result over the distinct (i, j) pairs = levels 1 and 2 of the example
+    lv = oracle.compressed_pair_levels(np.array(t["ttv"]["i"]), np.array(t["ttv"]["j"]))
+    assert lv["pos1"].tolist() == want["pos"][0] and lv["crd1"].tolist() == want["crd"][0]
+    assert lv["pos2"].tolist() == want["pos"][1] and lv["crd2"].tolist() == want["crd"][1]
+    assert all(lv[k].dtype == np.int32 for k in lv)
+    L = fmt.pack_csf3(t["shape"], torch.tensor(c["i"]), torch.tensor(c["j"]), torch.tensor(c["k"]),
+                          torch.tensor(c["vals"], dtype=torch.float64))
+    assert list(L.tags) == [1, 1, 1]
+    for l in range(3):
+        assert L.pos[l].tolist() == want["pos"][l], "pos of level %d" % l
+        assert L.crd[l].tolist() == want["crd"][l], "crd of level %d" % l
+        assert L.pos[l].dtype == torch.int32 and L.crd[l].dtype == torch.int32
+    assert L.vals.tolist() == c["vals"]
+    m = json.load(open(GOLD))["matrix"]
+    mc = m["coo"]
+    args = (m["shape"][0], m["shape"][1], torch.tensor(mc["rows"]), torch.tensor(mc["cols"]), torch.tensor(mc["vals"], dtype=torch.float64))
+    for pack, name in ((fmt.pack_csr, "csr"), (fmt.pack_dcsr, "dcsr")):
+        P = pack(*args)
+        for l in range(2):
+            assert (None if P.pos[l] is None else P.pos[l].tolist()) == m[name]["pos"][l], name
+            assert (None if P.crd[l] is None else P.crd[l].tolist()) == m[name]["crd"][l], name
+    # a planted mistake: the pair list with its columns swapped must not give the example's arrays
+    bad = oracle.compressed_pair_levels(np.array(t["ttv"]["j"]), np.array(t["ttv"]["i"]))
+    assert bad["crd1"].tolist() != want["crd"][0] or bad["pos2"].tolist() != want["pos"][1]
+
+
 def test_compressed_unique_stores_a_shared_row_coordinate_once():
     """Section 4, CU: two nonzeros of one row share a single stored row coordinate;
     CN: pos holds only the start and the extent of crd; S: one coordinate per parent position."""
