@@ -179,6 +179,22 @@ comet_status comet_tensor_convert(const comet_tensor *X, const int32_t *mode_ord
  *                                       (rows without stored nonzeros become 0). */
 comet_status comet_spmv(const comet_tensor *A, const double *x, double *y, void *stream);
 
+/* SpMV for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same result as comet_spmv (the same kernels run), but the
+ * kernels' carry scratch is a static device array of COMET_STATIC_SCRATCH_BYTES inside the library
+ * (one copy per GPU, held until the process ends) instead of memory owned by the handle, and the call
+ * makes no hipMalloc / hipFree or other allocating call.
+ *   A   order-2 handle, [D,CU] or [CU,CU]; a coordinate list gives COMET_ERR_UNSUPPORTED (its compressed
+ *       copy would have to be allocated).
+ *   The kernels need about 24.4 bytes of scratch per 1024 nonzeros, so the array covers matrices of up
+ *   to about 88 M nonzeros; a larger one gives COMET_ERR_UNSUPPORTED and nothing is enqueued.
+ *   All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ *   streams, different threads) race -- serialise them.  Nothing in the array has to be cleared between
+ *   calls (every entry that is read was written by the same call).  The first call on each device looks
+ *   up the array's address, which is not a stream operation: make one call before starting a capture. */
+#define COMET_STATIC_SCRATCH_BYTES (2u << 20)
+comet_status comet_spmv_static(const comet_tensor *A, const double *x, double *y, void *stream);
+
 /* SpMM, C = A B :  c_ir = sum_j a_ij b_jr   (Section 8.2, SpMM; the paper's example program).
  *   A   order-2 handle, [D,CU], [CU,CU] or (through a compressed copy) [CN,S].
  *   B   device, [dims[1] x R] row-major.   C   device, [dims[0] x R] row-major, overwritten.

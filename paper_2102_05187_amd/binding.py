@@ -27,7 +27,7 @@ _STATUS_NAMES = {0: "COMET_OK", 1: "COMET_ERR_INVALID_ARG", 2: "COMET_ERR_BAD_FO
 
 EXPORTS = ["comet_tensor_create", "comet_tensor_destroy", "comet_tensor_info", "comet_spmv", "comet_spmm",
            "comet_ttv", "comet_ttm", "comet_mttkrp", "comet_status_string", "comet_tensor_set_variant",
-           "comet_tensor_reorder", "comet_tensor_convert", "comet_tensor_reserve"]
+           "comet_tensor_reorder", "comet_tensor_convert", "comet_tensor_reserve", "comet_spmv_static"]
 
 
 class CometError(RuntimeError):
@@ -65,6 +65,7 @@ def _lib():
         lib.comet_tensor_destroy.argtypes = [vp]
         lib.comet_tensor_info.argtypes = [vp, ctypes.POINTER(_Info)]
         lib.comet_spmv.argtypes = [vp, vp, vp, vp]
+        lib.comet_spmv_static.argtypes = [vp, vp, vp, vp]
         lib.comet_tensor_reserve.argtypes = [vp, i64, vp]
         lib.comet_spmm.argtypes = [vp, vp, i64, vp, vp]
         lib.comet_ttv.argtypes = [vp, ci, vp, ctypes.POINTER(vp), vp]
@@ -258,6 +259,18 @@ def comet_spmv(A: Tensor, x: torch.Tensor, y: Optional[torch.Tensor] = None, str
     if y.numel() != I:
         raise CometError(3, "comet_spmv")
     _check(_lib().comet_spmv(A.handle, x.data_ptr(), y.data_ptr(), _stream(stream)), "comet_spmv")
+    return y
+
+
+def comet_spmv_static(A: Tensor, x: torch.Tensor, y: torch.Tensor, stream=None) -> torch.Tensor:
+    """comet_spmv for callers that cannot allocate: the caller passes y, the library's scratch is static."""
+    x, y = _dev(x, torch.float64, "x"), _dev(y, torch.float64, "y")
+    if len(A.dims()) != 2:
+        raise CometError(4, "comet_spmv_static")
+    I, J = A.dims()
+    if x.numel() != J or y.numel() != I:
+        raise CometError(3, "comet_spmv_static")
+    _check(_lib().comet_spmv_static(A.handle, x.data_ptr(), y.data_ptr(), _stream(stream)), "comet_spmv_static")
     return y
 
 

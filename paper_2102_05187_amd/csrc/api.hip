@@ -2,6 +2,7 @@
 // schedule building, and dispatch of the five contractions to the HIP kernels.
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "kernels.hpp"
@@ -711,6 +712,38 @@ comet_status comet_spmv(const comet_tensor *A, const double *x, double *y, void 
 
 comet_status comet_spmm(const comet_tensor *A, const double *B, int64_t R, double *C, void *stream) {
     return matrix_product(A, B, R, C, (hipStream_t)stream);
+}
+
+// ---- SpMV for callers that cannot allocate --------------------------------------------------------
+// The carry scratch of the tiled kernels lives in this array instead of in memory owned by the handle.
+// Every GPU the library runs on holds its own copy at its own address: host code must go through the
+// address that hipGetSymbolAddress returns for the current device, never through the array's name.
+static __device__ __align__(256) unsigned char g_static_scratch[COMET_STATIC_SCRATCH_BYTES];
+
+static void *static_scratch_of_current_device(hipError_t *err) {
+    static std::mutex mu;
+    static void *ptrs[64] = {};
+    int dev = -1;
+    *err = hipGetDevice(&dev);
+    if (*err != hipSuccess) return nullptr;
+    if (dev < 0 || dev >= 64) { *err = hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void *p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_scratch));
+        if (*err != hipSuccess) return nullptr;
+        ptrs[dev] = p;
+    }
+    return ptrs[dev];
+}
+
+comet_status comet_spmv_static(const comet_tensor *A, const double *x, double *y, void *stream) {
+    if (!A || !x || !y) return COMET_ERR_INVALID_ARG;
+    if (A->fmt != Format::CSR && A->fmt != Format::DCSR) return COMET_ERR_UNSUPPORTED;
+    hipError_t e = hipSuccess;
+    void *scr = static_scratch_of_current_device(&e);
+    if (!scr) { (void)hipGetLastError(); return COMET_ERR_DEVICE; }
+    return matrix_product(A, x, 1, y, (hipStream_t)stream, scr, (size_t)COMET_STATIC_SCRATCH_BYTES);
 }
 
 // ---- TTV / TTM along the mode stored in the last level ------------------------------------------
