@@ -79,6 +79,8 @@ typedef struct {
     int32_t        mode_of_level[COMET_MAX_ORDER];  /* tensor mode stored at each level: 0,1,2,..
                                                  * unless comet_tensor_reorder chose another order;
                                                  * dims / levels / pos / crd above are per LEVEL    */
+    int64_t        heavy_rows;                /* schedule: rows that comet_spmm hands to its heavy-row sweep */
+    int64_t        heavy_nnz;                 /* ... and the nonzeros they hold (both 0: no sweep planned)   */
 } comet_tensor_info_t;
 
 /*

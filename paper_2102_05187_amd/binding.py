@@ -47,7 +47,9 @@ class _Info(ctypes.Structure):
                 ("crd_len", ctypes.c_int64 * COMET_MAX_ORDER),
                 ("vals", ctypes.c_void_p),
                 ("nvals", ctypes.c_int64),
-                ("mode_of_level", ctypes.c_int32 * COMET_MAX_ORDER)]
+                ("mode_of_level", ctypes.c_int32 * COMET_MAX_ORDER),
+                ("heavy_rows", ctypes.c_int64),
+                ("heavy_nnz", ctypes.c_int64)]
 
 
 _LIB = None
@@ -153,6 +155,11 @@ class Tensor:
     def mode_of_level(self) -> List[int]:
         inf = self.info()
         return [int(inf.mode_of_level[l]) for l in range(inf.order)]
+
+    def heavy_plan(self):
+        """(rows, nonzeros) that comet_spmm hands to its heavy-row sweep; (0, 0) when none is planned."""
+        inf = self.info()
+        return int(inf.heavy_rows), int(inf.heavy_nnz)
 
     def mode_dims(self) -> List[int]:
         """Sizes indexed by tensor mode (dims() is indexed by level)."""

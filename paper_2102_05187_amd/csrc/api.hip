@@ -97,6 +97,8 @@ comet_status build_schedule(comet_tensor &t, hipStream_t st) {
             if (rs != COMET_OK) return rs;
             sc.max_root_gap = h;
         }
+        if (t.fmt == Format::CSR || t.fmt == Format::DCSR)
+            HIP_TRY(comet::heavy_plan_build(t.pos_i(1), sc.nseg, t.crd_i(1), sc.nnz, t.dims[1], sc.heavy, st));
         if (t.fmt == Format::CSF3) {
             HIP_TRY(hipMemsetAsync(mx->ptr, 0, sizeof(int32_t), st));
             HIP_TRY(comet::max_parent_span(t.pos_i(1), t.pos_len[1] - 1, t.pos_i(2), (int32_t *)mx->ptr, st));
@@ -377,7 +379,8 @@ static size_t scratch_need(const comet_tensor *t, int64_t R) {
     size_t need = 0;
     if (t->sched.nchunks > 0) need = comet::stream_scratch_bytes(t->sched.nchunks, 1);
     if (t->sched.ntiles > 0 && comet::stream_supports_rank(R)) {
-        const size_t b = comet::stream_scratch_bytes(t->sched.ntiles, R);
+        size_t b = comet::stream_scratch_bytes(t->sched.ntiles, R);
+        if (t->sched.heavy.nunits > 0) b += comet::heavy_partial_bytes(t->sched.heavy, R > 64 ? 64 : R);
         if (b > need) need = b;
     }
     return need;
@@ -415,6 +418,8 @@ comet_status comet_tensor_info(const comet_tensor *t, comet_tensor_info_t *info)
     }
     info->vals = t->nvals ? t->vals_d() : nullptr;
     info->nvals = t->nvals;
+    info->heavy_rows = t->sched.heavy.nunits > 0 ? t->sched.heavy.nheavy : 0;
+    info->heavy_nnz = t->sched.heavy.nunits > 0 ? t->sched.heavy.heavy_nnz : 0;
     return COMET_OK;
 }
 
@@ -675,7 +680,12 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
     if (R < 1 || R > 1024) return COMET_ERR_UNSUPPORTED;
     const int64_t nseg = A->pos_len[1] - 1, nnz = A->nvals;
     const bool tiled = nnz > 0 && use_tiled(A, R, Dn, out, A->dims[1], A->sched.max_seg_len);
-    const size_t need = tiled ? comet::stream_scratch_bytes(R == 1 ? A->sched.nchunks : A->sched.ntiles, R) : 0;
+    const size_t carry = tiled ? comet::stream_scratch_bytes(R == 1 ? A->sched.nchunks : A->sched.ntiles, R) : 0;
+    // The heavy-row sweep pays when the dense operand is much larger than the L2 caches (else its rows are
+    // cache hits anyway) and the long rows hold a good share of the nonzeros (decided when the plan was built).
+    const bool heavy = tiled && !ext_scratch && A->variant != 3 && A->sched.heavy.nunits > 0 &&
+                       A->dims[1] * R * 8 >= (int64_t(16) << 20) && R <= 64 && comet::heavy_supports(A->sched.heavy, R);
+    const size_t need = carry + (heavy ? comet::heavy_partial_bytes(A->sched.heavy, R) : 0);
     if (ext_scratch && need > ext_bytes) return COMET_ERR_UNSUPPORTED;       // before anything is enqueued
     const int32_t *rowmap = nullptr;
     if (A->fmt == Format::DCSR) {
@@ -699,7 +709,9 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
             scr = A->scratch->ptr;
         }
         HIP_TRY(comet::stream_segreduce(A->sched, A->pos_i(1), A->crd_i(1), A->vals_d(), rowmap, Dn, A->dims[1], R, out,
-                                        scr, A->variant == 3, st));
+                                        scr, A->variant == 3, st, heavy ? A->sched.heavy.min_len : 0));
+        if (heavy)
+            HIP_TRY(comet::heavy_spmm(A->sched.heavy, A->crd_i(1), A->vals_d(), rowmap, Dn, R, out, (char *)scr + carry, st));
         return COMET_OK;
     }
     HIP_TRY(comet::simple_segreduce(A->pos_i(1), A->crd_i(1), A->vals_d(), nseg, nnz, rowmap, Dn, R, out, st));

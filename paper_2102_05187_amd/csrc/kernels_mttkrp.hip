@@ -5,24 +5,6 @@ namespace comet {
 
 namespace {
 
-// Cross-lane broadcast inside a lane group (quad_perm inside a quad, plus one row_shr:4 / row_shl:4 with a
-// bank mask to cross the two quads of an 8-lane group); used by the MTTKRP walk, whose LDS budget goes
-// to its two tail maps.
-template <int L, int BP>
-__device__ __forceinline__ int grp_bcast_i(int v) {
-    static_assert(L == 4 || L == 8, "lane groups of 4 or 8");
-    // quad_perm broadcast; every lane is written, and bound_ctrl with full masks tells the compiler so
-    // (no move of the unused old value in front of it)
-    const int x1 = __builtin_amdgcn_update_dpp(0, v, (BP % 4) * 0x55, 0xf, 0xf, true);
-    if constexpr (L == 4) return x1;
-    else if constexpr (BP < 4) return __builtin_amdgcn_update_dpp(x1, x1, 0x114, 0xf, 0xa, false);   // row_shr:4 into the odd quads
-    else return __builtin_amdgcn_update_dpp(x1, x1, 0x104, 0xf, 0x5, false);                          // row_shl:4 into the even quads
-}
-template <int L, int BP>
-__device__ __forceinline__ double grp_bcast_d(double v) {
-    return __hiloint2double(grp_bcast_i<L, BP>(__double2hiint(v)), grp_bcast_i<L, BP>(__double2loint(v)));
-}
-
 // ---- MTTKRP: the same walk, two nested segment levels ---------------------------------------------
 // Inner level: fibers (segments of pos3); the per-fiber sum of vals * C[crd3, :] is scaled by the row
 // B[crd2[fiber], :] when the fiber ends and folded into the slice accumulator.  Scaling is linear,

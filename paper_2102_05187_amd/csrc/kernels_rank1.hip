@@ -567,9 +567,10 @@ size_t stream_scratch_bytes(int64_t ntiles, int64_t R) {
 
 hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                             const int32_t *rowmap, const double *Dn, int64_t dense_rows, int64_t R, double *out,
-                            void *scratch, bool plain, hipStream_t st) {
+                            void *scratch, bool plain, hipStream_t st, int32_t heavy_len) {
     if (sc.ntiles <= 0) return hipSuccess;
     if (!stream_supports_rank(R)) return hipErrorNotSupported;
+    if (heavy_len > 0 && (R == 1 || heavy_len < 256)) return hipErrorNotSupported;
     const int32_t *sb = (const int32_t *)sc.seg_begin->ptr;
     hipError_t e = hipSuccess;
     if (R == 1) {
@@ -605,7 +606,7 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
                                rowmap, Dn, out, sc.nnz, sc.ntiles, scratch);
         e = hipGetLastError();
     } else {
-        e = stream_segreduce_rankR(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st);
+        e = stream_segreduce_rankR(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st, heavy_len);
     }
     if (e != hipSuccess) return e;
     return run_fixup(scratch, sc.ntiles, (int)R, rowmap, out, sc.max_seg_len / kTile + 2, st);

@@ -24,14 +24,29 @@ size_t stream_scratch_bytes(int64_t ntiles, int64_t R);
 // Every segment of the level is written (empty ones with zeros).  dense_rows = number of rows of Dn.
 // plain = true keeps rank-1 work on the per-tile kernel that gathers the vector through L1 (measurement
 // baseline) instead of the kernel that stages it in LDS.
+// heavy_len > 0 (rank > 1 only): segments of at least that many nonzeros are left out altogether -- their
+// nonzeros are skipped and their rows are not written; the heavy-row sweep produces them.
 hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                             const int32_t *rowmap, const double *Dn, int64_t dense_rows, int64_t R, double *out,
-                            void *scratch, bool plain, hipStream_t st);
+                            void *scratch, bool plain, hipStream_t st, int32_t heavy_len = 0);
 
 // Sorted COO [CN,S,S]: one output (i, j, value) per run of equal (c0, c1).
 hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *c1, const int32_t *c2,
                           const double *vals, const double *v, int64_t dense_rows, int32_t *y0, int32_t *y1, double *yv,
                           void *scratch, bool plain, hipStream_t st);
+
+// ---- heavy-row sweep of SpMM (kernels_heavy.hip) ---------------------------------------------------
+// Builds the plan for a [*,CU] matrix level (pos over nseg segments, crd with coordinates < ncols); leaves
+// plan.nunits = 0 when the rows of >= min_len nonzeros hold too small a share to matter.  Synchronises.
+hipError_t heavy_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd, int64_t nnz, int64_t ncols,
+                            HeavyPlan &plan, hipStream_t st);
+// The sweep exists for ranks 16, 32, 48 and 64 and for as many units as can be resident at once.
+bool   heavy_supports(const HeavyPlan &plan, int64_t R);
+size_t heavy_partial_bytes(const HeavyPlan &plan, int64_t R);
+// out[row(h), :] = sum over heavy row h of vals * Dn[crd, :] for every heavy row (row(h) = rowmap ?
+// rowmap[seg] : seg); `partial` holds heavy_partial_bytes(plan, R).
+hipError_t heavy_spmm(const HeavyPlan &plan, const int32_t *crd, const double *vals, const int32_t *rowmap,
+                      const double *Dn, int64_t R, double *out, void *partial, hipStream_t st);
 
 // Number of compute units of the current device (cached per device).
 int current_device_cu_count();

@@ -45,6 +45,20 @@ constexpr int kTile = 4096;
 // Items per chunk of the wavefront-per-chunk kernel (one wavefront's share of a tile).
 constexpr int kChunk = 1024;
 
+// Plan of the heavy-row sweep of SpMM (kernels_heavy.hip), built once at creation for matrices whose long
+// rows hold a large share of the nonzeros.  Rows of at least `min_len` nonzeros are "heavy"; each is cut
+// into units of roughly equal length (a unit takes the q-th of nsplit equal pieces of the row's nonzeros
+// inside every column window), and wstart[h][w] is the position of heavy row h's first nonzero whose
+// column is >= w * window (wstart[h][nwin] = the row's end).
+struct HeavyPlan {
+    int64_t nheavy = 0, nunits = 0, heavy_nnz = 0;
+    int32_t min_len = 0, window = 0, nwin = 0;
+    DevRef  units;        // int4 [nunits], longest unit first: {heavy row h, piece q, pieces of the row, row-major unit number}
+    DevRef  unit_begin;   // int32 [nheavy + 1]: units of heavy row h
+    DevRef  hseg;         // int32 [nheavy]: segment (row position) of heavy row h, longest rows first
+    DevRef  wstart;       // int32 [nheavy][nwin + 1]
+};
+
 // Per-tensor schedule for the nonzero-tiled kernels, built once at creation.
 //   The leaf level's nonzeros are cut into tiles of kTile consecutive positions; seg_begin[t] is
 //   the segment (row / fiber) that contains the first nonzero of tile t (seg_begin[0] = 0 and
@@ -64,6 +78,7 @@ struct Schedule {
     int64_t max_seg_len = 0;      // longest leaf segment, in nonzeros (0 = unknown)
     int64_t max_parent_len = 0;   // CSF3: most nonzeros under one slice (0 = unknown)
     int64_t max_root_gap = -1;    // compressed root level: longest run of absent root coordinates (-1 = unknown)
+    HeavyPlan heavy;              // matrices only; nunits = 0 when the sweep does not apply
 };
 
 }  // namespace comet

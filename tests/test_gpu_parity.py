@@ -104,6 +104,43 @@ def test_spmm(comet, name, layout, R, variant):
     assert_values_close(np_(C), ref, absum, "spmm %s R=%d" % (name, R))
 
 
+def _heavy_row_matrix():
+    """1.3 M nonzeros in 300 000 columns; rows of 255 / 256 / 257 nonzeros around the heavy-row threshold, long
+    rows first, last and next to each other, rows longer than a tile and than a unit, empty and short rows."""
+    J = 300_000
+    block = [5000, 0, 256, 255, 257, 1, 4096, 3, 8192, 8193, 300, 0, 0, 2, 20000, 511, 512, 7, 2047, 2049]
+    lens = torch.tensor([9000] + block * 20 + [256, 1, 6000], dtype=torch.int64)
+    return (lens.numel(), J), gen.matrix_from_row_lengths(lens.numel(), J, lens, 21)
+
+
+@pytest.mark.parametrize("variant", [2, 0, 3])
+@pytest.mark.parametrize("R", [16, 32, 48, 64, 24])
+@pytest.mark.parametrize("name,layout", [("heavy_rows", "csr"), ("heavy_rows", "dcsr"), ("zipf_large", "csr")])
+def test_spmm_with_heavy_rows(comet, name, layout, R, variant):
+    """Matrices for which SpMM hands the long rows to the heavy-row sweep and leaves them out of the tiled
+    kernel (ranks 16, 32, 48, 64; rank 24 and variant 3 stay on the tiled kernel alone).  Every element."""
+    if name == "heavy_rows":
+        (I, J), (rows, cols, vals) = _heavy_row_matrix()
+    else:
+        c = gen.config_spmm(seed=2, scale=0.2)
+        (I, J), (rows, cols, vals) = c["dims"], c["coo"]
+    say("spmm heavy case=%s layout=%s R=%d variant=%d nnz=%d" % (name, layout, R, variant, vals.numel()))
+    pack = fmt.pack_csr if layout == "csr" else fmt.pack_dcsr
+    A = comet.from_levels(pack(I, J, rows, cols, vals).to("cuda")).set_variant(variant)
+    hrows, hnnz = A.heavy_plan()
+    lens = torch.bincount(rows, minlength=I)
+    assert hrows == int((lens >= 256).sum()) and hnnz == int(lens[lens >= 256].sum()) and hrows > 0
+    B = gen.dense_operand(2, 0, (J, R))
+    C = torch.full((I, R), float("nan"), dtype=torch.float64, device="cuda")
+    comet.comet_spmm(A, dev(B), C)
+    C2 = torch.full((I, R), float("nan"), dtype=torch.float64, device="cuda")
+    comet.comet_spmm(A, dev(B), C2)
+    torch.cuda.synchronize()
+    ref, absum = oracle.spmm(np_(rows), np_(cols), np_(vals), (I, J), np_(B))
+    assert_values_close(np_(C), ref, absum, "spmm %s R=%d" % (name, R))
+    assert torch.equal(C, C2), "two runs differ"
+
+
 @pytest.mark.parametrize("R", [1, 16])
 @pytest.mark.parametrize("name", ["zipf_rows", "edge_lengths", "hypersparse", "empty", "single"])
 def test_products_of_a_coordinate_list_matrix(comet, name, R):
