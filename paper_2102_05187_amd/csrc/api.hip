@@ -98,7 +98,7 @@ comet_status build_schedule(comet_tensor &t, hipStream_t st) {
             sc.max_root_gap = h;
         }
         if (t.fmt == Format::CSR || t.fmt == Format::DCSR)
-            HIP_TRY(comet::heavy_plan_build(t.pos_i(1), sc.nseg, t.crd_i(1), sc.nnz, t.dims[1], sc.heavy, st));
+            HIP_TRY(comet::heavy_plan_build(t.pos_i(1), sc.nseg, t.crd_i(1), t.vals_d(), sc.nnz, t.dims[1], sc.heavy, st));
         if (t.fmt == Format::CSF3) {
             HIP_TRY(hipMemsetAsync(mx->ptr, 0, sizeof(int32_t), st));
             HIP_TRY(comet::max_parent_span(t.pos_i(1), t.pos_len[1] - 1, t.pos_i(2), (int32_t *)mx->ptr, st));
@@ -711,7 +711,7 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
         HIP_TRY(comet::stream_segreduce(A->sched, A->pos_i(1), A->crd_i(1), A->vals_d(), rowmap, Dn, A->dims[1], R, out,
                                         scr, A->variant == 3, st, heavy ? A->sched.heavy.min_len : 0));
         if (heavy)
-            HIP_TRY(comet::heavy_spmm(A->sched.heavy, A->crd_i(1), A->vals_d(), rowmap, Dn, R, out, (char *)scr + carry, st));
+            HIP_TRY(comet::heavy_spmm(A->sched.heavy, rowmap, Dn, R, out, (char *)scr + carry, st));
         return COMET_OK;
     }
     HIP_TRY(comet::simple_segreduce(A->pos_i(1), A->crd_i(1), A->vals_d(), nseg, nnz, rowmap, Dn, R, out, st));

@@ -6,20 +6,24 @@
 // the nonzeros (the paper's load-imbalance discussion, Section 8.3, is about exactly these rows), and all of
 // them touch the same columns.  So the columns are cut into windows of kWindow (a window's rows of B fit
 // the 4 MB L2 of one XCD several times over), the windows are dealt to the eight XCDs in contiguous ranges,
-// and on each XCD every heavy row is walked window by window by lane groups that all advance at the same
-// pace: a row of B is fetched from memory once per sweep and then hit in L2 by every other heavy row that
-// has a nonzero in that column.  Workgroups are placed on the XCDs round-robin, so workgroup b sweeps the
-// window range of XCD b mod 8; were the placement different only the cache reuse would suffer.
+// and on each XCD all heavy rows are walked window by window at the same pace: a row of B is fetched from
+// memory once per sweep and then hit in L2 by every other heavy row with a nonzero in that column.
+// Workgroups are placed on the XCDs round-robin, so workgroup b sweeps the window range of XCD b mod 8 (were
+// the placement different only the cache reuse would suffer).
 //
 // A heavy row is cut into units of comparable length (a unit takes the q-th of nsplit equal pieces of the
-// row's nonzeros inside every window), every lane group owns up to RPG units and keeps their sums in
-// registers for the whole sweep, and units are dealt to the lane groups longest rows first, so all groups
-// carry about the same number of nonzeros per window, and the grid fills every compute unit with the same
-// number of workgroups, so that none runs ahead for having a compute unit more to itself -- that, not a
-// barrier, is what keeps the sweeps in step.  (A window clock in memory that every wavefront counts into and
-// waits on was tried: same-address atomics across the device cost more than the drift they remove.)
-// Each (unit, XCD) pair yields one partial row; a second kernel adds the partial rows of a heavy row in a
-// fixed order (no atomics: results are reproducible run to run).
+// row's nonzeros inside every window); every lane group (8 lanes) owns a few units, dealt longest first and
+// back and forth so that all groups carry about the same number of nonzeros, and keeps their running sums
+// in LDS.  What a group has to do is then a fixed sequence: window by window, unit by unit, nonzero by
+// nonzero.  That sequence is laid out once, when the tensor is created, as a stream per wavefront: the 8
+// groups of a wavefront advance in lockstep, so every window is padded for each group to the longest of the
+// 8 (padding items are skipped without a gather), and a wavefront reads its stream with fully coalesced
+// 16-byte loads, 32 positions x 8 groups at a time.  At run time a group is a plain walker over its stream --
+// rows of B gathered a few positions ahead of the multiply-adds, a sum flushed into LDS where a unit's piece
+// ends -- and the 16 wavefronts of a compute unit meet at a barrier where a window ends (no data is
+// exchanged there; it only keeps them on the same rows of B).  Each (unit, XCD) pair yields one partial row;
+// a second kernel adds the partial rows of a heavy row in a fixed order (no atomics anywhere: results are
+// reproducible run to run).
 #include <algorithm>
 #include <atomic>
 #include <vector>
@@ -34,8 +38,17 @@ constexpr int kXcd = 8;              // XCDs of the device = number of column ra
 constexpr int kWindow = 4096;        // columns per window
 constexpr int kHeavyLen = 256;       // a row with at least this many nonzeros is heavy
 constexpr int kUnitLen = 2048;       // target nonzeros per unit
-constexpr int kHeavyThreads = 1024;  // 128 lane groups of 8 lanes per workgroup: one workgroup fills a compute unit
+constexpr int kHeavyThreads = 1024;  // one workgroup fills a compute unit: 16 wavefronts, 128 lane groups of 8 lanes
 constexpr int kHeavyGroups = kHeavyThreads / 8;
+constexpr int kSlots = 32;           // workgroups per column range (= compute units of an XCD)
+constexpr int kWaves = kSlots * (kHeavyThreads / 64);      // wavefronts per column range
+constexpr int kGroupSlots = kSlots * kHeavyGroups;         // lane groups per column range
+constexpr int kMaxUnitsPerGroup = 4;
+constexpr int kBlock = 32;           // stream positions per lane group in one super-block (4 per lane)
+constexpr int kSync = 4;             // windows between two points where the groups of a wavefront (and the wavefronts of a
+                                     // compute unit) line up again: padding and barriers cost less, and within such an
+                                     // interval the groups stay within a window or two of each other anyway
+constexpr int32_t kNoFlush = -1, kSkip = -2;               // stream item codes (>= 0: flush into that unit slot)
 
 __global__ void __launch_bounds__(256) k_count_heavy(const int32_t *__restrict__ pos, int64_t nseg, int32_t min_len,
                                                      unsigned long long *__restrict__ count_and_nnz) {
@@ -88,125 +101,209 @@ __global__ void __launch_bounds__(256) k_build_wstart(const int32_t *__restrict_
     wstart[g] = lo;
 }
 
-// ---- the sweep -------------------------------------------------------------------------------------------
-// Lane group = 8 lanes; lane j holds ranks 16 q + 2 j, 16 q + 2 j + 1 of a row (q < V / 2), so one load
-// instruction reads a whole 128-byte line of a gathered row per lane group.  A lane group owns `nu` units
-// (their running sums sit in LDS, R doubles each) and walks them window by window: the work of a group is
-// the flat sequence of pieces t = (window, unit).  Three pieces are in flight at a time -- the window bounds
-// of piece t + 2 and the nonzeros of piece t + 1 are being fetched while the rows of B for piece t are
-// gathered (all of a piece's rows at once, up to 8) -- so that the chain bounds -> nonzeros -> rows is not
-// walked one memory latency at a time.
-struct UnitMeta { int woff, qn, uid; };      // window-table row offset, (piece << 16 | pieces of the row), partial row
+// ---- laying out the streams (once per tensor) ------------------------------------------------------------
+// Unit of lane-group slot gs (0 .. kGroupSlots-1) in round k: units come longest first and are dealt back and forth.
+__device__ __host__ inline int unit_of_slot(int gs, int k) { return k * kGroupSlots + ((k & 1) ? kGroupSlots - 1 - gs : gs); }
+// Lane-group slot of group gl (0..7) of wavefront wv (0 .. kWaves-1): consecutive slots go to different workgroups.
+__device__ __host__ inline int slot_of_group(int wv, int gl) {
+    const int wg = wv / (kHeavyThreads / 64), g = (wv % (kHeavyThreads / 64)) * 8 + gl;
+    return g * kSlots + wg;
+}
+// Positions [lo, hi) of unit u's piece inside window w (absolute window number).
+__device__ inline void piece_of(const int4 *__restrict__ units, const int32_t *__restrict__ wstart, int nwin, int u, int w,
+                                int *lo, int *hi) {
+    const int4 un = units[u];
+    const int64_t row = (int64_t)un.x * (nwin + 1);
+    const int a = wstart[row + w], e = wstart[row + w + 1];
+    const int n = e - a;                                              // at most kWindow
+    *lo = a + n * un.y / un.z;
+    *hi = a + n * (un.y + 1) / un.z;
+}
 
-template <int V>
-__global__ void __launch_bounds__(kHeavyThreads) k_spmm_heavy(const int32_t *__restrict__ crd, const double *__restrict__ vals,
-                                                              const int4 *__restrict__ units, int nunits, int nu,
-                                                              const int32_t *__restrict__ wstart, int nwin, int nwx,
-                                                              const double *__restrict__ Dn, int R,
-                                                              double *__restrict__ partial) {
-    constexpr int L = 8;
-    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    double *accs = reinterpret_cast<double *>(lds_raw);                          // [nu][groups][R]
-    int *meta = reinterpret_cast<int *>(lds_raw + (size_t)nu * kHeavyGroups * R * sizeof(double));   // [nu][groups][3]
-    const int x = blockIdx.x % kXcd, slot = blockIdx.x / kXcd, nslots = gridDim.x / kXcd;
-    const int g = threadIdx.x >> 3, j = threadIdx.x & 7;
-    // group slot: consecutive units (the table comes longest unit first) go to different workgroups, back and
-    // forth from one round to the next, so that every group -- and every workgroup -- gets about the same number
-    // of nonzeros per window and all of them need about the same time for it
-    const int gslot = g * nslots + slot, ngslots = nslots * kHeavyGroups;
-    const int w0 = x * nwx, w1 = (w0 + nwx < nwin) ? w0 + nwx : nwin;
-    const int per = nwin + 1;
-    for (int k = 0; k < nu; ++k) {
-        const int u = k * ngslots + ((k & 1) ? ngslots - 1 - gslot : gslot);
-        const int4 un = u < nunits ? units[u] : make_int4(0, 0, 1, -1);
-        if (j == 0) {
-            int *m = meta + (k * kHeavyGroups + g) * 3;
-            m[0] = un.x * per; m[1] = (un.y << 16) | un.z; m[2] = u < nunits ? un.w : -1;
+// wmax[(x * kWaves + wv) * nsx + i] = positions wavefront wv of range x needs for its i-th interval of kSync
+// windows: the most nonzeros any of its 8 groups has there
+__global__ void __launch_bounds__(256) k_window_lengths(const int4 *__restrict__ units, int nunits, int nu,
+                                                        const int32_t *__restrict__ wstart, int nwin, int nwx, int nsx,
+                                                        int32_t *__restrict__ wmax) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)kXcd * kWaves * nsx) return;
+    const int iv = (int)(t % nsx), wv = (int)((t / nsx) % kWaves), x = (int)(t / ((int64_t)nsx * kWaves));
+    int m = 0;
+    for (int gl = 0; gl < 8; ++gl) {
+        const int gs = slot_of_group(wv, gl);
+        int total = 0;
+        for (int w = iv * kSync; w < (iv + 1) * kSync && w < nwx; ++w) {
+            const int wabs = x * nwx + w;
+            if (wabs >= nwin) break;
+            for (int k = 0; k < nu; ++k) {
+                const int u = unit_of_slot(gs, k);
+                if (u >= nunits) continue;
+                int lo, hi;
+                piece_of(units, wstart, nwin, u, wabs, &lo, &hi);
+                total += hi - lo;
+            }
         }
+        m = total > m ? total : m;
+    }
+    wmax[t] = m;
+}
+
+// wend[(x * kWaves + wv) * (nsx + 1) + i] = first position of interval i (last entry: all positions);
+// nblocks[x * kWaves + wv] = super-blocks of kBlock positions the wavefront's stream takes
+__global__ void __launch_bounds__(256) k_window_ends(const int32_t *__restrict__ wmax, int nwx, int32_t *__restrict__ wend,
+                                                     int32_t *__restrict__ nblocks) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= kXcd * kWaves) return;
+    int p = 0;
+    for (int w = 0; w < nwx; ++w) { wend[(int64_t)t * (nwx + 1) + w] = p; p += wmax[(int64_t)t * nwx + w]; }
+    wend[(int64_t)t * (nwx + 1) + nwx] = p;
+    nblocks[t] = (p + kBlock - 1) / kBlock;
+}
+
+// One thread per (range, wavefront, interval, group): writes that group's positions of that interval -- window by
+// window, unit by unit -- and pads them to the interval's length.
+__global__ void __launch_bounds__(256) k_fill_streams(const int32_t *__restrict__ crd, const double *__restrict__ vals,
+                                                      const int4 *__restrict__ units, int nunits, int nu,
+                                                      const int32_t *__restrict__ wstart, int nwin, int nwx, int nsx,
+                                                      const int32_t *__restrict__ wend, const int32_t *__restrict__ block_start,
+                                                      int32_t *__restrict__ scrd, int32_t *__restrict__ scode,
+                                                      double *__restrict__ sval) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= (int64_t)kXcd * kWaves * nsx * 8) return;
+    const int gl = (int)(t % 8), iv = (int)((t / 8) % nsx), wv = (int)((t / (8 * (int64_t)nsx)) % kWaves),
+              x = (int)(t / (8 * (int64_t)nsx * kWaves));
+    const int wave = x * kWaves + wv;
+    const int32_t *we = wend + (int64_t)wave * (nsx + 1);
+    const int64_t base = (int64_t)block_start[wave] * (8 * kBlock) + gl * kBlock;
+    auto put = [&](int p, int c, int code, double v) {
+        const int64_t i = base + (int64_t)(p / kBlock) * (8 * kBlock) + (p % kBlock);
+        scrd[i] = c; scode[i] = code; sval[i] = v;
+    };
+    int p = we[iv];
+    const int gs = slot_of_group(wv, gl);
+    for (int w = iv * kSync; w < (iv + 1) * kSync && w < nwx; ++w) {
+        const int wabs = x * nwx + w;
+        if (wabs >= nwin) break;
+        for (int k = 0; k < nu; ++k) {
+            const int u = unit_of_slot(gs, k);
+            if (u >= nunits) continue;
+            int lo, hi;
+            piece_of(units, wstart, nwin, u, wabs, &lo, &hi);
+            for (int i = lo; i < hi; ++i, ++p) put(p, crd[i], i + 1 == hi ? k : kNoFlush, vals[i]);
+        }
+    }
+    int pend = we[iv + 1];
+    if (iv == nsx - 1) pend = (block_start[wave + 1] - block_start[wave]) * kBlock;   // and the padding behind the last interval
+    for (; p < pend; ++p) put(p, 0, kSkip, 0.0);
+}
+
+// ---- the sweep -------------------------------------------------------------------------------------------
+// Lane j of a group holds ranks 16 q + 2 j, 16 q + 2 j + 1 of a row (q < V / 2): one load instruction reads a
+// whole 128-byte line of a gathered row per lane group.  In a super-block lane j holds stream positions
+// 4 j .. 4 j + 3 of its group and hands them to the group one at a time with DPP broadcasts.
+template <int V>
+__global__ void __launch_bounds__(kHeavyThreads) k_heavy_sweep(const int32_t *__restrict__ scrd, const int32_t *__restrict__ scode,
+                                                               const double *__restrict__ sval,
+                                                               const int32_t *__restrict__ block_start,
+                                                               const int32_t *__restrict__ wend, int nsx, int nu,
+                                                               const int4 *__restrict__ units, int nunits,
+                                                               const double *__restrict__ Dn, int R,
+                                                               double *__restrict__ partial) {
+    constexpr int L = 8, G = V <= 4 ? 4 : 2, NG = kBlock / G;     // G rows gathered ahead of the multiply-adds
+    extern __shared__ __attribute__((aligned(16))) double accs[];              // [nu][groups][R]
+    const int x = blockIdx.x % kXcd, wg = blockIdx.x / kXcd;
+    const int g = threadIdx.x >> 3, j = threadIdx.x & 7, gl = g & 7;
+    const int wave = x * kWaves + wg * (kHeavyThreads / 64) + (threadIdx.x >> 6);
+    for (int k = 0; k < nu; ++k) {
         double *ac = accs + (size_t)(k * kHeavyGroups + g) * R;
 #pragma unroll
         for (int q = 0; q < V / 2; ++q) *reinterpret_cast<double2 *>(ac + 2 * L * q + 2 * j) = make_double2(0.0, 0.0);
     }
-    __builtin_amdgcn_wave_barrier();      // meta and sums of a group are written and read by the group's own lanes only
+    __builtin_amdgcn_wave_barrier();           // a group's sums are written and read by its own lanes only
 
-    const int T = (w1 - w0) * nu;         // pieces of this group: t = (w - w0) * nu + k
-    // piece t + 2: bounds;  piece t + 1: first L nonzeros;  piece t: being processed
-    int ba = 0, be = 0, bq = 1;           // bounds (and split code) of the piece two ahead
-    int nc = 0, nlo = 0, nhi = 0;         // the piece one ahead
-    double na = 0.0;
-    auto fetch_bounds = [&](int t) {      // t < T
-        const int k = t % nu, w = w0 + t / nu;
-        const int *m = meta + (k * kHeavyGroups + g) * 3;
-        const bool have = m[2] >= 0;
-        ba = have ? wstart[m[0] + w] : 0;
-        be = have ? wstart[m[0] + w + 1] : 0;
-        bq = m[1];
+    const int nsb = block_start[wave + 1] - block_start[wave];
+    const int64_t base = (int64_t)block_start[wave] * (8 * kBlock) + gl * kBlock + 4 * j;
+    const int32_t *we = wend + (int64_t)wave * (nsx + 1);
+    int w = 0;                                 // intervals (of kSync windows) finished so far
+    int next_end = we[1];                      // position at which interval w ends
+    typedef int v4i __attribute__((ext_vector_type(4)));
+    typedef double v2d __attribute__((ext_vector_type(2)));
+    struct Items { int cr[4], cd[4]; double va[4]; };
+    auto load_items = [&](Items &it, int sb) {
+        const int64_t i = base + (int64_t)sb * (8 * kBlock);
+        const v4i c4 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(scrd + i));
+        const v4i d4 = __builtin_nontemporal_load(reinterpret_cast<const v4i *>(scode + i));
+        const v2d a01 = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(sval + i));
+        const v2d a23 = __builtin_nontemporal_load(reinterpret_cast<const v2d *>(sval + i + 2));
+        it.cr[0] = c4.x; it.cr[1] = c4.y; it.cr[2] = c4.z; it.cr[3] = c4.w;
+        it.cd[0] = d4.x; it.cd[1] = d4.y; it.cd[2] = d4.z; it.cd[3] = d4.w;
+        it.va[0] = a01.x; it.va[1] = a01.y; it.va[2] = a23.x; it.va[3] = a23.y;
     };
-    auto fetch_items = [&]() {            // from the bounds in (ba, be, bq)
-        const int n = be - ba;                                                  // at most kWindow
-        const int qq = bq >> 16, ns = bq & 0xffff;
-        nlo = ba + n * qq / ns;
-        nhi = ba + n * (qq + 1) / ns;
-        const int i = nlo + j;
-        const bool in = i < nhi;
-        nc = in ? __builtin_nontemporal_load(crd + i) : 0;
-        na = in ? __builtin_nontemporal_load(vals + i) : 0.0;                   // 0 past the end
-    };
-    if (T > 0) { fetch_bounds(0); fetch_items(); }
-    if (T > 1) fetch_bounds(1);
-    for (int t = 0; t < T; ++t) {
-        int c = nc;
-        double a0 = na;
-        const int lo = nlo, hi = nhi;
-        if (t + 1 < T) fetch_items();
-        if (t + 2 < T) fetch_bounds(t + 2);
-        if (lo < hi) {
-            double *ac = accs + (size_t)((t % nu) * kHeavyGroups + g) * R;
-            double acc[V];
+    double acc[V];
 #pragma unroll
-            for (int v = 0; v < V; ++v) acc[v] = 0.0;
-            for (int base = lo; base < hi; base += L) {
-                if (base != lo) {                                              // a piece of more than L nonzeros: the rest on demand
-                    const int i = base + j;
-                    const bool in = i < hi;
-                    c = in ? __builtin_nontemporal_load(crd + i) : 0;
-                    a0 = in ? __builtin_nontemporal_load(vals + i) : 0.0;
+    for (int v = 0; v < V; ++v) acc[v] = 0.0;
+    Items cur;
+    if (nsb > 0) load_items(cur, 0);
+    for (int sb = 0; sb < nsb; ++sb) {
+        Items nxt;
+        if (sb + 1 < nsb) load_items(nxt, sb + 1);
+        const int p0 = sb * kBlock;
+        struct Row { double d[V]; };
+        Row buf[2][G];
+        auto issue = [&](auto gc, Row *bb) {
+            static_for<0, G>([&](auto sc) {
+                constexpr int k = decltype(gc)::value * G + decltype(sc)::value;
+                const int c = grp_bcast_i<L, k / 4>(cur.cr[k % 4]);
+                const int code = grp_bcast_i<L, k / 4>(cur.cd[k % 4]);
+                if (code != kSkip) {
+                    grp_load_row<L, V, true>(Dn, c, R, j, bb[decltype(sc)::value].d);
+                } else {
+#pragma unroll
+                    for (int v = 0; v < V; ++v) bb[decltype(sc)::value].d[v] = 0.0;
                 }
-                const int cnt = hi - base;                                     // items of this batch (more than L: then L)
-                double row[L][V];
-                static_for<0, L>([&](auto bp) {
-                    constexpr int BP = decltype(bp)::value;
-                    const int cb = grp_bcast_i<L, BP>(c);
-                    if (BP < cnt) {
-                        grp_load_row<L, V, true>(Dn, cb, R, j, row[BP]);
-                    } else {
+            });
+        };
+        auto consume = [&](auto gc, const Row *bb) {
+            static_for<0, G>([&](auto sc) {
+                constexpr int k = decltype(gc)::value * G + decltype(sc)::value;
+                // intervals that end before this position: all wavefronts of the compute unit finish an
+                // interval before any of them starts the next (wavefront-uniform condition)
+                while (p0 + k == next_end && w < nsx) {
+                    __builtin_amdgcn_s_barrier();
+                    ++w;
+                    next_end = w < nsx ? we[w + 1] : -1;
+                }
+                const double a = grp_bcast_d<L, k / 4>(cur.va[k % 4]);
+                const int code = grp_bcast_i<L, k / 4>(cur.cd[k % 4]);
 #pragma unroll
-                        for (int v = 0; v < V; ++v) row[BP][v] = 0.0;
+                for (int v = 0; v < V; ++v) acc[v] = fma(a, bb[decltype(sc)::value].d[v], acc[v]);
+                if (code >= 0) {                                   // the unit's piece ends here: add it to the unit's sum
+                    double *ac = accs + (size_t)(code * kHeavyGroups + g) * R;
+#pragma unroll
+                    for (int q = 0; q < V / 2; ++q) {
+                        double2 *pp = reinterpret_cast<double2 *>(ac + 2 * L * q + 2 * j);
+                        const double2 o = *pp;
+                        *pp = make_double2(o.x + acc[2 * q], o.y + acc[2 * q + 1]);
+                        acc[2 * q] = 0.0; acc[2 * q + 1] = 0.0;
                     }
-                });
-                static_for<0, L>([&](auto bp) {
-                    constexpr int BP = decltype(bp)::value;
-                    const double av = grp_bcast_d<L, BP>(a0);                  // 0 for the lanes past the end
-#pragma unroll
-                    for (int v = 0; v < V; ++v) acc[v] = fma(av, row[BP][v], acc[v]);
-                });
-            }
-#pragma unroll
-            for (int q = 0; q < V / 2; ++q) {
-                double2 *p = reinterpret_cast<double2 *>(ac + 2 * L * q + 2 * j);
-                const double2 o = *p;
-                *p = make_double2(o.x + acc[2 * q], o.y + acc[2 * q + 1]);
-            }
-        }
-        // all wavefronts of the compute unit finish a window before any starts the next (no data is exchanged:
-        // this only keeps them on the same rows of B)
-        if ((t + 1) % nu == 0) __builtin_amdgcn_s_barrier();
+                }
+            });
+        };
+        issue(IntC<0>{}, buf[0]);
+        static_for<0, NG>([&](auto gc) {
+            constexpr int gi = decltype(gc)::value;
+            if constexpr (gi + 1 < NG) issue(IntC<gi + 1>{}, buf[(gi + 1) & 1]);
+            consume(gc, buf[gi & 1]);
+        });
+        if (sb + 1 < nsb) cur = nxt;
     }
+    while (w < nsx) { __builtin_amdgcn_s_barrier(); ++w; }         // every wavefront meets every barrier
+    const int gs = g * kSlots + wg;
     for (int k = 0; k < nu; ++k) {
-        const int uid = meta[(k * kHeavyGroups + g) * 3 + 2];
-        if (uid < 0) continue;
+        const int u = unit_of_slot(gs, k);
+        if (u >= nunits) continue;
         const double *ac = accs + (size_t)(k * kHeavyGroups + g) * R;
-        double *pr = partial + ((int64_t)x * nunits + uid) * R;
+        double *pr = partial + ((int64_t)x * nunits + units[u].w) * R;
 #pragma unroll
         for (int q = 0; q < V / 2; ++q)
             *reinterpret_cast<double2 *>(pr + 2 * L * q + 2 * j) = *reinterpret_cast<const double2 *>(ac + 2 * L * q + 2 * j);
@@ -229,74 +326,34 @@ __global__ void __launch_bounds__(256) k_heavy_reduce(const double *__restrict__
     out[row * R + r] = s;
 }
 
-size_t heavy_lds_bytes(int nu, int R) { return (size_t)nu * kHeavyGroups * ((size_t)R * sizeof(double) + 3 * sizeof(int)); }
-
-constexpr int kMaxUnitsPerGroup = 6;
-
-// Units per lane group (nu) and workgroups per column range (nslots): the smallest nu for which all units are
-// resident at once, every compute unit filled with the same number of workgroups -- a workgroup that had a
-// compute unit more to itself would run ahead of the others and the sweeps would fall out of step.
-// False when one sweep cannot hold all units.
-template <int V>
-bool heavy_shape(const HeavyPlan &plan, int R, int *nu_out, int *nslots_out) {
-    static std::atomic<int> per_cu_of[kMaxUnitsPerGroup + 1];          // occupancy by nu, cached (0 = not asked yet)
-    static hipError_t attr = hipFuncSetAttribute((const void *)k_spmm_heavy<V>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (attr != hipSuccess) { (void)hipGetLastError(); return false; }
-    const int cus_per_xcd = current_device_cu_count() / kXcd > 0 ? current_device_cu_count() / kXcd : 1;
-    for (int nu = 1; nu <= kMaxUnitsPerGroup; ++nu) {
-        int per_cu = per_cu_of[nu].load();
-        if (per_cu == 0) {
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)k_spmm_heavy<V>, kHeavyThreads,
-                                                             heavy_lds_bytes(nu, R)) != hipSuccess || per_cu < 1) {
-                (void)hipGetLastError();
-                per_cu = -1;
-            }
-            per_cu_of[nu].store(per_cu);
-        }
-        if (per_cu < 1) return false;
-        if ((int64_t)per_cu * cus_per_xcd * kHeavyGroups * nu >= plan.nunits) {
-            int64_t want = (plan.nunits + (int64_t)nu * kHeavyGroups - 1) / ((int64_t)nu * kHeavyGroups);
-            want = (want + cus_per_xcd - 1) / cus_per_xcd * cus_per_xcd;
-            *nu_out = nu;
-            *nslots_out = (int)want;
-            return true;
-        }
-    }
-    return false;
-}
+size_t heavy_lds_bytes(int nu, int R) { return (size_t)nu * kHeavyGroups * (size_t)R * sizeof(double); }
 
 template <int V>
-hipError_t launch_heavy_v(const HeavyPlan &plan, const int32_t *crd, const double *vals, const double *Dn, int R,
-                          double *partial, hipStream_t st) {
-    int nu = 0, nslots = 0;
-    if (!heavy_shape<V>(plan, R, &nu, &nslots)) return hipErrorNotSupported;
-    const int nwx = (plan.nwin + kXcd - 1) / kXcd;
-    hipLaunchKernelGGL((k_spmm_heavy<V>), dim3((unsigned)(nslots * kXcd)), dim3(kHeavyThreads), heavy_lds_bytes(nu, R), st, crd,
-                       vals, (const int4 *)plan.units->ptr, (int)plan.nunits, nu, (const int32_t *)plan.wstart->ptr,
-                       (int)plan.nwin, nwx, Dn, R, partial);
+hipError_t launch_sweep(const HeavyPlan &plan, const double *Dn, int R, double *partial, hipStream_t st) {
+    static hipError_t attr = hipFuncSetAttribute((const void *)k_heavy_sweep<V>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (attr != hipSuccess) return attr;
+    const int nwx = (plan.nwin + kXcd - 1) / kXcd, nsx = (nwx + kSync - 1) / kSync;
+    hipLaunchKernelGGL((k_heavy_sweep<V>), dim3(kXcd * kSlots), dim3(kHeavyThreads), heavy_lds_bytes(plan.nu, R), st,
+                       (const int32_t *)plan.scrd->ptr, (const int32_t *)plan.scode->ptr, (const double *)plan.sval->ptr,
+                       (const int32_t *)plan.block_start->ptr, (const int32_t *)plan.wend->ptr, nsx, plan.nu,
+                       (const int4 *)plan.units->ptr, (int)plan.nunits, Dn, R, partial);
     return hipGetLastError();
 }
 
 }  // namespace
 
 bool heavy_supports(const HeavyPlan &plan, int64_t R) {
-    int nu = 0, nslots = 0;
     if (plan.nunits <= 0) return false;
-    switch ((int)R) {
-    case 16: return R == 16 && heavy_shape<2>(plan, 16, &nu, &nslots);
-    case 32: return heavy_shape<4>(plan, 32, &nu, &nslots);
-    case 48: return heavy_shape<6>(plan, 48, &nu, &nslots);
-    case 64: return heavy_shape<8>(plan, 64, &nu, &nslots);
-    }
-    return false;
+    if (R != 16 && R != 32 && R != 48 && R != 64) return false;
+    return heavy_lds_bytes(plan.nu, (int)R) <= 150 * 1024;          // the units' sums must fit next to nothing else in LDS
 }
 
 size_t heavy_partial_bytes(const HeavyPlan &plan, int64_t R) {
     return ((size_t)kXcd * (size_t)plan.nunits * (size_t)R * sizeof(double) + 255) & ~(size_t)255;
 }
 
-hipError_t heavy_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd, int64_t nnz, int64_t ncols,
-                            HeavyPlan &plan, hipStream_t st) {
+hipError_t heavy_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd, const double *vals, int64_t nnz,
+                            int64_t ncols, HeavyPlan &plan, hipStream_t st) {
     plan = HeavyPlan();
     // worth it only when the dense operand is far larger than the caches and there is real work
     if (nnz < (int64_t(1) << 20) || ncols < (int64_t(1) << 16) || nseg < 1) return hipSuccess;
@@ -314,6 +371,7 @@ hipError_t heavy_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd
     if (e != hipSuccess) return e;
     const int64_t nheavy = (int64_t)h[0], heavy_nnz = (int64_t)h[1];
     const int64_t nwin = (ncols + kWindow - 1) / kWindow;
+    const int nwx = (int)((nwin + kXcd - 1) / kXcd), nsx = (nwx + kSync - 1) / kSync;
     if (nheavy < 1 || heavy_nnz * 8 < nnz) return hipSuccess;              // the long rows hold under an eighth
     if (nheavy * (nwin + 1) > (int64_t(1) << 27)) return hipSuccess;      // window table beyond 512 MB: not worth it
     DevRef list = dev_alloc(sizeof(int2) * nheavy);
@@ -336,47 +394,86 @@ hipError_t heavy_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd
         hseg[(size_t)k] = rows[(size_t)k].x;
         ubeg[(size_t)k] = (int32_t)recs.size();
         int nsplit = (rows[(size_t)k].y + kUnitLen - 1) / kUnitLen;
-        if (nsplit > 0x7fff) nsplit = 0x7fff;                              // (piece, pieces) travel in 16 bits each
+        if (nsplit > kWindow) nsplit = kWindow;
         for (int qq = 0; qq < nsplit; ++qq)
             recs.push_back({(int)k, qq, nsplit, (int)recs.size(), rows[(size_t)k].y / nsplit});
     }
     ubeg[(size_t)nheavy] = (int32_t)recs.size();
+    const int64_t nunits = (int64_t)recs.size();
+    const int nu = (int)((nunits + kGroupSlots - 1) / kGroupSlots);
+    if (nu > kMaxUnitsPerGroup) return hipSuccess;                         // more units than one sweep can hold
     // the kernel takes the units longest first (ties in row order): units of equal rank in two rounds of the
     // dealing then have about the same length.  The partial row of a unit keeps its row-major number (.w).
     std::stable_sort(recs.begin(), recs.end(), [](const UnitRec &a, const UnitRec &b) { return a.len > b.len; });
     std::vector<int4> units(recs.size());
     for (size_t k = 0; k < recs.size(); ++k) units[k] = make_int4(recs[k].h, recs[k].q, recs[k].nsplit, recs[k].id);
-    if (units.size() >= (size_t(1) << 28)) return hipSuccess;
+
+    const int nwaves = kXcd * kWaves;
     plan.units = dev_alloc(sizeof(int4) * units.size());
     plan.unit_begin = dev_alloc(sizeof(int32_t) * ubeg.size());
     plan.hseg = dev_alloc(sizeof(int32_t) * hseg.size());
-    plan.wstart = dev_alloc(sizeof(int32_t) * (size_t)(nheavy * (nwin + 1)));
-    if (!plan.units || !plan.unit_begin || !plan.hseg || !plan.wstart) { plan = HeavyPlan(); return hipErrorOutOfMemory; }
+    plan.wend = dev_alloc(sizeof(int32_t) * (size_t)nwaves * (nsx + 1));
+    plan.block_start = dev_alloc(sizeof(int32_t) * (nwaves + 1));
+    DevRef wstart = dev_alloc(sizeof(int32_t) * (size_t)(nheavy * (nwin + 1)));
+    DevRef wmax = dev_alloc(sizeof(int32_t) * (size_t)nwaves * nsx);
+    DevRef nblocks = dev_alloc(sizeof(int32_t) * nwaves);
+    if (!plan.units || !plan.unit_begin || !plan.hseg || !plan.wend || !plan.block_start || !wstart || !wmax || !nblocks) {
+        plan = HeavyPlan();
+        return hipErrorOutOfMemory;
+    }
     e = hipMemcpyAsync(plan.units->ptr, units.data(), sizeof(int4) * units.size(), hipMemcpyHostToDevice, st);
     if (e == hipSuccess) e = hipMemcpyAsync(plan.unit_begin->ptr, ubeg.data(), sizeof(int32_t) * ubeg.size(), hipMemcpyHostToDevice, st);
     if (e == hipSuccess) e = hipMemcpyAsync(plan.hseg->ptr, hseg.data(), sizeof(int32_t) * hseg.size(), hipMemcpyHostToDevice, st);
     if (e != hipSuccess) { plan = HeavyPlan(); return e; }
     const int64_t cells = nheavy * (nwin + 1);
     hipLaunchKernelGGL(k_build_wstart, dim3((unsigned)((cells + 255) / 256)), dim3(256), 0, st, pos, crd,
-                       (const int32_t *)plan.hseg->ptr, nheavy, (int)nwin, (int)kWindow, (int32_t *)plan.wstart->ptr);
-    e = hipStreamSynchronize(st);                                          // the host vectors go out of scope
+                       (const int32_t *)plan.hseg->ptr, nheavy, (int)nwin, (int)kWindow, (int32_t *)wstart->ptr);
+    const int64_t nlen = (int64_t)nwaves * nsx;
+    hipLaunchKernelGGL(k_window_lengths, dim3((unsigned)((nlen + 255) / 256)), dim3(256), 0, st, (const int4 *)plan.units->ptr,
+                       (int)nunits, nu, (const int32_t *)wstart->ptr, (int)nwin, nwx, nsx, (int32_t *)wmax->ptr);
+    hipLaunchKernelGGL(k_window_ends, dim3((unsigned)((nwaves + 255) / 256)), dim3(256), 0, st, (const int32_t *)wmax->ptr, nsx,
+                       (int32_t *)plan.wend->ptr, (int32_t *)nblocks->ptr);
+    std::vector<int32_t> nb((size_t)nwaves), bs((size_t)nwaves + 1);
+    e = hipMemcpyAsync(nb.data(), nblocks->ptr, sizeof(int32_t) * nwaves, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
     if (e != hipSuccess) { plan = HeavyPlan(); return e; }
-    plan.nheavy = nheavy; plan.nunits = (int64_t)units.size(); plan.heavy_nnz = heavy_nnz;
-    plan.min_len = kHeavyLen; plan.window = kWindow; plan.nwin = (int32_t)nwin;
+    int64_t total_blocks = 0;
+    for (int k = 0; k < nwaves; ++k) { bs[(size_t)k] = (int32_t)total_blocks; total_blocks += nb[(size_t)k]; }
+    bs[(size_t)nwaves] = (int32_t)total_blocks;
+    const int64_t npos = total_blocks * 8 * kBlock;                       // stream items, padding included
+    if (total_blocks >= (int64_t(1) << 31) / (8 * kBlock) || npos > 8 * heavy_nnz + (int64_t(1) << 24)) {
+        plan = HeavyPlan();                                                // the padding would outweigh the nonzeros
+        return hipSuccess;
+    }
+    plan.scrd = dev_alloc(sizeof(int32_t) * (size_t)npos);
+    plan.scode = dev_alloc(sizeof(int32_t) * (size_t)npos);
+    plan.sval = dev_alloc(sizeof(double) * (size_t)npos);
+    if (!plan.scrd || !plan.scode || !plan.sval) { plan = HeavyPlan(); return hipErrorOutOfMemory; }
+    e = hipMemcpyAsync(plan.block_start->ptr, bs.data(), sizeof(int32_t) * bs.size(), hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) { plan = HeavyPlan(); return e; }
+    const int64_t nfill = (int64_t)nwaves * nsx * 8;
+    hipLaunchKernelGGL(k_fill_streams, dim3((unsigned)((nfill + 255) / 256)), dim3(256), 0, st, crd, vals,
+                       (const int4 *)plan.units->ptr, (int)nunits, nu, (const int32_t *)wstart->ptr, (int)nwin, nwx, nsx,
+                       (const int32_t *)plan.wend->ptr, (const int32_t *)plan.block_start->ptr, (int32_t *)plan.scrd->ptr,
+                       (int32_t *)plan.scode->ptr, (double *)plan.sval->ptr);
+    e = hipStreamSynchronize(st);                                          // the host vectors and the temporaries go out of scope
+    if (e != hipSuccess) { plan = HeavyPlan(); return e; }
+    plan.nheavy = nheavy; plan.nunits = nunits; plan.heavy_nnz = heavy_nnz; plan.nu = nu;
+    plan.min_len = kHeavyLen; plan.window = kWindow; plan.nwin = (int32_t)nwin; plan.stream_items = npos;
     return hipGetLastError();
 }
 
-hipError_t heavy_spmm(const HeavyPlan &plan, const int32_t *crd, const double *vals, const int32_t *rowmap,
-                      const double *Dn, int64_t R, double *out, void *partial, hipStream_t st) {
+hipError_t heavy_spmm(const HeavyPlan &plan, const int32_t *rowmap, const double *Dn, int64_t R, double *out, void *partial,
+                      hipStream_t st) {
     if (plan.nunits <= 0) return hipSuccess;
     if (!heavy_supports(plan, R)) return hipErrorNotSupported;
     hipError_t e;
     double *pp = (double *)partial;
     switch ((int)R) {
-    case 16: e = launch_heavy_v<2>(plan, crd, vals, Dn, 16, pp, st); break;
-    case 32: e = launch_heavy_v<4>(plan, crd, vals, Dn, 32, pp, st); break;
-    case 48: e = launch_heavy_v<6>(plan, crd, vals, Dn, 48, pp, st); break;
-    default: e = launch_heavy_v<8>(plan, crd, vals, Dn, 64, pp, st); break;
+    case 16: e = launch_sweep<2>(plan, Dn, 16, pp, st); break;
+    case 32: e = launch_sweep<4>(plan, Dn, 32, pp, st); break;
+    case 48: e = launch_sweep<6>(plan, Dn, 48, pp, st); break;
+    default: e = launch_sweep<8>(plan, Dn, 64, pp, st); break;
     }
     if (e != hipSuccess) return e;
     const int64_t threads = plan.nheavy * R;

@@ -38,15 +38,15 @@ hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *
 // ---- heavy-row sweep of SpMM (kernels_heavy.hip) ---------------------------------------------------
 // Builds the plan for a [*,CU] matrix level (pos over nseg segments, crd with coordinates < ncols); leaves
 // plan.nunits = 0 when the rows of >= min_len nonzeros hold too small a share to matter.  Synchronises.
-hipError_t heavy_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd, int64_t nnz, int64_t ncols,
-                            HeavyPlan &plan, hipStream_t st);
-// The sweep exists for ranks 16, 32, 48 and 64 and for as many units as can be resident at once.
+hipError_t heavy_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd, const double *vals, int64_t nnz,
+                            int64_t ncols, HeavyPlan &plan, hipStream_t st);
+// The sweep exists for ranks 16, 32, 48 and 64, as long as the sums of a compute unit's units fit its LDS.
 bool   heavy_supports(const HeavyPlan &plan, int64_t R);
 size_t heavy_partial_bytes(const HeavyPlan &plan, int64_t R);
 // out[row(h), :] = sum over heavy row h of vals * Dn[crd, :] for every heavy row (row(h) = rowmap ?
 // rowmap[seg] : seg); `partial` holds heavy_partial_bytes(plan, R).
-hipError_t heavy_spmm(const HeavyPlan &plan, const int32_t *crd, const double *vals, const int32_t *rowmap,
-                      const double *Dn, int64_t R, double *out, void *partial, hipStream_t st);
+hipError_t heavy_spmm(const HeavyPlan &plan, const int32_t *rowmap, const double *Dn, int64_t R, double *out, void *partial,
+                      hipStream_t st);
 
 // Number of compute units of the current device (cached per device).
 int current_device_cu_count();

@@ -47,16 +47,19 @@ constexpr int kChunk = 1024;
 
 // Plan of the heavy-row sweep of SpMM (kernels_heavy.hip), built once at creation for matrices whose long
 // rows hold a large share of the nonzeros.  Rows of at least `min_len` nonzeros are "heavy"; each is cut
-// into units of roughly equal length (a unit takes the q-th of nsplit equal pieces of the row's nonzeros
-// inside every column window), and wstart[h][w] is the position of heavy row h's first nonzero whose
-// column is >= w * window (wstart[h][nwin] = the row's end).
+// into units of roughly equal length, every lane group of the sweep owns `nu` units, and the nonzeros of
+// the heavy rows are laid out again as one stream per wavefront in the order the sweep takes them (window
+// by window, unit by unit; 16 bytes per stream item, padding included) -- the one place where the library
+// keeps a re-ordered copy of (a part of) a tensor, because the order is what makes the cache reuse work.
 struct HeavyPlan {
-    int64_t nheavy = 0, nunits = 0, heavy_nnz = 0;
-    int32_t min_len = 0, window = 0, nwin = 0;
+    int64_t nheavy = 0, nunits = 0, heavy_nnz = 0, stream_items = 0;
+    int32_t min_len = 0, window = 0, nwin = 0, nu = 0;
     DevRef  units;        // int4 [nunits], longest unit first: {heavy row h, piece q, pieces of the row, row-major unit number}
-    DevRef  unit_begin;   // int32 [nheavy + 1]: units of heavy row h
+    DevRef  unit_begin;   // int32 [nheavy + 1]: units of heavy row h (row-major numbers)
     DevRef  hseg;         // int32 [nheavy]: segment (row position) of heavy row h, longest rows first
-    DevRef  wstart;       // int32 [nheavy][nwin + 1]
+    DevRef  scrd, scode, sval;   // the streams: column, item code (-1 plain, -2 padding, k >= 0: ends unit slot k's piece), value
+    DevRef  block_start;  // int32 [wavefronts + 1]: first super-block (8 groups x 32 positions) of each wavefront's stream
+    DevRef  wend;         // int32 [wavefronts][windows per range + 1]: first position of each window in the stream
 };
 
 // Per-tensor schedule for the nonzero-tiled kernels, built once at creation.
