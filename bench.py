@@ -26,7 +26,13 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-ALL_OPS = ["spmm", "spmv", "ttv", "ttv_coo", "ttm", "mttkrp16", "mttkrp64", "ttv_m0", "ttm_m0", "mttkrp16_m1", "spmm_dcsr"]
+ALL_OPS = ["spmm", "spmv", "spmv_large", "ttv", "ttv_coo", "ttm", "mttkrp16", "mttkrp64", "ttv_m0", "ttm_m0", "mttkrp16_m1",
+           "spmm_dcsr", "read", "gather_l2", "gather_c64", "gather_b16", "gather_b32", "gather_b64"]
+# calibration legs (no tensor): a plain 2 GiB read and row gathers by lane groups of 8 from tables of
+# (rows x R doubles): 16384 x 16 (2 MB, L2-resident), 20000 x 64 (10 MB: the C factor of MTTKRP at rank 64),
+# 10^6 x 16 / 32 / 64 (128 / 256 / 512 MB: the B operands of MTTKRP and SpMM)
+CALIBRATION = {"gather_l2": (16384, 16), "gather_c64": (20000, 64), "gather_b16": (1000000, 16),
+               "gather_b32": (1000000, 32), "gather_b64": (1000000, 64)}
 # "<op>_m<n>": the same operation along / for mode n of the same tensor, on the storage that
 # comet_tensor_reorder builds for it (first-mode TTV and TTM are the forms Section 8.2 writes out)
 
@@ -132,6 +138,10 @@ def measured_traffic(op):
     return None if e is None else int(e["fetch_bytes"]) + int(e["write_bytes"])
 
 
+TRAFFIC_SOURCE = ("profiles/hbm_traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command at full size, "
+                  "collected in separate runs (the counters cannot be read in-process); not measured in this run")
+
+
 def roofline(bytes_per_launch, ms, op=None, full_size=True):
     gbs = bytes_per_launch / (ms * 1e-3) / 1e9
     traffic = measured_traffic(op) if (op and full_size) else None
@@ -139,6 +149,7 @@ def roofline(bytes_per_launch, ms, op=None, full_size=True):
            "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": traffic, "bytes_per_launch": int(bytes_per_launch)}
     if traffic is not None:
         out["traffic_gbs"] = round(traffic / (ms * 1e-3) / 1e9, 1)
+        out["traffic_source"] = TRAFFIC_SOURCE
     return out
 
 
@@ -150,7 +161,27 @@ def run_op(op, args, comet, dev):
     t_gen = time.perf_counter()
     sc = args.scale
     keep = {}
-    if op == "copy":
+    if op == "read":
+        n = 1 << 28
+        src = torch.ones(n, dtype=torch.float64, device=dev)
+        sink = torch.zeros(1, dtype=torch.float64, device=dev)
+        fn = lambda: comet.comet_calibrate_read(src, sink)
+        nnz, flops, nbytes = n, 0, 8 * n
+        desc = "plain read of %d bytes (calibration)" % (8 * n)
+        extra = {}
+        keep = dict(src=src, sink=sink)
+    elif op in CALIBRATION:
+        rows_, R_ = CALIBRATION[op]
+        table = torch.ones((rows_, R_), dtype=torch.float64, device=dev)
+        sink = torch.zeros(1, dtype=torch.float64, device=dev)
+        gathers = 1 << 26
+        fn = lambda: comet.comet_calibrate_gather(table, gathers, sink)
+        nnz, flops, nbytes = gathers, 0, gathers * 8 * R_
+        desc = "%d gathers of %d-byte rows from a %.1f MB table (calibration; bytes = gathered bytes, not HBM traffic)" % (
+            gathers, 8 * R_, rows_ * R_ * 8 / 1e6)
+        extra = {"rows_per_s": None, "table_bytes": rows_ * R_ * 8, "row_bytes": 8 * R_}
+        keep = dict(table=table, sink=sink)
+    elif op == "copy":
         # calibration only: a plain 1 GiB device-to-device copy, to scale the rocprofv3 HBM byte counters
         n = 1 << 27
         src = torch.ones(n, dtype=torch.float64, device=dev)
@@ -287,6 +318,9 @@ def run_op(op, args, comet, dev):
     ms = tm["mean_ms"]
     if op == "spmv":
         extra.update(small_problem_latency(fn, keep["y"], dev))
+    if op in CALIBRATION:
+        extra["rows_per_s"] = round(nnz / (ms * 1e-3), 1)
+        extra["bytes_per_clk_per_cu"] = round(nbytes / (ms * 1e-3) / 2.4e9 / 256, 2)
     if "gather_bytes" in extra:
         # second roofline: every operand-row gather counted as HBM traffic (no cache reuse at all) instead of
         # each touched row once -- the upper bracket of what the call has to move
@@ -304,7 +338,10 @@ def run_op(op, args, comet, dev):
 
 
 def cpu_baseline_spmm(keep, budget_nnz=40_000_000):
-    """The CPU oracle (single thread, as it stands) on the leading rows of the headline matrix."""
+    """The CPU oracle, as it stands, on the leading rows of the headline matrix: once on one thread, and once
+    on every core this process may use -- the same C function called on row-disjoint pieces of the coordinate
+    list from a thread pool (the rows of C are disjoint, so the arithmetic per element is unchanged)."""
+    import concurrent.futures
     import numpy as np
     import torch
     import oracle
@@ -326,9 +363,35 @@ def cpu_baseline_spmm(keep, budget_nnz=40_000_000):
     dt = time.perf_counter() - t0
     got = keep["C"][:nrows].cpu().numpy()
     ok = bool(np.all(np.abs(got - ref) <= 1e-10 * np.abs(ref) + 1e-12 * absum))
+    # all cores: pieces of about equal nonzero count, cut at row boundaries
+    cores = len(os.sched_getaffinity(0))
+    cuts = [0]
+    for q in range(1, cores):
+        p = int(np.searchsorted(r_h, r_h[min(m - 1, q * m // cores)], side="left"))
+        if p > cuts[-1]:
+            cuts.append(p)
+    cuts.append(m)
+    pieces = []
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        r0 = int(r_h[a])
+        r1 = int(r_h[b - 1]) + 1
+        pieces.append((r0, r1, (r_h[a:b] - r0).astype(np.int32), c_h[a:b], v_h[a:b]))
+
+    def run(piece):
+        r0, r1, rr, cc, vv = piece
+        return r0, r1, oracle.spmm(rr, cc, vv, (r1 - r0, n), B_h)[0]
+
+    t0 = time.perf_counter()
+    with concurrent.futures.ThreadPoolExecutor(max_workers=len(pieces)) as pool:
+        outs = list(pool.map(run, pieces))
+    dt_all = time.perf_counter() - t0
+    same = all(np.array_equal(o[np.unique(p[2])], ref[r0:r1][np.unique(p[2])]) for (r0, r1, o), p in zip(outs, pieces))
     return {"value": round(2 * R * m / dt / 1e9, 3), "unit": "GFLOP/s", "cores": 1, "kind": "oracle",
             "sample": "rows 0..%d of the SpMM matrix (%d of %d nnz), %.1f s" % (nrows - 1, m, nnz, dt),
-            "parity_on_sample": ok}
+            "parity_on_sample": ok,
+            "all_cores": {"value": round(2 * R * m / dt_all / 1e9, 3), "unit": "GFLOP/s", "cores": len(pieces),
+                          "cores_available": cores, "seconds": round(dt_all, 2), "same_values_as_one_thread": bool(same),
+                          "how": "the same oracle function on row-disjoint pieces, one thread each"}}
 
 
 def main():
@@ -367,7 +430,8 @@ def main():
             head_keep = keep
             if not args.no_cpu_baseline:
                 cpu = cpu_baseline_spmm(keep)
-                log("[bench] cpu oracle: %s GFLOP/s on %s (parity on sample: %s)" % (cpu["value"], cpu["sample"], cpu["parity_on_sample"]))
+                log("[bench] cpu oracle: %s GFLOP/s on %s (parity on sample: %s); all %d cores: %s GFLOP/s" % (
+                    cpu["value"], cpu["sample"], cpu["parity_on_sample"], cpu["all_cores"]["cores"], cpu["all_cores"]["value"]))
         del keep
         head_keep = None
         torch.cuda.empty_cache()

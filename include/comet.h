@@ -255,6 +255,18 @@ const char *comet_status_string(comet_status s);
  * For testing and measurement; results are the same up to summation order. */
 comet_status comet_tensor_set_variant(comet_tensor *t, int variant);
 
+/* Calibration of the device's memory system, for the benchmark (no tensor involved): the two access
+ * patterns the operations are made of, timed by the caller.
+ *   comet_calibrate_read    streams n doubles (n >= 2, data 16-byte aligned) once through the device.
+ *   comet_calibrate_gather  lets lane groups of 8 gather `gathers` (rounded up to a multiple of 262144) whole
+ *                           rows of R doubles (R = 16, 32 or 64) at pseudo-random row numbers from a
+ *                           [nrows x R] row-major table (nrows < 2^29): L2-resident, cache-exceeding or
+ *                           memory-resident according to the table's size.
+ *   sink                    device, 1 double; never written for finite data (it keeps the loads alive). */
+comet_status comet_calibrate_read(const double *data, int64_t n, double *sink, void *stream);
+comet_status comet_calibrate_gather(const double *table, int64_t nrows, int64_t R, int64_t gathers, double *sink,
+                                    void *stream);
+
 #ifdef __cplusplus
 }
 #endif

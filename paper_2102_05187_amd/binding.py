@@ -27,7 +27,8 @@ _STATUS_NAMES = {0: "COMET_OK", 1: "COMET_ERR_INVALID_ARG", 2: "COMET_ERR_BAD_FO
 
 EXPORTS = ["comet_tensor_create", "comet_tensor_destroy", "comet_tensor_info", "comet_spmv", "comet_spmm",
            "comet_ttv", "comet_ttm", "comet_mttkrp", "comet_status_string", "comet_tensor_set_variant",
-           "comet_tensor_reorder", "comet_tensor_convert", "comet_tensor_reserve", "comet_spmv_static"]
+           "comet_tensor_reorder", "comet_tensor_convert", "comet_tensor_reserve", "comet_spmv_static",
+           "comet_calibrate_read", "comet_calibrate_gather"]
 
 
 class CometError(RuntimeError):
@@ -69,6 +70,8 @@ def _lib():
         lib.comet_spmv.argtypes = [vp, vp, vp, vp]
         lib.comet_spmv_static.argtypes = [vp, vp, vp, vp]
         lib.comet_tensor_reserve.argtypes = [vp, i64, vp]
+        lib.comet_calibrate_read.argtypes = [vp, i64, vp, vp]
+        lib.comet_calibrate_gather.argtypes = [vp, i64, i64, i64, vp, vp]
         lib.comet_spmm.argtypes = [vp, vp, i64, vp, vp]
         lib.comet_ttv.argtypes = [vp, ci, vp, ctypes.POINTER(vp), vp]
         lib.comet_ttm.argtypes = [vp, ci, vp, i64, ctypes.POINTER(vp), vp]
@@ -279,6 +282,19 @@ def comet_spmv_static(A: Tensor, x: torch.Tensor, y: torch.Tensor, stream=None) 
         raise CometError(3, "comet_spmv_static")
     _check(_lib().comet_spmv_static(A.handle, x.data_ptr(), y.data_ptr(), _stream(stream)), "comet_spmv_static")
     return y
+
+
+def comet_calibrate_read(data: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    data, sink = _dev(data, torch.float64, "data"), _dev(sink, torch.float64, "sink")
+    _check(_lib().comet_calibrate_read(data.data_ptr(), data.numel(), sink.data_ptr(), _stream(stream)), "comet_calibrate_read")
+
+
+def comet_calibrate_gather(table: torch.Tensor, gathers: int, sink: torch.Tensor, stream=None) -> None:
+    table, sink = _dev(table, torch.float64, "table"), _dev(sink, torch.float64, "sink")
+    if table.dim() != 2:
+        raise CometError(3, "comet_calibrate_gather")
+    _check(_lib().comet_calibrate_gather(table.data_ptr(), table.shape[0], table.shape[1], int(gathers), sink.data_ptr(),
+                                         _stream(stream)), "comet_calibrate_gather")
 
 
 def comet_spmm(A: Tensor, B: torch.Tensor, C: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
