@@ -153,6 +153,22 @@ def roofline(bytes_per_launch, ms, op=None, full_size=True):
     return out
 
 
+def relabel_matrix(c, sweeps):
+    """(rows, cols, vals) of a generated matrix configuration, relabelled and re-sorted when sweeps > 0; the
+    dense operand follows the new column labels so that the product is the relabelled original one."""
+    if not sweeps:
+        return c["coo"]
+    import torch
+    from synth import lexi
+    (rows, cols), labels = lexi.lexi_relabel(c["coo"][:2], c["dims"], sweeps)
+    (rows, cols), vals = lexi.sort_nonzeros((rows, cols), c["dims"], c["coo"][2])
+    moved = torch.empty_like(c["B"])
+    moved[labels[1]] = c["B"]
+    c["B"] = moved
+    c["coo"] = (rows, cols, vals)
+    return rows, cols, vals
+
+
 def run_op(op, args, comet, dev):
     """Generate the op's configuration on the GPU, time it, return the report entry (+ inputs for the baseline)."""
     import torch
@@ -208,7 +224,7 @@ def run_op(op, args, comet, dev):
     elif op == "spmv_large":
         # the SpMM matrix with one dense column: x (8 MB) does not fit in LDS, gathers go through L1 / L2
         c = gen.config_spmm(seed=0, device=dev, scale=sc, R=1)
-        rows, cols, vals = c["coo"]
+        rows, cols, vals = relabel_matrix(c, args.lexi_sweeps)
         n = c["dims"][0]
         L = fmt.pack_csr(n, n, rows, cols, vals)
         A = comet.from_levels(L).set_variant(args.variant)
@@ -222,7 +238,7 @@ def run_op(op, args, comet, dev):
         keep = dict(A=A, L=L, x=x, y=y)
     elif op in ("spmm", "spmm_dcsr"):
         c = gen.config_spmm(seed=0, device=dev, scale=sc, R=32)
-        rows, cols, vals = c["coo"]
+        rows, cols, vals = relabel_matrix(c, args.lexi_sweeps)
         n = c["dims"][0]
         R = 32
         L = fmt.pack_csr(n, n, rows, cols, vals) if op == "spmm" else fmt.pack_dcsr(n, n, rows, cols, vals)
@@ -249,8 +265,19 @@ def run_op(op, args, comet, dev):
             c = gen.config_ttm(seed=0, device=dev, scale=sc, R=R, **kw)
         else:
             c = gen.config_mttkrp(seed=0, device=dev, scale=sc, R=R, **kw)
-        i, j, k, vals = c["coo"]
         dims = c["dims"]
+        if args.lexi_sweeps:
+            from synth import lexi
+            (i, j, k), labels = lexi.lexi_relabel(c["coo"][:3], dims, args.lexi_sweeps)
+            (i, j, k), vals = lexi.sort_nonzeros((i, j, k), dims, c["coo"][3])
+            for name, m in (("v", 2), ("U", 2), ("C", 2), ("B", 1)):      # dense operands follow their mode's new labels
+                if name in c:
+                    moved = torch.empty_like(c[name])
+                    moved[labels[m]] = c[name]
+                    c[name] = moved
+            del labels
+        else:
+            i, j, k, vals = c["coo"]
         nnz = vals.numel()
         L = fmt.pack_coo(dims, (i, j, k), vals) if op == "ttv_coo" else fmt.pack_csf3(dims, i, j, k, vals)
         touched_k = count_distinct(k)
@@ -403,6 +430,9 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink every configuration (testing only)")
     ap.add_argument("--variant", type=int, default=0, help="0 auto, 1 simple kernels, 2 tiled kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--lexi-sweeps", type=int, default=0,
+                    help="relabel the coordinates lexicographically (synth/lexi.py, Section 7 of the paper) this many "
+                         "sweeps over all modes before packing; the on/off experiment of the reordering")
     ap.add_argument("--identity-ranks", action="store_true",
                     help="tensor configs: Zipf rank r maps to coordinate r (clusters the nonzeros) instead of a seeded permutation")
     args = ap.parse_args()

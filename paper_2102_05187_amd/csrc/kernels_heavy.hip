@@ -441,8 +441,25 @@ hipError_t heavy_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd
     for (int k = 0; k < nwaves; ++k) { bs[(size_t)k] = (int32_t)total_blocks; total_blocks += nb[(size_t)k]; }
     bs[(size_t)nwaves] = (int32_t)total_blocks;
     const int64_t npos = total_blocks * 8 * kBlock;                       // stream items, padding included
-    if (total_blocks >= (int64_t(1) << 31) / (8 * kBlock) || npos > 8 * heavy_nnz + (int64_t(1) << 24)) {
-        plan = HeavyPlan();                                                // the padding would outweigh the nonzeros
+    int64_t longest = 0;
+    for (int k = 0; k < nwaves; ++k) longest = std::max<int64_t>(longest, nb[(size_t)k]);
+    // The sweep lasts as long as its longest wavefront stream.  With the columns of every unit spread evenly over
+    // the column ranges, the stream of a lane group holds an eighth of the nonzeros of the group's units (plus
+    // padding).  Columns clustered in a few windows (a banded or relabelled matrix) put whole units into one
+    // stream and leave the other wavefronts idle; the nonzero-tiled kernel, which is insensitive to that, then
+    // does the whole matrix.
+    int64_t even_share = 0;
+    for (int gs = 0; gs < kGroupSlots; ++gs) {
+        int64_t sum = 0;
+        for (int k = 0; k < nu; ++k) {
+            const int u = unit_of_slot(gs, k);
+            if (u < (int)nunits) sum += recs[(size_t)u].len;
+        }
+        even_share = std::max(even_share, sum / kXcd);
+    }
+    if (total_blocks >= (int64_t(1) << 31) / (8 * kBlock) || npos > 8 * heavy_nnz + (int64_t(1) << 24) ||
+        longest * kBlock > 3 * even_share + 16 * kBlock) {
+        plan = HeavyPlan();
         return hipSuccess;
     }
     plan.scrd = dev_alloc(sizeof(int32_t) * (size_t)npos);

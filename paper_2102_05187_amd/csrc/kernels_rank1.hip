@@ -609,7 +609,8 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
         e = stream_segreduce_rankR(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st, heavy_len);
     }
     if (e != hipSuccess) return e;
-    return run_fixup(scratch, sc.ntiles, (int)R, rowmap, out, sc.max_seg_len / kTile + 2, st);
+    // the rank-R kernel publishes result rows as ids, the rank-1 kernel segment numbers
+    return run_fixup(scratch, sc.ntiles, (int)R, R == 1 ? rowmap : nullptr, out, sc.max_seg_len / kTile + 2, st);
 }
 
 hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *c1, const int32_t *c2,

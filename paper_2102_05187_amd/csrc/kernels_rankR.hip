@@ -5,6 +5,8 @@ namespace comet {
 
 namespace {
 
+// ROWMAP: segment s writes result row rowmap[s]; the tail map then holds rows, and so do the ids this kernel
+// publishes in its carries (the fix-up takes them as rows).
 // HEAVY: segments of at least heavy_len nonzeros belong to the heavy-row sweep: their nonzeros are skipped
 // (no gather, nothing added) and their rows are not written.
 template <int L, int V, bool WIDE, bool ROWMAP, bool HEAVY>
@@ -38,7 +40,7 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
     }
     LaneItems cur;
     lane_load_items(cur, crd, vals, gb + 4 * j, nnz);             // in flight while the map is built
-    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, R, HEAVY ? heavy_len : 0, nseg);
+    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, R, HEAVY ? heavy_len : 0, nseg, ROWMAP);
 
     WalkState<V> st;
 #pragma unroll
@@ -98,7 +100,7 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
                         st.first_id = b.tail;
                         st.ht = 1;
                     } else {
-                        const unsigned row = ROWMAP ? (unsigned)rowmap[b.tail] : (unsigned)b.tail;
+                        const unsigned row = (unsigned)b.tail;
                         grp_store_row_stream<L, V, WIDE>(reinterpret_cast<double *>(outb + (size_t)row * R8), 0, R, j, st.acc);
                     }
 #pragma unroll
@@ -123,7 +125,7 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
         if (j == 0) wht[g] = st.ht;
     }
     __syncthreads();
-    const int64_t first_row = st.ht ? (ROWMAP ? (int64_t)rowmap[st.first_id] : (int64_t)st.first_id) : 0;
+    const int64_t first_row = st.ht ? (int64_t)st.first_id : 0;
     finish_tile_walkers<L, V, WIDE>(wopen, wht, g, j, st.ht, st.first, first_row, st.first_id, st.acc, out, R,
                                     carry_view(scratch, ntiles, R), t);
 }

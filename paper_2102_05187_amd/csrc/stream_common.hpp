@@ -69,11 +69,14 @@ __host__ __device__ inline CarryView carry_view(void *scratch, int64_t n, int64_
 // item of the next tile ends later), so each of them owns exactly one map entry.
 // heavy_len > 0: segments of at least heavy_len nonzeros are left to another kernel -- they get no map
 // entry (their result row is not written here) and their items inside the tile are marked kSkipItem.
+// rows_in_map: the entry of a segment end is the segment's result row rowmap[s] instead of s (looked up here by
+// all threads at once, so that the walk has no dependent load at a segment end); ids are opaque to the fix-up.
 constexpr int32_t kSkipItem = -2;
 __device__ __forceinline__ void build_tail_map_from_pos(int32_t *ts, const int32_t *__restrict__ pos,
                                                         const int32_t *__restrict__ rowmap, int64_t tb, int32_t s0,
                                                         int32_t s1, double *__restrict__ out, int R,
-                                                        int32_t heavy_len = 0, int32_t nseg = 0) {
+                                                        int32_t heavy_len = 0, int32_t nseg = 0,
+                                                        bool rows_in_map = false) {
     __shared__ int hv_lo[24], hv_hi[24], hv_n;      // heavy pieces inside the tile: at most kTile / heavy_len + 2
     if (threadIdx.x == 0) hv_n = 0;
     for (int i = threadIdx.x * 4; i < kTile; i += blockDim.x * 4)
@@ -85,7 +88,7 @@ __device__ __forceinline__ void build_tail_map_from_pos(int32_t *ts, const int32
             const int k = atomicAdd(&hv_n, 1);
             if (k < 24) { hv_lo[k] = (int64_t)b > tb ? (int)((int64_t)b - tb) : 0; hv_hi[k] = (int)((int64_t)e - tb); }
         } else if (e > b) {
-            ts[(int64_t)e - 1 - tb] = s;
+            ts[(int64_t)e - 1 - tb] = rows_in_map ? rowmap[s] : s;
         } else {
             int64_t row = rowmap ? (int64_t)rowmap[s] : (int64_t)s;
             for (int r = 0; r < R; ++r) out[row * R + r] = 0.0;

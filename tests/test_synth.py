@@ -74,3 +74,31 @@ def test_mttkrp_factors_share_columns_across_ranks():
     a = gen.config_mttkrp(seed=0, scale=1e-5, R=16, chunk=1 << 14)
     b = gen.config_mttkrp(seed=0, scale=1e-5, R=64, chunk=1 << 14)
     assert torch.equal(a["B"], b["B"][:, :16]) and torch.equal(a["C"], b["C"][:, :16])
+
+
+def test_lexi_relabel_renames_indices_and_orders_by_first_nonzero():
+    """synth/lexi.py (Section 7 of the paper, reordering): the relabelled tensor is the same tensor under one
+    permutation per mode, and after the iteration for a mode its indices are numbered in the order in which they
+    first appear when the nonzeros are sorted by the other modes."""
+    from synth import lexi
+    dims = (7, 5, 6)
+    i, j, k, vals = gen.bernoulli_tensor3(dims, 0.2, seed=3)
+    (ni, nj, nk), labels = lexi.lexi_relabel((i, j, k), dims, sweeps=2)
+    for n, d in enumerate(dims):
+        assert sorted(labels[n].tolist()) == list(range(d))           # a permutation of the mode's indices
+    dense = torch.zeros(dims, dtype=torch.float64)
+    dense[i, j, k] = vals
+    moved = torch.zeros(dims, dtype=torch.float64)
+    moved[ni, nj, nk] = vals
+    assert torch.equal(moved[labels[0]][:, labels[1]][:, :, labels[2]], dense)
+    # hand example, one iteration for the rows of a 4 x 4 matrix: rows sorted by their smallest column
+    rows = torch.tensor([0, 0, 1, 2, 3, 3])
+    cols = torch.tensor([2, 3, 0, 1, 0, 3])
+    (nr, nc), lab = lexi.lexi_relabel((rows, cols), (4, 4), sweeps=1)
+    # rows: first appearance in column order: col 0 -> rows 1, 3; col 1 -> row 2; col 2 -> row 0
+    assert lab[0].tolist() == [3, 0, 2, 1]
+    # columns, with the new row labels (row 0 = old 1 has col 0; row 1 = old 3 has cols 0, 3; row 2 = old 2 has col 1; row 3 = old 0 has cols 2, 3)
+    assert lab[1].tolist() == [0, 2, 3, 1]
+    (sr, sc), sv = lexi.sort_nonzeros((nr, nc), (4, 4), torch.arange(6, dtype=torch.float64))
+    key = (sr * 4 + sc).tolist()
+    assert key == sorted(key) and len(set(key)) == 6
