@@ -10,8 +10,9 @@ namespace {
 // B[crd2[fiber], :] when the fiber ends and folded into the slice accumulator.  Scaling is linear,
 // so a fiber cut by a walker or tile boundary is folded piecewise (each piece times the same B row);
 // only the slice level needs carries.  Outer level: slices (segments of pos2); a slice end writes
-// row crd1[slice] of M.  Two LDS maps, both keyed by tile item: ts = fiber id at a fiber's last
-// nonzero, tm = output row at a slice's last nonzero (-1 elsewhere).
+// row crd1[slice] of M.  Two LDS maps, both keyed by tile item: ts = the fiber's coordinate crd2[fiber]
+// (its row of B) at a fiber's last nonzero, tm = output row at a slice's last nonzero (-1 elsewhere).  Both
+// are looked up while the maps are built, with coalesced loads, so that the walk has no dependent index load.
 template <int L, int V, bool WIDE>
 __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict__ pos2, const int32_t *__restrict__ crd1,
                                                        const int32_t *__restrict__ pos3, const int32_t *__restrict__ crd2,
@@ -26,7 +27,7 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
     constexpr int kOpenInts = 256 * V * 2;
     constexpr int kLdsInts = kMapInts > kOpenInts ? kMapInts : kOpenInts;
     __shared__ __attribute__((aligned(16))) int32_t lds[kLdsInts];
-    __shared__ int wht[NW], wfirst_fid[NW];
+    __shared__ int wht[NW], wfirst_j[NW];
     int32_t *ts = lds, *tm = lds + kTile;
     double *wopen = reinterpret_cast<double *>(lds);              // reused once the maps are dead
     const int64_t t = blockIdx.x;
@@ -41,7 +42,7 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
     __syncthreads();
     for (int32_t f = seg_begin[t] + threadIdx.x; f < seg_begin[t + 1]; f += blockDim.x) {
         int32_t b = pos3[f], e = pos3[f + 1];
-        if (e > b) ts[(int64_t)e - 1 - tb] = f;
+        if (e > b) ts[(int64_t)e - 1 - tb] = crd2[f];
     }
     for (int32_t sl = slice_begin[t] + threadIdx.x; sl < slice_begin[t + 1]; sl += blockDim.x) {
         int32_t fb = pos2[sl], fe = pos2[sl + 1];
@@ -61,7 +62,7 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
     double facc[V], sacc[V], first[V];
 #pragma unroll
     for (int q = 0; q < V; ++q) { facc[q] = 0.0; sacc[q] = 0.0; first[q] = 0.0; }
-    int ht = 0, first_row = -1, first_fid = -1, last_is_tail = 1;
+    int ht = 0, first_row = -1, first_j = -1, last_is_tail = 1;
 
     // narrow rows: two steps per pipeline group instead of four keeps the kernel under 128 registers
     // (four wavefronts per SIMD instead of three), which is worth more here than the deeper gather queue
@@ -70,15 +71,13 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
         const int64_t i0 = gb + SB * sb + 4 * j;
         LaneItems nxt;
         if (sb + 1 < WI / SB) lane_load_items(nxt, crd3, vals, i0 + SB, nnz);
-        int tl[4], tr[4], jb[4];
+        int tl[4], tr[4];
         {
             const int4 t4 = *reinterpret_cast<const int4 *>(ts + (i0 - tb));
             const int4 m4 = *reinterpret_cast<const int4 *>(tm + (i0 - tb));
             tl[0] = t4.x; tl[1] = t4.y; tl[2] = t4.z; tl[3] = t4.w;
             tr[0] = m4.x; tr[1] = m4.y; tr[2] = m4.z; tr[3] = m4.w;
         }
-#pragma unroll
-        for (int s = 0; s < 4; ++s) jb[s] = tl[s] >= 0 ? crd2[tl[s]] : 0;      // B row of a fiber that ends here
         const bool any_item = gb + SB * sb < nnz;
         RowBuf<V> cbuf[2][G], bbuf[2][G];
         auto issue = [&](auto gc, RowBuf<V> *cb_, RowBuf<V> *bb_) {
@@ -88,10 +87,13 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
                 const int c = grp_bcast_i<L, k / 4>(cur.cr[k % 4]);
                 grp_load_row<L, V, WIDE>(Cm, c, R, j, cb_[s_].d);
                 const int tf = grp_bcast_i<L, k / 4>(tl[k % 4]);
-                if (tf >= 0) {                                    // the fiber ends here: its B row is needed too
-                    const int jrow = grp_bcast_i<L, k / 4>(jb[k % 4]);
-                    grp_load_row<L, V, WIDE>(Bm, jrow, R, j, bb_[s_].d);
-                }
+                // The B row is needed where a fiber ends.  Narrow rows: loaded at every item (row 0, a cache hit,
+                // where no fiber ends), so that the number of loads in flight is fixed and the gathers of the next
+                // group really overlap these FMAs (a load under a branch makes the wait for the rows of this group
+                // cover part of the next group's loads): 1.74 -> 1.61 ms at rank 16.  Wide rows pay more for the
+                // extra load instructions than they gain (5.18 -> 5.32 ms at rank 64) and keep the branch.
+                if constexpr (V <= 2) grp_load_row<L, V, WIDE>(Bm, tf >= 0 ? tf : 0, R, j, bb_[s_].d);
+                else if (tf >= 0) grp_load_row<L, V, WIDE>(Bm, tf, R, j, bb_[s_].d);
             });
         };
         auto consume = [&](auto gc, const RowBuf<V> *cb_, const RowBuf<V> *bb_) {
@@ -105,7 +107,7 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
                 for (int q = 0; q < V; ++q) facc[q] = fma(a, cb_[s_].d[q], facc[q]);
                 if (any_item) last_is_tail = tf >= 0;
                 if (tf >= 0) {
-                    if (first_fid < 0) first_fid = tf;
+                    if (first_j < 0) first_j = tf;
 #pragma unroll
                     for (int q = 0; q < V; ++q) { sacc[q] = fma(bb_[s_].d[q], facc[q], sacc[q]); facc[q] = 0.0; }
                     if (tmr >= 0) {
@@ -133,14 +135,15 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
 
     // A fiber left open at the end of this walker's range ends at the next fiber end of the tile, or,
     // if there is none, it is the fiber that contains the first nonzero of the next tile.
-    if (j == 0) wfirst_fid[g] = first_fid;
+    if (j == 0) wfirst_j[g] = first_j;
     __syncthreads();                                              // also: every walk is done, the maps are dead
     if (!last_is_tail) {
-        int64_t fid = seg_begin[t + 1];
-        for (int g2 = g + 1; g2 < NW; ++g2) { int f2 = wfirst_fid[g2]; if (f2 >= 0) { fid = f2; break; } }
-        if (fid < nfib) {
+        int jrow = -1;
+        for (int g2 = g + 1; g2 < NW; ++g2) { const int j2 = wfirst_j[g2]; if (j2 >= 0) { jrow = j2; break; } }
+        if (jrow < 0 && (int64_t)seg_begin[t + 1] < nfib) jrow = crd2[seg_begin[t + 1]];
+        if (jrow >= 0) {
             double bw[V];
-            grp_load_row<L, V, WIDE>(Bm, crd2[fid], R, j, bw);
+            grp_load_row<L, V, WIDE>(Bm, jrow, R, j, bw);
 #pragma unroll
             for (int q = 0; q < V; ++q) sacc[q] = fma(bw[q], facc[q], sacc[q]);
         }
