@@ -250,8 +250,10 @@ def run_op(op, args, comet, dev):
         flops = 2 * R * nnz
         nbytes = 12 * nnz + (4 + 8 * R) * n + 8 * R * touched
         desc = "SpMM %s %dx%d, %d nnz, Zipf(1.8) rows capped at 10000, B %dx%d" % ("CSR" if op == "spmm" else "DCSR", n, n, nnz, n, R)
+        hrows, hnnz = A.heavy_plan()
         extra = {"nnz": nnz, "rows": n, "R": R, "touched_B_rows": touched, "gather_bytes": 8 * R * nnz,
-                 "touched_row_bytes": 8 * R * touched}
+                 "touched_row_bytes": 8 * R * touched, "heavy_rows": hrows, "heavy_nnz": hnnz,
+                 "heavy_stream_bytes": A.heavy_stream_bytes()}
         keep = dict(A=A, L=L, B=B, C=C, coo=(rows, cols, vals), n=n)
     else:
         full_op, mode_n = op, None

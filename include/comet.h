@@ -81,6 +81,7 @@ typedef struct {
                                                  * dims / levels / pos / crd above are per LEVEL    */
     int64_t        heavy_rows;                /* schedule: rows that comet_spmm hands to its heavy-row sweep */
     int64_t        heavy_nnz;                 /* ... and the nonzeros they hold (both 0: no sweep planned)   */
+    int64_t        heavy_stream_bytes;        /* device memory of the sweep's re-ordered copy of those rows   */
 } comet_tensor_info_t;
 
 /*

@@ -50,7 +50,8 @@ class _Info(ctypes.Structure):
                 ("nvals", ctypes.c_int64),
                 ("mode_of_level", ctypes.c_int32 * COMET_MAX_ORDER),
                 ("heavy_rows", ctypes.c_int64),
-                ("heavy_nnz", ctypes.c_int64)]
+                ("heavy_nnz", ctypes.c_int64),
+                ("heavy_stream_bytes", ctypes.c_int64)]
 
 
 _LIB = None
@@ -163,6 +164,10 @@ class Tensor:
         """(rows, nonzeros) that comet_spmm hands to its heavy-row sweep; (0, 0) when none is planned."""
         inf = self.info()
         return int(inf.heavy_rows), int(inf.heavy_nnz)
+
+    def heavy_stream_bytes(self) -> int:
+        """Device memory held by the re-ordered copy of the heavy rows that the sweep reads (0: no sweep planned)."""
+        return int(self.info().heavy_stream_bytes)
 
     def mode_dims(self) -> List[int]:
         """Sizes indexed by tensor mode (dims() is indexed by level)."""

@@ -420,6 +420,7 @@ comet_status comet_tensor_info(const comet_tensor *t, comet_tensor_info_t *info)
     info->nvals = t->nvals;
     info->heavy_rows = t->sched.heavy.nunits > 0 ? t->sched.heavy.nheavy : 0;
     info->heavy_nnz = t->sched.heavy.nunits > 0 ? t->sched.heavy.heavy_nnz : 0;
+    info->heavy_stream_bytes = t->sched.heavy.nunits > 0 ? t->sched.heavy.stream_items * 16 : 0;
     return COMET_OK;
 }
 
