@@ -246,6 +246,21 @@ comet_status comet_ttm(const comet_tensor *X, int mode, const double *U, int64_t
 comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *factors,
                           int64_t R, double *M, void *stream);
 
+/* Scaled and accumulating forms of the three products with a dense result (Section 6.2 Step III: the
+ * generated code accumulates into the output, "C[...] += A[...] * B[...]"; alpha and beta are the usual
+ * generalisation):
+ *     y = alpha A x + beta y        C = alpha A B + beta C        M = alpha X_(mode) (C (.) B) + beta M
+ * Arguments as for comet_spmv / comet_spmm / comet_mttkrp; the result array is read and written in place.
+ * beta == 0: the old contents of the result are not read (they may be NaN); alpha == 0: the product is not
+ * formed and the operands are not read.  beta == 1 accumulates.  The scaling is fused into the kernels'
+ * stores (each result element is read and written once); rows that receive no contribution (empty rows,
+ * rows absent from a compressed root level) become beta times their old value. */
+comet_status comet_spmv_axpby(const comet_tensor *A, double alpha, const double *x, double beta, double *y, void *stream);
+comet_status comet_spmm_axpby(const comet_tensor *A, double alpha, const double *B, int64_t R, double beta, double *C,
+                              void *stream);
+comet_status comet_mttkrp_axpby(const comet_tensor *X, int mode, double alpha, const double *const *factors, int64_t R,
+                                double beta, double *M, void *stream);
+
 /* Human-readable name of a status (static string). */
 const char *comet_status_string(comet_status s);
 

@@ -87,6 +87,17 @@ def spmm(rows, cols, vals, shape: Sequence[int], U) -> Tuple[np.ndarray, np.ndar
     return Y, Ya
 
 
+def axpby(alpha: float, prod, prod_abs, beta: float, old) -> Tuple[np.ndarray, np.ndarray]:
+    """alpha * prod + beta * old element by element (the in-place update of Section 6.2, Step III, with the usual
+    two scalars); beta == 0 does not read `old`, alpha == 0 does not read `prod`.  Returns (result, sum of |terms|)."""
+    prod, prod_abs, old = _f64(prod), _f64(prod_abs), _f64(old)
+    assert prod.shape == prod_abs.shape == old.shape
+    out, out_abs = np.empty(prod.shape), np.empty(prod.shape)
+    _check(_load().oracle_axpby(_I64(prod.size), ctypes.c_double(alpha), _p(prod), _p(prod_abs), ctypes.c_double(beta),
+                                _p(old), _p(out), _p(out_abs)), "axpby")
+    return out, out_abs
+
+
 def group_pairs(ci, cj) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
     """Distinct (i, j) pairs in lexicographic order: (gid per nonzero, gi, gj)."""
     ci, cj = _i32(ci), _i32(cj)

@@ -176,6 +176,23 @@ int oracle_mttkrp(i64 nnz, const int32_t *ci, const int32_t *cj, const int32_t *
     return 0;
 }
 
+/* Scaled / accumulating result: out = alpha * prod + beta * old, element by element.  Step III of the
+ * code generation algorithm (Section 6.2) updates the output element in place, i.e. the product is added
+ * to what the output holds (beta = 1); alpha and beta generalise that the usual way.  beta == 0: `old` is
+ * not read (it may hold NaN); alpha == 0: `prod` is not read.  out_abs = |alpha| * prod_abs + |beta * old|
+ * is the sum of absolute values of everything that was added, for the error bound of a comparison. */
+int oracle_axpby(i64 n, double alpha, const double *prod, const double *prod_abs, double beta,
+                 const double *old, double *out, double *out_abs) {
+    for (i64 p = 0; p < n; ++p) {
+        double v = 0.0, a = 0.0;
+        if (alpha != 0.0) { v = alpha * prod[p]; a = fabs(alpha) * prod_abs[p]; }
+        if (beta != 0.0) { const double o = beta * old[p]; v = v + o; a += fabs(o); }
+        out[p] = v;
+        out_abs[p] = a;
+    }
+    return 0;
+}
+
 /* ------------------------------------------------------------------------------------------
  * Level walker (Section 4; Table "Generated code to access nonzeros coordinates").
  *

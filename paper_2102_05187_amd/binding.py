@@ -28,7 +28,8 @@ _STATUS_NAMES = {0: "COMET_OK", 1: "COMET_ERR_INVALID_ARG", 2: "COMET_ERR_BAD_FO
 EXPORTS = ["comet_tensor_create", "comet_tensor_destroy", "comet_tensor_info", "comet_spmv", "comet_spmm",
            "comet_ttv", "comet_ttm", "comet_mttkrp", "comet_status_string", "comet_tensor_set_variant",
            "comet_tensor_reorder", "comet_tensor_convert", "comet_tensor_reserve", "comet_spmv_static",
-           "comet_calibrate_read", "comet_calibrate_gather"]
+           "comet_calibrate_read", "comet_calibrate_gather", "comet_spmv_axpby", "comet_spmm_axpby",
+           "comet_mttkrp_axpby"]
 
 
 class CometError(RuntimeError):
@@ -77,6 +78,10 @@ def _lib():
         lib.comet_ttv.argtypes = [vp, ci, vp, ctypes.POINTER(vp), vp]
         lib.comet_ttm.argtypes = [vp, ci, vp, i64, ctypes.POINTER(vp), vp]
         lib.comet_mttkrp.argtypes = [vp, ci, vp, i64, vp, vp]
+        f64 = ctypes.c_double
+        lib.comet_spmv_axpby.argtypes = [vp, f64, vp, f64, vp, vp]
+        lib.comet_spmm_axpby.argtypes = [vp, f64, vp, i64, f64, vp, vp]
+        lib.comet_mttkrp_axpby.argtypes = [vp, ci, f64, vp, i64, f64, vp, vp]
         lib.comet_tensor_set_variant.argtypes = [vp, ci]
         lib.comet_tensor_reorder.argtypes = [vp, vp, ctypes.POINTER(vp), vp]
         lib.comet_tensor_convert.argtypes = [vp, vp, vp, ctypes.POINTER(vp), vp]
@@ -277,6 +282,32 @@ def comet_spmv(A: Tensor, x: torch.Tensor, y: Optional[torch.Tensor] = None, str
     return y
 
 
+def comet_spmv_axpby(A: Tensor, alpha: float, x: torch.Tensor, beta: float, y: torch.Tensor, stream=None) -> torch.Tensor:
+    """y = alpha * A x + beta * y, in place."""
+    x, y = _dev(x, torch.float64, "x"), _dev(y, torch.float64, "y")
+    if len(A.dims()) != 2:
+        raise CometError(4, "comet_spmv_axpby")
+    I, J = A.dims()
+    if x.numel() != J or y.numel() != I:
+        raise CometError(3, "comet_spmv_axpby")
+    _check(_lib().comet_spmv_axpby(A.handle, float(alpha), x.data_ptr(), float(beta), y.data_ptr(), _stream(stream)),
+           "comet_spmv_axpby")
+    return y
+
+
+def comet_spmm_axpby(A: Tensor, alpha: float, B: torch.Tensor, beta: float, C: torch.Tensor, stream=None) -> torch.Tensor:
+    """C = alpha * A B + beta * C, in place."""
+    B, C = _dev(B, torch.float64, "B"), _dev(C, torch.float64, "C")
+    if len(A.dims()) != 2:
+        raise CometError(4, "comet_spmm_axpby")
+    I, J = A.dims()
+    if B.dim() != 2 or B.shape[0] != J or tuple(C.shape) != (I, B.shape[1]):
+        raise CometError(3, "comet_spmm_axpby")
+    _check(_lib().comet_spmm_axpby(A.handle, float(alpha), B.data_ptr(), B.shape[1], float(beta), C.data_ptr(),
+                                   _stream(stream)), "comet_spmm_axpby")
+    return C
+
+
 def comet_spmv_static(A: Tensor, x: torch.Tensor, y: torch.Tensor, stream=None) -> torch.Tensor:
     """comet_spmv for callers that cannot allocate: the caller passes y, the library's scratch is static."""
     x, y = _dev(x, torch.float64, "x"), _dev(y, torch.float64, "y")
@@ -366,6 +397,31 @@ def comet_mttkrp(X: Tensor, mode: int, factors: Sequence[Optional[torch.Tensor]]
         raise CometError(3, "comet_mttkrp")
     c_f = (ctypes.c_void_p * 3)(*[_ptr(f) for f in fs])
     _check(_lib().comet_mttkrp(X.handle, mode, c_f, R, M.data_ptr(), _stream(stream)), "comet_mttkrp")
+    return M
+
+
+def comet_mttkrp_axpby(X: Tensor, mode: int, alpha: float, factors: Sequence[Optional[torch.Tensor]], beta: float,
+                       M: torch.Tensor, stream=None) -> torch.Tensor:
+    """M = alpha * MTTKRP(X, factors) + beta * M, in place."""
+    dims = X.mode_dims()
+    if len(dims) != 3 or len(factors) != 3:
+        raise CometError(4, "comet_mttkrp_axpby")
+    fs = [None if (f is None or l == mode) else _dev(f, torch.float64, "factors[%d]" % l) for l, f in enumerate(factors)]
+    R = None
+    for l, f in enumerate(fs):
+        if f is None:
+            continue
+        if f.dim() != 2 or f.shape[0] != dims[l] or (R is not None and f.shape[1] != R):
+            raise CometError(3, "comet_mttkrp_axpby")
+        R = f.shape[1]
+    if R is None or not (0 <= mode < 3):
+        raise CometError(1, "comet_mttkrp_axpby")
+    M = _dev(M, torch.float64, "M")
+    if tuple(M.shape) != (dims[mode], R):
+        raise CometError(3, "comet_mttkrp_axpby")
+    c_f = (ctypes.c_void_p * 3)(*[_ptr(f) for f in fs])
+    _check(_lib().comet_mttkrp_axpby(X.handle, mode, float(alpha), c_f, R, float(beta), M.data_ptr(), _stream(stream)),
+           "comet_mttkrp_axpby")
     return M
 
 

@@ -665,8 +665,10 @@ static comet_status ensure_shadow(const comet_tensor *X, hipStream_t st) {
 
 // ---- SpMV / SpMM: the last level is compressed; rows come from a dense or compressed root -------
 // ext_scratch != nullptr: the caller supplies the carry scratch (ext_bytes of it) and nothing may be allocated.
+// ep: what the kernels do with a finished element (off: out = A * Dn; on: out = alpha * A * Dn + beta * out).
 static comet_status matrix_product(const comet_tensor *A, const double *Dn, int64_t R, double *out, hipStream_t st,
-                                   void *ext_scratch = nullptr, size_t ext_bytes = 0) {
+                                   void *ext_scratch = nullptr, size_t ext_bytes = 0,
+                                   comet::Epilogue ep = comet::Epilogue()) {
     if (!A || !Dn || !out) return COMET_ERR_INVALID_ARG;
     note_stream(A, st);
     if (A->fmt == Format::COO2) {
@@ -695,11 +697,16 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
         // the gaps between them are cleared; otherwise, or when there is nothing to run, the whole result.
         rowmap = A->crd_i(0);
         const int64_t nstored = A->crd_len[0];
-        if (nnz > 0 && gaps_are_short(A, R)) HIP_TRY(comet::zero_unstored_rows(rowmap, nstored, A->dims[0], R, out, st));
-        else HIP_TRY(comet::fill_zero_f64(out, A->dims[0] * R, st));
+        if (nnz > 0 && gaps_are_short(A, R)) {
+            HIP_TRY(comet::zero_unstored_rows(rowmap, nstored, A->dims[0], R, out, st, ep.on ? ep.beta : 0.0));
+        } else {
+            // every element is cleared (scaled by beta) here, so the kernels add to what they find
+            HIP_TRY(comet::scale_f64(out, A->dims[0] * R, ep.on ? ep.beta : 0.0, st));
+            if (ep.on && ep.beta != 0.0) ep.beta = 1.0;
+        }
     }
     if (nnz == 0) {
-        if (A->fmt == Format::CSR) HIP_TRY(comet::fill_zero_f64(out, A->dims[0] * R, st));
+        if (A->fmt == Format::CSR) HIP_TRY(comet::scale_f64(out, A->dims[0] * R, ep.on ? ep.beta : 0.0, st));
         return COMET_OK;
     }
     if (tiled) {
@@ -710,13 +717,20 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
             scr = A->scratch->ptr;
         }
         HIP_TRY(comet::stream_segreduce(A->sched, A->pos_i(1), A->crd_i(1), A->vals_d(), rowmap, Dn, A->dims[1], R, out,
-                                        scr, A->variant == 3, st, heavy ? A->sched.heavy.min_len : 0));
+                                        scr, A->variant == 3, st, heavy ? A->sched.heavy.min_len : 0, ep));
         if (heavy)
-            HIP_TRY(comet::heavy_spmm(A->sched.heavy, rowmap, Dn, R, out, (char *)scr + carry, st));
+            HIP_TRY(comet::heavy_spmm(A->sched.heavy, rowmap, Dn, R, out, (char *)scr + carry, st, ep));
         return COMET_OK;
     }
-    HIP_TRY(comet::simple_segreduce(A->pos_i(1), A->crd_i(1), A->vals_d(), nseg, nnz, rowmap, Dn, R, out, st));
+    HIP_TRY(comet::simple_segreduce(A->pos_i(1), A->crd_i(1), A->vals_d(), nseg, nnz, rowmap, Dn, R, out, st, ep));
     return COMET_OK;
+}
+
+// alpha == 0: the product is not formed at all (the operands may hold anything), the result is beta * out.
+static comet::Epilogue make_epilogue(double alpha, double beta) {
+    comet::Epilogue ep;
+    ep.alpha = alpha; ep.beta = beta; ep.on = 1;
+    return ep;
 }
 
 comet_status comet_spmv(const comet_tensor *A, const double *x, double *y, void *stream) {
@@ -725,6 +739,29 @@ comet_status comet_spmv(const comet_tensor *A, const double *x, double *y, void 
 
 comet_status comet_spmm(const comet_tensor *A, const double *B, int64_t R, double *C, void *stream) {
     return matrix_product(A, B, R, C, (hipStream_t)stream);
+}
+
+comet_status comet_spmv_axpby(const comet_tensor *A, double alpha, const double *x, double beta, double *y, void *stream) {
+    if (!A || !y) return COMET_ERR_INVALID_ARG;
+    if (alpha == 0.0) {
+        if (A->order != 2) return COMET_ERR_UNSUPPORTED;
+        note_stream(A, (hipStream_t)stream);
+        HIP_TRY(comet::scale_f64(y, A->dims[0], beta, (hipStream_t)stream));
+        return COMET_OK;
+    }
+    return matrix_product(A, x, 1, y, (hipStream_t)stream, nullptr, 0, make_epilogue(alpha, beta));
+}
+
+comet_status comet_spmm_axpby(const comet_tensor *A, double alpha, const double *B, int64_t R, double beta, double *C,
+                              void *stream) {
+    if (!A || !C) return COMET_ERR_INVALID_ARG;
+    if (alpha == 0.0) {
+        if (A->order != 2 || R < 1 || R > 1024) return COMET_ERR_UNSUPPORTED;
+        note_stream(A, (hipStream_t)stream);
+        HIP_TRY(comet::scale_f64(C, A->dims[0] * R, beta, (hipStream_t)stream));
+        return COMET_OK;
+    }
+    return matrix_product(A, B, R, C, (hipStream_t)stream, nullptr, 0, make_epilogue(alpha, beta));
 }
 
 // ---- SpMV for callers that cannot allocate --------------------------------------------------------
@@ -864,8 +901,8 @@ comet_status comet_ttm(const comet_tensor *X, int mode, const double *U, int64_t
     return leaf_contract(X, mode, U, R, 2, Y, (hipStream_t)stream);
 }
 
-comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *factors, int64_t R, double *M,
-                          void *stream) {
+static comet_status mttkrp_impl(const comet_tensor *X, int mode, const double *const *factors, int64_t R, double *M,
+                                void *stream, comet::Epilogue ep) {
     if (!X || !factors || !M) return COMET_ERR_INVALID_ARG;
     note_stream(X, (hipStream_t)stream);
     if (X->fmt == Format::COO3) {
@@ -890,19 +927,41 @@ comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *
     // Rows of M whose index is not stored at the root level receive no contribution.  The tiled kernel
     // writes every stored slice's row itself (a slice without nonzeros is cleared in its slice pass), so
     // when most rows are stored only the gaps between them are cleared; otherwise all of M is.
-    if (tiled && gaps_are_short(X, R)) HIP_TRY(comet::zero_unstored_rows(X->crd_i(0), nslice, X->dims[0], R, M, st));
-    else HIP_TRY(comet::fill_zero_f64(M, X->dims[0] * R, st));
+    if (tiled && gaps_are_short(X, R)) {
+        HIP_TRY(comet::zero_unstored_rows(X->crd_i(0), nslice, X->dims[0], R, M, st, ep.on ? ep.beta : 0.0));
+    } else {
+        // every element is cleared (scaled by beta) here, so the kernels add to what they find
+        HIP_TRY(comet::scale_f64(M, X->dims[0] * R, ep.on ? ep.beta : 0.0, st));
+        if (ep.on && ep.beta != 0.0) ep.beta = 1.0;
+    }
     if (X->nvals == 0) return COMET_OK;
     if (tiled) {
         comet_status rs = ensure_scratch(X, comet::stream_scratch_bytes(X->sched.ntiles, R));
         if (rs != COMET_OK) return rs;
         HIP_TRY(comet::stream_mttkrp(X->sched, X->pos_i(1), X->crd_i(0), nslice, X->pos_i(2), X->crd_i(1),
-                                     X->crd_i(2), X->vals_d(), B, C, R, M, X->scratch->ptr, st));
+                                     X->crd_i(2), X->vals_d(), B, C, R, M, X->scratch->ptr, st, ep));
         return COMET_OK;
     }
     HIP_TRY(comet::simple_mttkrp(X->pos_i(1), X->crd_i(0), X->pos_len[1] - 1, X->pos_i(2), X->crd_i(1), X->crd_i(2),
-                                 X->vals_d(), B, C, R, M, st));
+                                 X->vals_d(), B, C, R, M, st, ep));
     return COMET_OK;
+}
+
+comet_status comet_mttkrp(const comet_tensor *X, int mode, const double *const *factors, int64_t R, double *M,
+                          void *stream) {
+    return mttkrp_impl(X, mode, factors, R, M, stream, comet::Epilogue());
+}
+
+comet_status comet_mttkrp_axpby(const comet_tensor *X, int mode, double alpha, const double *const *factors, int64_t R,
+                                double beta, double *M, void *stream) {
+    if (!X || !M) return COMET_ERR_INVALID_ARG;
+    if (alpha == 0.0) {
+        if (X->order != 3 || mode != X->mode_of_level[0] || R < 1 || R > 1024) return COMET_ERR_UNSUPPORTED;
+        note_stream(X, (hipStream_t)stream);
+        HIP_TRY(comet::scale_f64(M, X->dims[0] * R, beta, (hipStream_t)stream));
+        return COMET_OK;
+    }
+    return mttkrp_impl(X, mode, factors, R, M, stream, make_epilogue(alpha, beta));
 }
 
 }  // extern "C"

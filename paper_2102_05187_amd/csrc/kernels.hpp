@@ -7,10 +7,30 @@
 
 namespace comet {
 
+// What a kernel does with a finished result element: off = store the value; on = store
+// alpha * value + beta * (what the element held before).  The old element is not read when beta is 0,
+// so it may hold anything then (NaN included), as in the BLAS convention.
+struct Epilogue {
+    double alpha = 1.0, beta = 0.0;
+    int on = 0;
+};
+__device__ __forceinline__ double ep_apply(const Epilogue &ep, double v, const double *p) {
+    if (!ep.on) return v;
+    return ep.beta != 0.0 ? fma(ep.alpha, v, ep.beta * *p) : ep.alpha * v;
+}
+// What an element without any contribution becomes under the same rule.
+__device__ __forceinline__ double ep_empty(const Epilogue &ep, const double *p) {
+    return (ep.on && ep.beta != 0.0) ? ep.beta * *p : 0.0;
+}
+
 // ---- utilities (util.hip) -----------------------------------------------------------------------
 hipError_t fill_zero_f64(double *p, int64_t n, hipStream_t st);
+// p[i] = beta * p[i] (beta == 0: p[i] = 0 without reading it).
+hipError_t scale_f64(double *p, int64_t n, double beta, hipStream_t st);
 // out[r, :] = 0 for every row r of [0, nrows) that does not occur in the sorted, duplicate-free list idx[0..n).
-hipError_t zero_unstored_rows(const int32_t *idx, int64_t n, int64_t nrows, int64_t R, double *out, hipStream_t st);
+// beta != 0: those rows are multiplied by beta instead.
+hipError_t zero_unstored_rows(const int32_t *idx, int64_t n, int64_t nrows, int64_t R, double *out, hipStream_t st,
+                              double beta = 0.0);
 
 // Structure checks; each ORs a bit into *err (device int32, zeroed by the caller) on failure.
 hipError_t check_pos(const int32_t *pos, int64_t n, int64_t last, int32_t *err, hipStream_t st);
@@ -39,11 +59,11 @@ hipError_t max_parent_span(const int32_t *parent_pos, int64_t nparent, const int
 // row(s) = rowmap ? rowmap[s] : s.   R == 1 reads Dn as a vector.
 hipError_t simple_segreduce(const int32_t *pos, const int32_t *crd, const double *vals, int64_t nseg,
                             int64_t nnz, const int32_t *rowmap, const double *Dn, int64_t R, double *out,
-                            hipStream_t st);
+                            hipStream_t st, Epilogue ep = Epilogue());
 // M[crd1[s], :] = sum_{f in slice s} B[crd2[f], :] * (sum_{p in fiber f} vals[p] * C[crd3[p], :])
 hipError_t simple_mttkrp(const int32_t *pos2, const int32_t *crd1, int64_t nslice, const int32_t *pos3,
                          const int32_t *crd2, const int32_t *crd3, const double *vals, const double *B,
-                         const double *C, int64_t R, double *M, hipStream_t st);
+                         const double *C, int64_t R, double *M, hipStream_t st, Epilogue ep = Epilogue());
 // Sorted COO [CN,S,S]: distinct (i,j) runs -> ycrd0/ycrd1/yvals (run_base from the schedule).
 hipError_t simple_ttv_coo(const int32_t *c0, const int32_t *c1, const int32_t *c2, const double *vals,
                           int64_t nnz, int tile, int64_t ntiles, const int32_t *run_base, const double *v,

@@ -313,7 +313,8 @@ __global__ void __launch_bounds__(kHeavyThreads) k_heavy_sweep(const int32_t *__
 // out[row(h), r] = sum over the units of heavy row h, and over the column ranges, of the partial rows
 __global__ void __launch_bounds__(256) k_heavy_reduce(const double *__restrict__ partial, const int32_t *__restrict__ unit_begin,
                                                       const int32_t *__restrict__ hseg, const int32_t *__restrict__ rowmap,
-                                                      int64_t nheavy, int nunits, int R, double *__restrict__ out) {
+                                                      int64_t nheavy, int nunits, int R, double *__restrict__ out,
+                                                      Epilogue ep) {
     const int64_t gidx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gidx >= nheavy * R) return;
     const int64_t h = gidx / R;
@@ -323,7 +324,7 @@ __global__ void __launch_bounds__(256) k_heavy_reduce(const double *__restrict__
         for (int x = 0; x < kXcd; ++x) s += partial[((int64_t)x * nunits + u) * R + r];
     const int seg = hseg[h];
     const int64_t row = rowmap ? (int64_t)rowmap[seg] : (int64_t)seg;
-    out[row * R + r] = s;
+    out[row * R + r] = ep_apply(ep, s, out + row * R + r);
 }
 
 size_t heavy_lds_bytes(int nu, int R) { return (size_t)nu * kHeavyGroups * (size_t)R * sizeof(double); }
@@ -481,7 +482,7 @@ hipError_t heavy_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd
 }
 
 hipError_t heavy_spmm(const HeavyPlan &plan, const int32_t *rowmap, const double *Dn, int64_t R, double *out, void *partial,
-                      hipStream_t st) {
+                      hipStream_t st, Epilogue ep) {
     if (plan.nunits <= 0) return hipSuccess;
     if (!heavy_supports(plan, R)) return hipErrorNotSupported;
     hipError_t e;
@@ -496,7 +497,7 @@ hipError_t heavy_spmm(const HeavyPlan &plan, const int32_t *rowmap, const double
     const int64_t threads = plan.nheavy * R;
     hipLaunchKernelGGL(k_heavy_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, (const double *)pp,
                        (const int32_t *)plan.unit_begin->ptr, (const int32_t *)plan.hseg->ptr, rowmap, plan.nheavy,
-                       (int)plan.nunits, (int)R, out);
+                       (int)plan.nunits, (int)R, out, ep);
     return hipGetLastError();
 }
 

@@ -21,7 +21,7 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
                                                        const int32_t *__restrict__ slice_begin,
                                                        const double *__restrict__ Bm, const double *__restrict__ Cm,
                                                        double *__restrict__ M, int64_t nnz, int64_t nfib, int64_t ntiles,
-                                                       int R, void *scratch) {
+                                                       int R, void *scratch, Epilogue ep) {
     constexpr int NW = 256 / L, WI = kTile / NW, SB = 4 * L;
     constexpr int kMapInts = 2 * kTile;
     constexpr int kOpenInts = 256 * V * 2;
@@ -54,7 +54,7 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
         if (il >= tb && il < te) tm[il - tb] = crd1[sl];
         if (il < 0) {                                             // a stored slice without any nonzero: its row is zero
             double *row = M + (int64_t)crd1[sl] * R;
-            for (int r = 0; r < R; ++r) row[r] = 0.0;
+            for (int r = 0; r < R; ++r) row[r] = ep_empty(ep, row + r);
         }
     }
     __syncthreads();
@@ -116,7 +116,7 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
                             for (int q = 0; q < V; ++q) first[q] = sacc[q];
                             first_row = tmr; ht = 1;
                         } else {
-                            grp_store_row_stream<L, V, WIDE>(M, tmr, R, j, sacc);
+                            grp_store_row_stream<L, V, WIDE>(M, tmr, R, j, sacc, ep);
                         }
 #pragma unroll
                         for (int q = 0; q < V; ++q) sacc[q] = 0.0;
@@ -156,16 +156,16 @@ __global__ void __launch_bounds__(256) k_stream_mttkrp(const int32_t *__restrict
     }
     __syncthreads();
     finish_tile_walkers<L, V, WIDE>(wopen, wht, g, j, ht, first, first_row, first_row, sacc, M, R,
-                                    carry_view(scratch, ntiles, R), t);
+                                    carry_view(scratch, ntiles, R), t, ep);
 }
 
 template <int L, int V, bool WIDE>
 hipError_t launch_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t *crd1, const int32_t *pos3,
                          const int32_t *crd2, const int32_t *crd3, const double *vals, const double *B, const double *C,
-                         int R, double *M, void *scratch, hipStream_t st) {
+                         int R, double *M, void *scratch, hipStream_t st, Epilogue ep) {
     hipLaunchKernelGGL((k_stream_mttkrp<L, V, WIDE>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos2, crd1, pos3, crd2,
                        crd3, vals, (const int32_t *)sc.seg_begin->ptr, (const int32_t *)sc.slice_begin->ptr, B, C, M,
-                       sc.nnz, sc.nseg, sc.ntiles, R, scratch);
+                       sc.nnz, sc.nseg, sc.ntiles, R, scratch, ep);
     return hipGetLastError();
 }
 
@@ -173,14 +173,15 @@ hipError_t launch_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t 
 
 hipError_t stream_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t *crd1, int64_t nslice,
                          const int32_t *pos3, const int32_t *crd2, const int32_t *crd3, const double *vals,
-                         const double *B, const double *C, int64_t R, double *M, void *scratch, hipStream_t st) {
+                         const double *B, const double *C, int64_t R, double *M, void *scratch, hipStream_t st,
+                         Epilogue ep) {
     (void)nslice;
     if (sc.ntiles <= 0) return hipSuccess;
     if (!stream_mttkrp_supports_rank(R) || !sc.slice_begin) return hipErrorNotSupported;
     const int r = (int)R;
-    hipError_t e = COMET_DISPATCH_RANK(launch_mttkrp, R, sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st);
+    hipError_t e = COMET_DISPATCH_RANK(launch_mttkrp, R, sc, pos2, crd1, pos3, crd2, crd3, vals, B, C, r, M, scratch, st, ep);
     if (e != hipSuccess) return e;
-    return run_fixup(scratch, sc.ntiles, r, nullptr, M, sc.max_parent_len > 0 ? sc.max_parent_len / kTile + 2 : 0, st);
+    return run_fixup(scratch, sc.ntiles, r, nullptr, M, sc.max_parent_len > 0 ? sc.max_parent_len / kTile + 2 : 0, st, ep);
 }
 
 }  // namespace comet

@@ -106,7 +106,8 @@ template <bool ROWMAP>
 __device__ __forceinline__ void rank1_process_half(const Rank1Half &h, const double2 *xv, const int2 *tt,
                                                    int64_t base, int64_t nnz, int lane, int w,
                                                    const int32_t *__restrict__ rowmap, double *__restrict__ out,
-                                                   Rank1Carry &cy, double *wsum_first, int *wsum_first_id) {
+                                                   Rank1Carry &cy, double *wsum_first, int *wsum_first_id,
+                                                   const Epilogue ep = Epilogue()) {
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
         const int64_t i0 = base + b * 128 + 2 * lane;
@@ -119,7 +120,7 @@ __device__ __forceinline__ void rank1_process_half(const Rank1Half &h, const dou
         const double open = t.y >= 0 ? 0.0 : (t.x >= 0 ? p1 : p0 + p1);
         if (t.x >= 0 && t.y >= 0) {                          // item i0+1 is a whole segment by itself
             const int64_t row = ROWMAP ? (int64_t)rowmap[t.y] : (int64_t)t.y;
-            out[row] = p1;
+            out[row] = ep_apply(ep, p1, out + row);
         }
         int sf = f;
         double sv = open;
@@ -133,7 +134,7 @@ __device__ __forceinline__ void rank1_process_half(const Rank1Half &h, const dou
             const double value = ev + first;
             if (ef) {
                 const int64_t row = ROWMAP ? (int64_t)rowmap[first_id] : (int64_t)first_id;
-                out[row] = value;
+                out[row] = ep_apply(ep, value, out + row);
             } else {                                         // the first segment end of this wavefront's range
                 wsum_first[w] = value;
                 wsum_first_id[w] = first_id;
@@ -157,7 +158,7 @@ __device__ __forceinline__ void walk_rank1(Rank1Half &h0, const int32_t *ts, con
                                            const double *__restrict__ vals, const double *__restrict__ x,
                                            const int32_t *__restrict__ rowmap, double *__restrict__ out, int64_t tb,
                                            int64_t nnz, int *wsum_ht, double *wsum_open, double *wsum_first,
-                                           int *wsum_first_id) {
+                                           int *wsum_first_id, const Epilogue ep = Epilogue()) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int64_t wb = tb + (int64_t)w * kWaveItems;
     Rank1Carry cy{0, 0.0};
@@ -168,11 +169,11 @@ __device__ __forceinline__ void walk_rank1(Rank1Half &h0, const int32_t *ts, con
     int2 tt[4];
 #pragma unroll
     for (int b = 0; b < 4; ++b) tt[b] = *reinterpret_cast<const int2 *>(ts + (wb - tb) + b * 128 + 2 * lane);
-    rank1_process_half<ROWMAP>(h0, xv, tt, wb, nnz, lane, w, rowmap, out, cy, wsum_first, wsum_first_id);
+    rank1_process_half<ROWMAP>(h0, xv, tt, wb, nnz, lane, w, rowmap, out, cy, wsum_first, wsum_first_id, ep);
     rank1_gather(h1, x, xv);
 #pragma unroll
     for (int b = 0; b < 4; ++b) tt[b] = *reinterpret_cast<const int2 *>(ts + (wb - tb) + 512 + b * 128 + 2 * lane);
-    rank1_process_half<ROWMAP>(h1, xv, tt, wb + 512, nnz, lane, w, rowmap, out, cy, wsum_first, wsum_first_id);
+    rank1_process_half<ROWMAP>(h1, xv, tt, wb + 512, nnz, lane, w, rowmap, out, cy, wsum_first, wsum_first_id, ep);
     if (lane == 0) { wsum_ht[w] = cy.cf; wsum_open[w] = cy.cv; }
 }
 
@@ -180,7 +181,8 @@ __device__ __forceinline__ void walk_rank1(Rank1Half &h0, const int32_t *ts, con
 template <bool ROWMAP>
 __device__ __forceinline__ void finish_tile_rank1(const int *wsum_ht, const double *wsum_open, const double *wsum_first,
                                                   const int *wsum_first_id, const int32_t *__restrict__ rowmap,
-                                                  double *__restrict__ out, CarryView cb, int64_t t) {
+                                                  double *__restrict__ out, CarryView cb, int64_t t,
+                                                  const Epilogue ep = Epilogue()) {
     if (threadIdx.x != 0) return;
     int rf = 0, fid = -1;
     double rv = 0.0, tfirst = 0.0;
@@ -189,7 +191,7 @@ __device__ __forceinline__ void finish_tile_rank1(const int *wsum_ht, const doub
             const double value = rv + wsum_first[w];
             if (rf) {
                 const int64_t row = ROWMAP ? (int64_t)rowmap[wsum_first_id[w]] : (int64_t)wsum_first_id[w];
-                out[row] = value;
+                out[row] = ep_apply(ep, value, out + row);
             } else {
                 tfirst = value; fid = wsum_first_id[w]; rf = 1;
             }
@@ -210,7 +212,7 @@ __global__ void __launch_bounds__(256) k_stream_rank1(const int32_t *__restrict_
                                                       const int32_t *__restrict__ seg_begin,
                                                       const int32_t *__restrict__ rowmap, const double *__restrict__ x,
                                                       double *__restrict__ out, int64_t nnz, int64_t ntiles,
-                                                      void *scratch) {
+                                                      void *scratch, Epilogue ep) {
     __shared__ __attribute__((aligned(16))) int32_t ts[kTile];
     __shared__ int wsum_ht[kWaves], wsum_first_id[kWaves];
     __shared__ double wsum_open[kWaves], wsum_first[kWaves];
@@ -218,10 +220,10 @@ __global__ void __launch_bounds__(256) k_stream_rank1(const int32_t *__restrict_
     const int64_t tb = t * (int64_t)kTile;
     Rank1Half h0;
     rank1_load_half(h0, crd, vals, tb + (int64_t)(threadIdx.x >> 6) * kWaveItems, threadIdx.x & 63, nnz);
-    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, 1);
-    walk_rank1<ROWMAP>(h0, ts, crd, vals, x, rowmap, out, tb, nnz, wsum_ht, wsum_open, wsum_first, wsum_first_id);
+    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, 1, 0, 0, false, ep);
+    walk_rank1<ROWMAP>(h0, ts, crd, vals, x, rowmap, out, tb, nnz, wsum_ht, wsum_open, wsum_first, wsum_first_id, ep);
     __syncthreads();
-    finish_tile_rank1<ROWMAP>(wsum_ht, wsum_open, wsum_first, wsum_first_id, rowmap, out, carry_view(scratch, ntiles, 1), t);
+    finish_tile_rank1<ROWMAP>(wsum_ht, wsum_open, wsum_first, wsum_first_id, rowmap, out, carry_view(scratch, ntiles, 1), t, ep);
 }
 
 // ---- rank-1 kernel with the dense vector staged in LDS ----------------------------------------------
@@ -245,7 +247,7 @@ __global__ void __launch_bounds__(1024) k_stream_rank1_ldsvec(const int32_t *__r
                                                               double *__restrict__ out, int64_t nnz, int64_t nchunks,
                                                               void *scratch, const int32_t *__restrict__ c0,
                                                               const int32_t *__restrict__ c1, int32_t *__restrict__ y0,
-                                                              int32_t *__restrict__ y1) {
+                                                              int32_t *__restrict__ y1, Epilogue ep) {
     extern __shared__ __attribute__((aligned(16))) char lds_raw[];
     const int64_t xpad = (ncols + 1) & ~(int64_t)1;
     double *xs = reinterpret_cast<double *>(lds_raw);
@@ -355,11 +357,11 @@ __global__ void __launch_bounds__(1024) k_stream_rank1_ldsvec(const int32_t *__r
         rank1_load_half(h1, crd, vals, cbeg + 512, lane, nnz);
         gather(h0, xv);
         tails_of_half(0, tt);
-        rank1_process_half<ROWMAP>(h0, xv, tt, cbeg, nnz, lane, w, rowmap, out, cy, wfirst_all, wfirst_id_all);
+        rank1_process_half<ROWMAP>(h0, xv, tt, cbeg, nnz, lane, w, rowmap, out, cy, wfirst_all, wfirst_id_all, ep);
         if (c + stride < nchunks) rank1_load_half(h0, crd, vals, (c + stride) * kChunk, lane, nnz);   // next chunk
         gather(h1, xv);
         tails_of_half(1, tt);
-        rank1_process_half<ROWMAP>(h1, xv, tt, cbeg + 512, nnz, lane, w, rowmap, out, cy, wfirst_all, wfirst_id_all);
+        rank1_process_half<ROWMAP>(h1, xv, tt, cbeg + 512, nnz, lane, w, rowmap, out, cy, wfirst_all, wfirst_id_all, ep);
         __builtin_amdgcn_wave_barrier();
         if (lane == 0) {
             cb.has_tail[c] = cy.cf;
@@ -433,7 +435,8 @@ __global__ void __launch_bounds__(256) k_stream_rank1_coo(const int32_t *__restr
 // value = first[t] + open[t-1] + open[t-2] + ... up to and including the nearest tile that contains
 // a segment end.  One thread per (tile, r).
 __global__ void __launch_bounds__(256) k_stream_fixup(void *scratch, int64_t ntiles, int R,
-                                                      const int32_t *__restrict__ rowmap, double *__restrict__ out) {
+                                                      const int32_t *__restrict__ rowmap, double *__restrict__ out,
+                                                      Epilogue ep) {
     const int64_t g = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (g >= ntiles * R) return;
     const int64_t t = g / R;
@@ -447,7 +450,7 @@ __global__ void __launch_bounds__(256) k_stream_fixup(void *scratch, int64_t nti
     }
     const int32_t id = cb.first_id[t];
     const int64_t row = rowmap ? (int64_t)rowmap[id] : (int64_t)id;
-    out[row * R + r] = v;
+    out[row * R + r] = ep_apply(ep, v, out + row * R + r);
 }
 
 
@@ -459,7 +462,8 @@ __global__ void __launch_bounds__(256) k_fixup_level(const double *__restrict__ 
                                                      int64_t n_lo, double *__restrict__ up_first,
                                                      double *__restrict__ up_open, int32_t *__restrict__ up_ht,
                                                      int32_t *__restrict__ up_id, int64_t n_up, int R,
-                                                     const int32_t *__restrict__ rowmap, double *__restrict__ out) {
+                                                     const int32_t *__restrict__ rowmap, double *__restrict__ out,
+                                                     Epilogue ep) {
     const int64_t gidx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gidx >= n_up * R) return;
     const int64_t g = gidx / R;
@@ -487,7 +491,7 @@ __global__ void __launch_bounds__(256) k_fixup_level(const double *__restrict__ 
                 const double value = rv + fi[i];
                 if (rf) {
                     const int64_t row = rowmap ? (int64_t)rowmap[id[i]] : (int64_t)id[i];
-                    out[row * R + r] = value;
+                    out[row * R + r] = ep_apply(ep, value, out + row * R + r);
                 } else {
                     gfirst = value; gid = id[i]; rf = 1;
                 }
@@ -509,7 +513,7 @@ __global__ void __launch_bounds__(256) k_fixup_level(const double *__restrict__ 
 // walk the few top-level summaries serially.  `max_chain` bounds the number of consecutive tiles
 // one segment can span (0 = unknown); short chains go straight to the serial walk.
 hipError_t run_fixup(void *scratch, int64_t ntiles, int R, const int32_t *rowmap, double *out, int64_t max_chain,
-                     hipStream_t st) {
+                     hipStream_t st, Epilogue ep) {
     char *base = (char *)scratch;
     int64_t n = ntiles;
     const bool direct = max_chain > 0 && max_chain <= 24;
@@ -520,13 +524,13 @@ hipError_t run_fixup(void *scratch, int64_t ntiles, int R, const int32_t *rowmap
         CarryView up = carry_view(up_base, n_up, R);
         const int64_t threads = n_up * R;
         hipLaunchKernelGGL(k_fixup_level, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, lo.first, lo.open,
-                           lo.has_tail, lo.first_id, n, up.first, up.open, up.has_tail, up.first_id, n_up, R, rowmap, out);
+                           lo.has_tail, lo.first_id, n, up.first, up.open, up.has_tail, up.first_id, n_up, R, rowmap, out, ep);
         base = up_base;
         n = n_up;
     }
     const int64_t threads = n * R;
     hipLaunchKernelGGL(k_stream_fixup, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, (void *)base, n, R,
-                       rowmap, out);
+                       rowmap, out, ep);
     return hipGetLastError();
 }
 
@@ -567,7 +571,7 @@ size_t stream_scratch_bytes(int64_t ntiles, int64_t R) {
 
 hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                             const int32_t *rowmap, const double *Dn, int64_t dense_rows, int64_t R, double *out,
-                            void *scratch, bool plain, hipStream_t st, int32_t heavy_len) {
+                            void *scratch, bool plain, hipStream_t st, int32_t heavy_len, Epilogue ep) {
     if (sc.ntiles <= 0) return hipSuccess;
     if (!stream_supports_rank(R)) return hipErrorNotSupported;
     if (heavy_len > 0 && (R == 1 || heavy_len < 256)) return hipErrorNotSupported;
@@ -586,31 +590,31 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
                 if (e != hipSuccess) return e;
                 hipLaunchKernelGGL((k_stream_rank1_ldsvec<true, false>), dim3(grid), dim3(1024), lds_bytes, st, pos, crd, vals,
                                    csb, rowmap, Dn, dense_rows, out, sc.nnz, sc.nchunks, scratch, (const int32_t *)nullptr,
-                                   (const int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr);
+                                   (const int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr, ep);
             } else {
                 e = allow_full_lds<k_stream_rank1_ldsvec<false, false>>();
                 if (e != hipSuccess) return e;
                 hipLaunchKernelGGL((k_stream_rank1_ldsvec<false, false>), dim3(grid), dim3(1024), lds_bytes, st, pos, crd, vals,
                                    csb, rowmap, Dn, dense_rows, out, sc.nnz, sc.nchunks, scratch, (const int32_t *)nullptr,
-                                   (const int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr);
+                                   (const int32_t *)nullptr, (int32_t *)nullptr, (int32_t *)nullptr, ep);
             }
             e = hipGetLastError();
             if (e != hipSuccess) return e;
-            return run_fixup(scratch, sc.nchunks, 1, rowmap, out, sc.max_seg_len / kChunk + 2, st);
+            return run_fixup(scratch, sc.nchunks, 1, rowmap, out, sc.max_seg_len / kChunk + 2, st, ep);
         }
         if (rowmap)
             hipLaunchKernelGGL(k_stream_rank1<true>, dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals, sb,
-                               rowmap, Dn, out, sc.nnz, sc.ntiles, scratch);
+                               rowmap, Dn, out, sc.nnz, sc.ntiles, scratch, ep);
         else
             hipLaunchKernelGGL(k_stream_rank1<false>, dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals, sb,
-                               rowmap, Dn, out, sc.nnz, sc.ntiles, scratch);
+                               rowmap, Dn, out, sc.nnz, sc.ntiles, scratch, ep);
         e = hipGetLastError();
     } else {
-        e = stream_segreduce_rankR(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st, heavy_len);
+        e = stream_segreduce_rankR(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st, heavy_len, ep);
     }
     if (e != hipSuccess) return e;
     // the rank-R kernel publishes result rows as ids, the rank-1 kernel segment numbers
-    return run_fixup(scratch, sc.ntiles, (int)R, R == 1 ? rowmap : nullptr, out, sc.max_seg_len / kTile + 2, st);
+    return run_fixup(scratch, sc.ntiles, (int)R, R == 1 ? rowmap : nullptr, out, sc.max_seg_len / kTile + 2, st, ep);
 }
 
 hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *c1, const int32_t *c2,
@@ -628,7 +632,7 @@ hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL((k_stream_rank1_ldsvec<false, true>), dim3(grid), dim3(1024), lds_bytes, st,
                            (const int32_t *)nullptr, c2, vals, (const int32_t *)sc.chunk_run_base->ptr,
-                           (const int32_t *)nullptr, v, dense_rows, yv, sc.nnz, sc.nchunks, scratch, c0, c1, y0, y1);
+                           (const int32_t *)nullptr, v, dense_rows, yv, sc.nnz, sc.nchunks, scratch, c0, c1, y0, y1, Epilogue());
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         return run_fixup(scratch, sc.nchunks, 1, nullptr, yv, max_run / kChunk + 2, st);

@@ -15,7 +15,7 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
                                                       const int32_t *__restrict__ seg_begin,
                                                       const int32_t *__restrict__ rowmap, const double *__restrict__ Dn,
                                                       double *__restrict__ out, int64_t nnz, int64_t ntiles, int R,
-                                                      void *scratch, int32_t heavy_len, int32_t nseg) {
+                                                      void *scratch, int32_t heavy_len, int32_t nseg, Epilogue ep) {
     constexpr int NW = 256 / L;                // walkers per tile
     constexpr int WI = kTile / NW;             // items per walker
     using RL = RecLayout<L, 2>;                // record = {row offset in doubles, tail id} + value
@@ -40,7 +40,7 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
     }
     LaneItems cur;
     lane_load_items(cur, crd, vals, gb + 4 * j, nnz);             // in flight while the map is built
-    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, R, HEAVY ? heavy_len : 0, nseg, ROWMAP);
+    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, R, HEAVY ? heavy_len : 0, nseg, ROWMAP, ep);
 
     WalkState<V> st;
 #pragma unroll
@@ -101,7 +101,7 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
                         st.ht = 1;
                     } else {
                         const unsigned row = (unsigned)b.tail;
-                        grp_store_row_stream<L, V, WIDE>(reinterpret_cast<double *>(outb + (size_t)row * R8), 0, R, j, st.acc);
+                        grp_store_row_stream<L, V, WIDE>(reinterpret_cast<double *>(outb + (size_t)row * R8), 0, R, j, st.acc, ep);
                     }
 #pragma unroll
                     for (int q = 0; q < V; ++q) st.acc[q] = 0.0;
@@ -127,31 +127,31 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
     __syncthreads();
     const int64_t first_row = st.ht ? (int64_t)st.first_id : 0;
     finish_tile_walkers<L, V, WIDE>(wopen, wht, g, j, st.ht, st.first, first_row, st.first_id, st.acc, out, R,
-                                    carry_view(scratch, ntiles, R), t);
+                                    carry_view(scratch, ntiles, R), t, ep);
 }
 
 template <int L, int V, bool WIDE, bool ROWMAP, bool HEAVY>
 void launch_rankR_one(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals, const int32_t *rowmap,
-                      const double *Dn, int R, double *out, void *scratch, hipStream_t st, int32_t heavy_len) {
+                      const double *Dn, int R, double *out, void *scratch, hipStream_t st, int32_t heavy_len, Epilogue ep) {
     hipLaunchKernelGGL((k_stream_rankR<L, V, WIDE, ROWMAP, HEAVY>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
                        (const int32_t *)sc.seg_begin->ptr, rowmap, Dn, out, sc.nnz, sc.ntiles, R, scratch, heavy_len,
-                       (int32_t)sc.nseg);
+                       (int32_t)sc.nseg, ep);
 }
 
 template <int L, int V, bool WIDE>
 hipError_t launch_rankR(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                         const int32_t *rowmap, const double *Dn, int R, double *out, void *scratch, hipStream_t st,
-                        int32_t heavy_len) {
+                        int32_t heavy_len, Epilogue ep) {
     if constexpr (WIDE && L == 8) {                           // the heavy-row sweep exists for these ranks only
         if (heavy_len > 0) {
-            if (rowmap) launch_rankR_one<L, V, WIDE, true, true>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, heavy_len);
-            else launch_rankR_one<L, V, WIDE, false, true>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, heavy_len);
+            if (rowmap) launch_rankR_one<L, V, WIDE, true, true>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, heavy_len, ep);
+            else launch_rankR_one<L, V, WIDE, false, true>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, heavy_len, ep);
             return hipGetLastError();
         }
     }
     if (heavy_len > 0) return hipErrorNotSupported;
-    if (rowmap) launch_rankR_one<L, V, WIDE, true, false>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, 0);
-    else launch_rankR_one<L, V, WIDE, false, false>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, 0);
+    if (rowmap) launch_rankR_one<L, V, WIDE, true, false>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, 0, ep);
+    else launch_rankR_one<L, V, WIDE, false, false>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, 0, ep);
     return hipGetLastError();
 }
 
@@ -159,8 +159,8 @@ hipError_t launch_rankR(const Schedule &sc, const int32_t *pos, const int32_t *c
 
 hipError_t stream_segreduce_rankR(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                                   const int32_t *rowmap, const double *Dn, int R, double *out, void *scratch,
-                                  hipStream_t st, int32_t heavy_len) {
-    return COMET_DISPATCH_RANK(launch_rankR, R, sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, heavy_len);
+                                  hipStream_t st, int32_t heavy_len, Epilogue ep) {
+    return COMET_DISPATCH_RANK(launch_rankR, R, sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, heavy_len, ep);
 }
 
 }  // namespace comet

@@ -21,7 +21,7 @@ template <int G>
 __global__ void __launch_bounds__(256) k_seg1_simple(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
                                                      const double *__restrict__ vals, int64_t nseg,
                                                      const int32_t *__restrict__ rowmap,
-                                                     const double *__restrict__ x, double *__restrict__ out) {
+                                                     const double *__restrict__ x, double *__restrict__ out, Epilogue ep) {
     int64_t s = ((int64_t)blockIdx.x * 256 + threadIdx.x) / G;
     int lane = threadIdx.x % G;
     if (s >= nseg) return;                       // whole groups leave together (G divides 64)
@@ -30,7 +30,7 @@ __global__ void __launch_bounds__(256) k_seg1_simple(const int32_t *__restrict__
     for (int32_t p = b + lane; p < e; p += G) acc = fma(vals[p], x[crd[p]], acc);
 #pragma unroll
     for (int o = G / 2; o > 0; o >>= 1) acc += __shfl_xor(acc, o, G);
-    if (lane == 0) out[rowmap ? (int64_t)rowmap[s] : s] = acc;
+    if (lane == 0) { double *o = out + (rowmap ? (int64_t)rowmap[s] : s); *o = ep_apply(ep, acc, o); }
 }
 
 // ---- rank R: thread (s, r), r fastest, so a wavefront reads contiguous pieces of operand rows ---
@@ -38,7 +38,7 @@ __global__ void __launch_bounds__(256) k_segR_simple(const int32_t *__restrict__
                                                      const double *__restrict__ vals, int64_t nseg,
                                                      const int32_t *__restrict__ rowmap,
                                                      const double *__restrict__ Dn, int R,
-                                                     double *__restrict__ out) {
+                                                     double *__restrict__ out, Epilogue ep) {
     int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= nseg * R) return;
     int64_t s = t / R;
@@ -46,23 +46,24 @@ __global__ void __launch_bounds__(256) k_segR_simple(const int32_t *__restrict__
     int32_t b = pos[s], e = pos[s + 1];
     double acc = 0.0;
     for (int32_t p = b; p < e; ++p) acc = fma(vals[p], Dn[(int64_t)crd[p] * R + r], acc);
-    out[(rowmap ? (int64_t)rowmap[s] : s) * R + r] = acc;
+    double *o = out + (rowmap ? (int64_t)rowmap[s] : s) * R + r;
+    *o = ep_apply(ep, acc, o);
 }
 
 hipError_t simple_segreduce(const int32_t *pos, const int32_t *crd, const double *vals, int64_t nseg,
                             int64_t nnz, const int32_t *rowmap, const double *Dn, int64_t R, double *out,
-                            hipStream_t st) {
+                            hipStream_t st, Epilogue ep) {
     if (nseg <= 0) return hipSuccess;
     if (R == 1) {
         double mean = (double)nnz / (double)nseg;
         if (mean <= 6.0)
-            hipLaunchKernelGGL(k_seg1_simple<4>, dim3(nblocks(nseg * 4, 256)), dim3(256), 0, st, pos, crd, vals, nseg, rowmap, Dn, out);
+            hipLaunchKernelGGL(k_seg1_simple<4>, dim3(nblocks(nseg * 4, 256)), dim3(256), 0, st, pos, crd, vals, nseg, rowmap, Dn, out, ep);
         else if (mean <= 24.0)
-            hipLaunchKernelGGL(k_seg1_simple<16>, dim3(nblocks(nseg * 16, 256)), dim3(256), 0, st, pos, crd, vals, nseg, rowmap, Dn, out);
+            hipLaunchKernelGGL(k_seg1_simple<16>, dim3(nblocks(nseg * 16, 256)), dim3(256), 0, st, pos, crd, vals, nseg, rowmap, Dn, out, ep);
         else
-            hipLaunchKernelGGL(k_seg1_simple<64>, dim3(nblocks(nseg * 64, 256)), dim3(256), 0, st, pos, crd, vals, nseg, rowmap, Dn, out);
+            hipLaunchKernelGGL(k_seg1_simple<64>, dim3(nblocks(nseg * 64, 256)), dim3(256), 0, st, pos, crd, vals, nseg, rowmap, Dn, out, ep);
     } else {
-        hipLaunchKernelGGL(k_segR_simple, dim3(nblocks(nseg * R, 256)), dim3(256), 0, st, pos, crd, vals, nseg, rowmap, Dn, (int)R, out);
+        hipLaunchKernelGGL(k_segR_simple, dim3(nblocks(nseg * R, 256)), dim3(256), 0, st, pos, crd, vals, nseg, rowmap, Dn, (int)R, out, ep);
     }
     return hipGetLastError();
 }
@@ -72,7 +73,8 @@ __global__ void __launch_bounds__(256) k_mttkrp_simple(const int32_t *__restrict
                                                        int64_t nslice, const int32_t *__restrict__ pos3,
                                                        const int32_t *__restrict__ crd2, const int32_t *__restrict__ crd3,
                                                        const double *__restrict__ vals, const double *__restrict__ B,
-                                                       const double *__restrict__ C, int R, double *__restrict__ M) {
+                                                       const double *__restrict__ C, int R, double *__restrict__ M,
+                                                       Epilogue ep) {
     int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= nslice * R) return;
     int64_t s = t / R;
@@ -83,15 +85,16 @@ __global__ void __launch_bounds__(256) k_mttkrp_simple(const int32_t *__restrict
         for (int32_t p = pos3[f]; p < pos3[f + 1]; ++p) inner = fma(vals[p], C[(int64_t)crd3[p] * R + r], inner);
         acc = fma(B[(int64_t)crd2[f] * R + r], inner, acc);
     }
-    M[(int64_t)crd1[s] * R + r] = acc;
+    double *o = M + (int64_t)crd1[s] * R + r;
+    *o = ep_apply(ep, acc, o);
 }
 
 hipError_t simple_mttkrp(const int32_t *pos2, const int32_t *crd1, int64_t nslice, const int32_t *pos3,
                          const int32_t *crd2, const int32_t *crd3, const double *vals, const double *B,
-                         const double *C, int64_t R, double *M, hipStream_t st) {
+                         const double *C, int64_t R, double *M, hipStream_t st, Epilogue ep) {
     if (nslice <= 0) return hipSuccess;
     hipLaunchKernelGGL(k_mttkrp_simple, dim3(nblocks(nslice * R, 256)), dim3(256), 0, st, pos2, crd1, nslice, pos3,
-                       crd2, crd3, vals, B, C, (int)R, M);
+                       crd2, crd3, vals, B, C, (int)R, M, ep);
     return hipGetLastError();
 }
 

@@ -28,17 +28,18 @@
 //           k_fixup_level / k_stream_fixup   carry resolution
 #pragma once
 
+#include "kernels.hpp"
 #include "stream_kernels.hpp"
 
 namespace comet {
 
 // Finishes every segment that a tile boundary cut (defined in kernels_rank1.hip).
 hipError_t run_fixup(void *scratch, int64_t ntiles, int R, const int32_t *rowmap, double *out, int64_t max_chain,
-                     hipStream_t st);
+                     hipStream_t st, Epilogue ep = Epilogue());
 // Rank-R part of stream_segreduce (defined in kernels_rankR.hip).
 hipError_t stream_segreduce_rankR(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                                   const int32_t *rowmap, const double *Dn, int R, double *out, void *scratch,
-                                  hipStream_t st, int32_t heavy_len);
+                                  hipStream_t st, int32_t heavy_len, Epilogue ep = Epilogue());
 
 namespace {
 
@@ -76,7 +77,7 @@ __device__ __forceinline__ void build_tail_map_from_pos(int32_t *ts, const int32
                                                         const int32_t *__restrict__ rowmap, int64_t tb, int32_t s0,
                                                         int32_t s1, double *__restrict__ out, int R,
                                                         int32_t heavy_len = 0, int32_t nseg = 0,
-                                                        bool rows_in_map = false) {
+                                                        bool rows_in_map = false, const Epilogue ep = Epilogue()) {
     __shared__ int hv_lo[24], hv_hi[24], hv_n;      // heavy pieces inside the tile: at most kTile / heavy_len + 2
     if (threadIdx.x == 0) hv_n = 0;
     for (int i = threadIdx.x * 4; i < kTile; i += blockDim.x * 4)
@@ -91,7 +92,7 @@ __device__ __forceinline__ void build_tail_map_from_pos(int32_t *ts, const int32
             ts[(int64_t)e - 1 - tb] = rows_in_map ? rowmap[s] : s;
         } else {
             int64_t row = rowmap ? (int64_t)rowmap[s] : (int64_t)s;
-            for (int r = 0; r < R; ++r) out[row * R + r] = 0.0;
+            for (int r = 0; r < R; ++r) out[row * R + r] = ep_empty(ep, out + row * R + r);
         }
     }
     if (heavy_len > 0 && threadIdx.x == 0 && s1 < nseg) {
@@ -163,31 +164,37 @@ __device__ __forceinline__ void grp_load_row(const double *__restrict__ Dn, int6
     }
 }
 template <int L, int V, bool WIDE>
-__device__ __forceinline__ void grp_store_row(double *__restrict__ out, int64_t row, int R, int j, const double *v) {
+__device__ __forceinline__ void grp_store_row(double *__restrict__ out, int64_t row, int R, int j, const double *v,
+                                              const Epilogue ep = Epilogue()) {
     double *p = out + row * R;
     if constexpr (WIDE) {
 #pragma unroll
-        for (int q = 0; q < V / 2; ++q) *reinterpret_cast<double2 *>(p + 2 * L * q + 2 * j) = make_double2(v[2 * q], v[2 * q + 1]);
+        for (int q = 0; q < V / 2; ++q) {
+            double *d = p + 2 * L * q + 2 * j;
+            *reinterpret_cast<double2 *>(d) = make_double2(ep_apply(ep, v[2 * q], d), ep_apply(ep, v[2 * q + 1], d + 1));
+        }
     } else {
 #pragma unroll
-        for (int q = 0; q < V; ++q) { int r = L * q + j; if (r < R) p[r] = v[q]; }
+        for (int q = 0; q < V; ++q) { int r = L * q + j; if (r < R) p[r] = ep_apply(ep, v[q], p + r); }
     }
 }
 
 // The same for a result row that this kernel does not read again: non-temporal stores.
 template <int L, int V, bool WIDE>
-__device__ __forceinline__ void grp_store_row_stream(double *__restrict__ out, int64_t row, int R, int j, const double *v) {
+__device__ __forceinline__ void grp_store_row_stream(double *__restrict__ out, int64_t row, int R, int j, const double *v,
+                                                     const Epilogue ep = Epilogue()) {
     double *p = out + row * R;
     if constexpr (WIDE) {
         typedef double v2d __attribute__((ext_vector_type(2)));
 #pragma unroll
         for (int q = 0; q < V / 2; ++q) {
-            v2d x; x.x = v[2 * q]; x.y = v[2 * q + 1];
-            __builtin_nontemporal_store(x, reinterpret_cast<v2d *>(p + 2 * L * q + 2 * j));
+            double *d = p + 2 * L * q + 2 * j;
+            v2d x; x.x = ep_apply(ep, v[2 * q], d); x.y = ep_apply(ep, v[2 * q + 1], d + 1);
+            __builtin_nontemporal_store(x, reinterpret_cast<v2d *>(d));
         }
     } else {
 #pragma unroll
-        for (int q = 0; q < V; ++q) { int r = L * q + j; if (r < R) __builtin_nontemporal_store(v[q], p + r); }
+        for (int q = 0; q < V; ++q) { int r = L * q + j; if (r < R) __builtin_nontemporal_store(ep_apply(ep, v[q], p + r), p + r); }
     }
 }
 
@@ -260,7 +267,7 @@ template <int L, int V, bool WIDE>
 __device__ __forceinline__ void finish_tile_walkers(const double *wopen, const int *wht, int g, int j, int ht,
                                                     const double *first, int64_t first_row, int32_t first_id,
                                                     const double *open, double *__restrict__ out, int R,
-                                                    CarryView cb, int64_t t) {
+                                                    CarryView cb, int64_t t, const Epilogue ep = Epilogue()) {
     constexpr int NW = 256 / L;
     const bool last = g == NW - 1;
     if (!(ht || last)) return;
@@ -279,7 +286,7 @@ __device__ __forceinline__ void finish_tile_walkers(const double *wopen, const i
 #pragma unroll
         for (int q = 0; q < V; ++q) value[q] = sum[q] + first[q];
         if (found) {
-            grp_store_row<L, V, WIDE>(out, first_row, R, j, value);
+            grp_store_row<L, V, WIDE>(out, first_row, R, j, value, ep);
         } else {                                              // first segment end of the whole tile
             grp_store_row<L, V, WIDE>(cb.first, t, R, j, value);
             if (j == 0) cb.first_id[t] = first_id;

@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 #include <cstdint>
 
+#include "kernels.hpp"
 #include "tensor.hpp"
 
 namespace comet {
@@ -28,7 +29,7 @@ size_t stream_scratch_bytes(int64_t ntiles, int64_t R);
 // nonzeros are skipped and their rows are not written; the heavy-row sweep produces them.
 hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                             const int32_t *rowmap, const double *Dn, int64_t dense_rows, int64_t R, double *out,
-                            void *scratch, bool plain, hipStream_t st, int32_t heavy_len = 0);
+                            void *scratch, bool plain, hipStream_t st, int32_t heavy_len = 0, Epilogue ep = Epilogue());
 
 // Sorted COO [CN,S,S]: one output (i, j, value) per run of equal (c0, c1).
 hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *c1, const int32_t *c2,
@@ -46,15 +47,17 @@ size_t heavy_partial_bytes(const HeavyPlan &plan, int64_t R);
 // out[row(h), :] = sum over heavy row h of vals * Dn[crd, :] for every heavy row (row(h) = rowmap ?
 // rowmap[seg] : seg); `partial` holds heavy_partial_bytes(plan, R).
 hipError_t heavy_spmm(const HeavyPlan &plan, const int32_t *rowmap, const double *Dn, int64_t R, double *out, void *partial,
-                      hipStream_t st);
+                      hipStream_t st, Epilogue ep = Epilogue());
 
 // Number of compute units of the current device (cached per device).
 int current_device_cu_count();
 
 // M[crd1[s], :] = sum_{f in slice s} B[crd2[f], :] * (sum_{p in fiber f} vals[p] * C[crd3[p], :]).
-// M must have been cleared for rows that have no stored slice.
+// M must have been cleared (or, with an epilogue, scaled by beta) for rows that have no stored slice.
+// Every comment above reads "=" as "= alpha * (...) + beta * (old value)" when an epilogue is switched on.
 hipError_t stream_mttkrp(const Schedule &sc, const int32_t *pos2, const int32_t *crd1, int64_t nslice,
                          const int32_t *pos3, const int32_t *crd2, const int32_t *crd3, const double *vals,
-                         const double *B, const double *C, int64_t R, double *M, void *scratch, hipStream_t st);
+                         const double *B, const double *C, int64_t R, double *M, void *scratch, hipStream_t st,
+                         Epilogue ep = Epilogue());
 
 }  // namespace comet

@@ -30,6 +30,26 @@ hipError_t fill_zero_f64(double *p, int64_t n, hipStream_t st) {
     return hipGetLastError();
 }
 
+__global__ void __launch_bounds__(256) k_scale_f64(double *__restrict__ p, int64_t n, double beta) {
+    int64_t n2 = n >> 1;
+    double2 *p2 = reinterpret_cast<double2 *>(p);
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n2; i += stride) {
+        const double2 v = p2[i];
+        p2[i] = make_double2(beta * v.x, beta * v.y);
+    }
+    if ((n & 1) && blockIdx.x == 0 && threadIdx.x == 0) p[n - 1] = beta * p[n - 1];
+}
+
+hipError_t scale_f64(double *p, int64_t n, double beta, hipStream_t st) {
+    if (n <= 0 || beta == 1.0) return hipSuccess;
+    if (beta == 0.0) return fill_zero_f64(p, n, st);
+    int64_t want = (n / 2 + 255) / 256;
+    unsigned grid = (unsigned)(want < 1 ? 1 : (want > 8192 ? 8192 : want));
+    hipLaunchKernelGGL(k_scale_f64, dim3(grid), dim3(256), 0, st, p, n, beta);
+    return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------------------
 // structure checks (bits: 1 pos, 2 range, 4 order inside a CU segment, 8 COO order)
 // ---------------------------------------------------------------------------------------------
@@ -283,19 +303,22 @@ hipError_t count_empty_segments(const int32_t *pos, int64_t nseg, int32_t *out_c
 // row ranges (idx[s-1], idx[s]) for s = 0..n (with idx[-1] = -1 and idx[n] = nrows).  One thread per
 // (gap, 16-byte piece); gaps are short when most rows are stored, which is the case this serves.
 __global__ void __launch_bounds__(256) k_zero_unstored_rows(const int32_t *__restrict__ idx, int64_t n, int64_t nrows,
-                                                            int R, double *__restrict__ out) {
+                                                            int R, double *__restrict__ out, double beta) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; s <= n; s += stride) {
         const int64_t lo = s == 0 ? 0 : (int64_t)idx[s - 1] + 1;
         const int64_t hi = s == n ? nrows : (int64_t)idx[s];
-        for (int64_t p = lo * R; p < hi * R; ++p) out[p] = 0.0;
+        if (beta == 0.0) for (int64_t p = lo * R; p < hi * R; ++p) out[p] = 0.0;
+        else for (int64_t p = lo * R; p < hi * R; ++p) out[p] = beta * out[p];
     }
 }
 
-hipError_t zero_unstored_rows(const int32_t *idx, int64_t n, int64_t nrows, int64_t R, double *out, hipStream_t st) {
+hipError_t zero_unstored_rows(const int32_t *idx, int64_t n, int64_t nrows, int64_t R, double *out, hipStream_t st,
+                              double beta) {
+    if (beta == 1.0) return hipSuccess;
     int64_t want = (n + 1 + 255) / 256;
     unsigned grid = (unsigned)(want > 4096 ? 4096 : want);
-    hipLaunchKernelGGL(k_zero_unstored_rows, dim3(grid), dim3(256), 0, st, idx, n, nrows, (int)R, out);
+    hipLaunchKernelGGL(k_zero_unstored_rows, dim3(grid), dim3(256), 0, st, idx, n, nrows, (int)R, out, beta);
     return hipGetLastError();
 }
 

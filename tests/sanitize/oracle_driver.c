@@ -16,6 +16,7 @@ int oracle_ttv(i64, const i64 *, const int32_t *, const double *, i64, const dou
 int oracle_ttm(i64, const i64 *, const int32_t *, const double *, i64, i64, const double *, i64, double *, double *);
 int oracle_mttkrp(i64, const int32_t *, const int32_t *, const int32_t *, const double *, i64, i64, i64, i64,
                   const double *, const double *, double *, double *);
+int oracle_axpby(i64, double, const double *, const double *, double, const double *, double *, double *);
 int oracle_walk(int, const int32_t *, const int32_t *const *, const i64 *, const int32_t *const *, const i64 *, i64,
                 int32_t *, int32_t *);
 
@@ -75,6 +76,19 @@ int main(void) {
     /* row 1: B[0] = (1, 2) times (9, 90)  +  B[2] = (5, 6) times (8, 80) */
     check(near(M[2], 9 + 40) && near(M[3], 180 + 480), "mttkrp row 1");
     check(oracle_mttkrp(5, ti, tj, tk, tv, 2, 2, 4, 2, B, U, M, Ma) == -1, "mttkrp coordinate out of range is an error");
+
+    /* y = 2 * (A x) + (-1) * old with old = (1, 1, 1): (0, 0, 5) -> (-1, -1, 9) */
+    {
+        const double old_[] = {1.0, 1.0, 1.0};
+        double *old = DUP(old_), *o = malloc(3 * sizeof(double)), *oa = malloc(3 * sizeof(double));
+        check(oracle_spmv(4, ri, ci, a, 3, 4, x, y, ya) == 0, "spmv again");
+        check(oracle_axpby(3, 2.0, y, ya, -1.0, old, o, oa) == 0, "axpby status");
+        check(near(o[0], -1) && near(o[1], -1) && near(o[2], 9), "axpby values");
+        check(near(oa[0], 17) && near(oa[1], 1) && near(oa[2], 11), "axpby absolute sums");
+        check(oracle_axpby(3, 2.0, y, ya, 0.0, NULL, o, oa) == 0 && near(o[2], 10), "axpby with beta 0 reads no old values");
+        check(oracle_axpby(0, 2.0, y, ya, 1.0, old, o, oa) == 0, "axpby of nothing");
+        free(old); free(o); free(oa);
+    }
 
     /* level walker: the 3 x 4 matrix as [D, CU] */
     const int32_t tags_[] = {0, 1};                                    /* D, CU */

@@ -77,6 +77,20 @@ def test_spmm_config(comet, spmm_config, layout):
     assert_values_close(np_(C), ref, absum, "spmm %s, every row" % layout)
 
 
+def test_spmm_axpby_config(comet, spmm_config):
+    """C = alpha A B + beta C at the headline size (heavy-row sweep and tiled kernel together), every element."""
+    c, ref, absum = spmm_config
+    rows, cols, vals = c["coo"]
+    n = c["dims"][0]
+    A = comet.from_levels(fmt.pack_csr(n, n, rows, cols, vals))
+    old = gen.dense_operand(0, 7, (n, 32), DEV)
+    C = old.clone()
+    comet.comet_spmm_axpby(A, -1.25, c["B"], 0.5, C)
+    torch.cuda.synchronize()
+    want, want_abs = oracle.axpby(-1.25, ref, absum, 0.5, np_(old))
+    assert_values_close(np_(C), want, want_abs, "spmm_axpby, every row")
+
+
 def test_spmv_on_the_spmm_matrix(comet, spmm_config):
     """SpMV at a size where it is not launch-bound: the headline matrix with one dense column (x is 8 MB, so
     the gathers go through L1 / L2 rather than LDS).  Every element of y."""

@@ -462,6 +462,45 @@ def test_pins_catch_transposed_or_swapped_operands():
     assert np.abs(moved - exact).max() > 1e-3
 
 
+@pytest.mark.parametrize("alpha,beta", [(1.0, 1.0), (-0.75, 2.5), (3.0, 0.0), (0.0, -1.5), (0.0, 0.0)])
+def test_scaled_accumulating_result_matches_exact_brute_force(alpha, beta):
+    """oracle.axpby (the in-place update of Section 6.2, Step III, with two scalars) against exact rational
+    arithmetic on a small SpMM: alpha * A B + beta * C for every element; what is not to be read may be NaN."""
+    shape = (6, 5)
+    rows, cols, vals = gen.bernoulli_matrix(shape[0], shape[1], 0.4, 17)
+    rows, cols, vals = np_(rows), np_(cols), np_(vals)
+    Xd = _dense_from_coo(shape, (rows, cols), vals)
+    U = np_(gen.dense_operand(17, 0, (shape[1], 3)))
+    C0 = np_(gen.dense_operand(17, 1, (shape[0], 3)))
+    Y, Ya = oracle.spmm(rows, cols, vals, shape, U)
+    exact = np.zeros_like(C0)
+    for i in range(shape[0]):
+        for r in range(3):
+            prod = sum((_fr(Xd[i, j]) * _fr(U[j, r]) for j in range(shape[1])), Fraction(0))
+            exact[i, r] = float(_fr(alpha) * prod + _fr(beta) * _fr(C0[i, r]))
+    old = C0.copy()
+    if beta == 0.0:
+        old[:] = np.nan                      # must not be read
+    prod_in = Y.copy()
+    if alpha == 0.0:
+        prod_in[:] = np.nan                  # must not be read
+    out, out_abs = oracle.axpby(alpha, prod_in, Ya, beta, old)
+    assert np.all(np.isfinite(out))
+    _assert_tight(out, exact, out_abs + 1e-300)
+    want_abs = (abs(alpha) * (np.abs(Xd) @ np.abs(U)) if alpha != 0.0 else 0.0) + (np.abs(beta * C0) if beta != 0.0 else 0.0)
+    assert np.allclose(out_abs, want_abs)
+
+
+def test_accumulating_twice_doubles_the_product():
+    """beta = 1 adds: starting from zeros, two accumulations of A x give exactly 2 A x (a power of two)."""
+    rows, cols, vals = (np_(a) for a in gen.bernoulli_matrix(9, 7, 0.5, 5))
+    x = np_(gen.dense_operand(5, 0, (7,)))
+    y, ya = oracle.spmv(rows, cols, vals, (9, 7), x)
+    once, _ = oracle.axpby(1.0, y, ya, 1.0, np.zeros(9))
+    twice, _ = oracle.axpby(1.0, y, ya, 1.0, once)
+    assert np.array_equal(once, y) and np.array_equal(twice, 2.0 * y)
+
+
 def test_oracle_is_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
     """The C oracle, built with -fsanitize=address,undefined, runs every entry point on hand-made inputs
     (tests/sanitize/oracle_driver.c: values worked out by hand from Section 8.2, empty inputs, a coordinate out
