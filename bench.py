@@ -122,16 +122,33 @@ def count_distinct(t):
 _TRAFFIC = None
 
 
+def kernel_sources_digest():
+    """sha256 over the HIP sources of the library (file names and contents, sorted): which kernels a figure belongs to."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2102_05187_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".hpp")):
+            h.update(name.encode())
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()
+
+
 def measured_traffic(op):
     """HBM bytes of one call (fetch + write) from the committed rocprofv3 counter summary, or None.
 
     The counters cannot be read from inside this process; profiles/hbm_traffic.json holds what
-    `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` measured for this same command at full size."""
+    `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` measured for this same command at full size, together with the
+    digest of the kernel sources it was collected with.  A figure collected with other kernels is not reported."""
     global _TRAFFIC
     if _TRAFFIC is None:
         try:
             with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
-                _TRAFFIC = json.load(f).get("ops", {})
+                doc = json.load(f)
+            _TRAFFIC = doc.get("ops", {}) if doc.get("kernel_sources_sha256") == kernel_sources_digest() else {}
+            if not _TRAFFIC:
+                log("[bench] profiles/hbm_traffic.json was collected with other kernel sources: roofline.traffic left out")
         except (OSError, ValueError):
             _TRAFFIC = {}
     e = _TRAFFIC.get(op)
@@ -139,7 +156,8 @@ def measured_traffic(op):
 
 
 TRAFFIC_SOURCE = ("profiles/hbm_traffic.json: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command at full size, "
-                  "collected in separate runs (the counters cannot be read in-process); not measured in this run")
+                  "collected in separate runs with these same kernel sources (digest checked; the counters cannot be "
+                  "read in-process); not measured in this run")
 
 
 def roofline(bytes_per_launch, ms, op=None, full_size=True):
