@@ -79,9 +79,11 @@ typedef struct {
     int32_t        mode_of_level[COMET_MAX_ORDER];  /* tensor mode stored at each level: 0,1,2,..
                                                  * unless comet_tensor_reorder chose another order;
                                                  * dims / levels / pos / crd above are per LEVEL    */
-    int64_t        heavy_rows;                /* schedule: rows that comet_spmm hands to its heavy-row sweep */
+    int64_t        heavy_rows;                /* schedule: rows that comet_spmm hands to its heavy-row sweep  */
+                                              /* (order 3: fibers that comet_ttm hands to its heavy-fiber sweep) */
     int64_t        heavy_nnz;                 /* ... and the nonzeros they hold (both 0: no sweep planned)   */
     int64_t        heavy_stream_bytes;        /* device memory of the sweep's re-ordered copy of those rows   */
+                                              /* (order 3: of the compacted copy of all other fibers)         */
 } comet_tensor_info_t;
 
 /*
@@ -224,6 +226,10 @@ comet_status comet_ttv(const comet_tensor *X, int mode, const double *v, comet_t
  *         last level).  For a coordinate list the first call builds a compressed copy of X inside the
  *         handle (one device sort, about 16 more bytes per nonzero, kept until X is destroyed) and
  *         synchronises; the result is then [CN,S,D]: the distinct (i,j) as for comet_ttv, R values each.
+ *         A [CU,CU,CU] tensor whose last mode has at most a few thousand coordinates and whose fibers of 256
+ *         or more nonzeros hold a quarter of the nonzeros or more also keeps, from comet_tensor_create on, a
+ *         compacted copy of all its other fibers (12 bytes per nonzero of them; see heavy_stream_bytes of
+ *         comet_tensor_info): for R = 16 and 32 the long fibers are then computed with the rows of U in LDS.
  *   U     device, [size of the contracted mode x R] row-major, 1 <= R <= 1024.
  *   Y     as for comet_ttv; the result is [CU,CU,D] with dims (I, J, R): levels 0/1 shared
  *         with X, a dense last level of size R, vals of [#fibers x R] row-major (#fibers x R

@@ -100,6 +100,23 @@ comet_status build_schedule(comet_tensor &t, hipStream_t st) {
         if (t.fmt == Format::CSR || t.fmt == Format::DCSR)
             HIP_TRY(comet::heavy_plan_build(t.pos_i(1), sc.nseg, t.crd_i(1), t.vals_d(), sc.nnz, t.dims[1], sc.heavy, st));
         if (t.fmt == Format::CSF3) {
+            HIP_TRY(comet::fiber_plan_build(t.pos_i(2), sc.nseg, t.crd_i(2), t.vals_d(), sc.nnz, t.dims[2], sc.fibers, st));
+            if (sc.fibers.nheavy > 0) {
+                // the short fibers as a matrix handle of their own (rows = fibers) over the plan's arrays
+                const comet::FiberPlan &fp = sc.fibers;
+                const int64_t dims2[2] = {sc.nseg, t.dims[2]};
+                const comet_level_t lv[2] = {COMET_CU, COMET_CU};
+                const int32_t *pp[2] = {(const int32_t *)fp.light_root->ptr, (const int32_t *)fp.light_pos->ptr};
+                const int32_t *cc[2] = {(const int32_t *)fp.light_rows->ptr, (const int32_t *)fp.light_crd->ptr};
+                const int64_t pl[2] = {2, fp.nlight + 1}, cl[2] = {fp.nlight, fp.light_nnz};
+                comet_tensor *lh = nullptr;
+                comet_status ls = comet_tensor_create(&lh, 2, dims2, lv, pp, pl, cc, cl, (const double *)fp.light_vals->ptr,
+                                                      fp.light_nnz, 0, st);
+                if (ls != COMET_OK) return ls;
+                t.light.reset(lh);
+            }
+        }
+        if (t.fmt == Format::CSF3) {
             HIP_TRY(hipMemsetAsync(mx->ptr, 0, sizeof(int32_t), st));
             HIP_TRY(comet::max_parent_span(t.pos_i(1), t.pos_len[1] - 1, t.pos_i(2), (int32_t *)mx->ptr, st));
             rs = read_i32((const int32_t *)mx->ptr, 1, &h, st);
@@ -381,6 +398,7 @@ static size_t scratch_need(const comet_tensor *t, int64_t R) {
     if (t->sched.ntiles > 0 && comet::stream_supports_rank(R)) {
         size_t b = comet::stream_scratch_bytes(t->sched.ntiles, R);
         if (t->sched.heavy.nunits > 0) b += comet::heavy_partial_bytes(t->sched.heavy, R > 64 ? 64 : R);
+        if (t->sched.fibers.nheavy > 0) b += comet::fiber_partial_bytes(t->sched.fibers, R >= 32 ? 32 : 16);
         if (b > need) need = b;
     }
     return need;
@@ -398,6 +416,10 @@ comet_status comet_tensor_reserve(comet_tensor *t, int64_t R, void *stream) {
             const size_t own = scratch_need(t, 1);
             if (own) { rs = ensure_scratch(t, own); if (rs != COMET_OK) return rs; }
         }
+    }
+    if (target->light) {                        // the short fibers of a tensor with a heavy-fiber plan run on their own handle
+        const size_t own = scratch_need(target->light.get(), Rt);
+        if (own) { comet_status rs = ensure_scratch(target->light.get(), own); if (rs != COMET_OK) return rs; }
     }
     const size_t need = scratch_need(target, Rt);
     return need ? ensure_scratch(target, need) : COMET_OK;
@@ -418,9 +440,10 @@ comet_status comet_tensor_info(const comet_tensor *t, comet_tensor_info_t *info)
     }
     info->vals = t->nvals ? t->vals_d() : nullptr;
     info->nvals = t->nvals;
-    info->heavy_rows = t->sched.heavy.nunits > 0 ? t->sched.heavy.nheavy : 0;
-    info->heavy_nnz = t->sched.heavy.nunits > 0 ? t->sched.heavy.heavy_nnz : 0;
-    info->heavy_stream_bytes = t->sched.heavy.nunits > 0 ? t->sched.heavy.stream_items * 16 : 0;
+    info->heavy_rows = t->sched.heavy.nunits > 0 ? t->sched.heavy.nheavy : t->sched.fibers.nheavy;
+    info->heavy_nnz = t->sched.heavy.nunits > 0 ? t->sched.heavy.heavy_nnz : t->sched.fibers.heavy_nnz;
+    info->heavy_stream_bytes = t->sched.heavy.nunits > 0 ? t->sched.heavy.stream_items * 16
+                                                         : t->sched.fibers.light_nnz * 12 + t->sched.fibers.nlight * 8;
     return COMET_OK;
 }
 
@@ -865,10 +888,26 @@ static comet_status leaf_contract(const comet_tensor *X, int mode, const double 
         if (csf || S) {
             const comet_tensor *C = csf ? X : S;                 // the compressed storage the kernels walk
             if (use_tiled(C, R, Dn, yv, C->dims[2], C->sched.max_seg_len)) {
-                rs = ensure_scratch(C, comet::stream_scratch_bytes(R == 1 ? C->sched.nchunks : C->sched.ntiles, R));
-                if (rs != COMET_OK) return rs;
-                HIP_TRY(comet::stream_segreduce(C->sched, C->pos_i(2), C->crd_i(2), C->vals_d(), nullptr, Dn, C->dims[2], R,
-                                                yv, C->scratch->ptr, C->variant == 3, st));
+                // long fibers over a small last mode: their rows come from the heavy-fiber sweep (operand rows in
+                // LDS), all other fibers from the tiled kernel run on the compacted copy of them
+                const comet_tensor *Lh = C->light.get();
+                const bool sweep = kind == 2 && C->variant != 3 && Lh && comet::fiber_supports(C->sched.fibers, R) &&
+                                   Lh->sched.ntiles > 0 && aligned16(Lh->crd_i(1)) && aligned16(Lh->vals_d());
+                if (sweep) {
+                    rs = ensure_scratch(Lh, comet::stream_scratch_bytes(Lh->sched.ntiles, R));
+                    if (rs != COMET_OK) return rs;
+                    rs = ensure_scratch(C, comet::fiber_partial_bytes(C->sched.fibers, R));
+                    if (rs != COMET_OK) return rs;
+                    HIP_TRY(comet::stream_segreduce(Lh->sched, Lh->pos_i(1), Lh->crd_i(1), Lh->vals_d(), Lh->crd_i(0), Dn,
+                                                    C->dims[2], R, yv, Lh->scratch->ptr, false, st));
+                    HIP_TRY(comet::fiber_ttm(C->sched.fibers, C->crd_i(2), C->vals_d(), Dn, C->dims[2], R, yv,
+                                             C->scratch->ptr, st));
+                } else {
+                    rs = ensure_scratch(C, comet::stream_scratch_bytes(R == 1 ? C->sched.nchunks : C->sched.ntiles, R));
+                    if (rs != COMET_OK) return rs;
+                    HIP_TRY(comet::stream_segreduce(C->sched, C->pos_i(2), C->crd_i(2), C->vals_d(), nullptr, Dn, C->dims[2], R,
+                                                    yv, C->scratch->ptr, C->variant == 3, st));
+                }
             } else {
                 HIP_TRY(comet::simple_segreduce(C->pos_i(2), C->crd_i(2), C->vals_d(), C->pos_len[2] - 1, C->nvals,
                                                 nullptr, Dn, R, yv, st));

@@ -501,4 +501,263 @@ hipError_t heavy_spmm(const HeavyPlan &plan, const int32_t *rowmap, const double
     return hipGetLastError();
 }
 
+
+// ======================================================================================================
+// Heavy-fiber sweep of TTM.
+//
+// y[f, :] = sum_p vals[p] * U[crd[p], :] over the nonzeros of fiber f (Section 8.2, SpTTM).  When the
+// contracted mode is small (a few thousand coordinates) U is cut into windows of rows that fill LDS (128 KB:
+// 1024 rows of 16 doubles or 512 rows of 32), every compute unit keeps ONE window for the whole kernel, and the
+// long fibers are handled piecewise: the nonzeros of a fiber are sorted by coordinate, so those inside window w
+// are the consecutive positions wstart[h][w] .. wstart[h][w+1].  A lane group of 8 takes such pieces one after
+// the other (pieces of window w are dealt back and forth over the lane groups of the compute units that hold
+// w, longest fibers first), gathers the operand rows from LDS -- 16 bytes per lane, a whole 128-byte row per
+// group and instruction, at LDS rather than L1 / texture-address cost -- and writes one partial row per
+// (fiber, window); a second kernel adds the windows of a fiber in a fixed order.  The remaining fibers stay with
+// the nonzero-tiled kernel, which skips the heavy ones.
+namespace {
+
+constexpr int kFiberLen = 256;         // a fiber with at least this many nonzeros is heavy
+constexpr int kFiberLdsBytes = 128 * 1024;
+constexpr int kFiberMaxWindows = 16;
+constexpr int kFiberThreads = 1024;
+
+template <int L, int V>                // L lanes per group, V doubles per lane; rank = L * V
+__global__ void __launch_bounds__(kFiberThreads) k_fiber_sweep(const int32_t *__restrict__ crd, const double *__restrict__ vals,
+                                                               const int32_t *__restrict__ wstart, int nheavy, int nwin,
+                                                               int window, const double *__restrict__ U, int ncols,
+                                                               double *__restrict__ partial) {
+    extern __shared__ __attribute__((aligned(16))) double2 urows[];          // [window][R / 2]
+    constexpr int R = L * V, R2 = R / 2, kGroups = kFiberThreads / L;
+    const int w = (int)(blockIdx.x % (unsigned)nwin), cw = (int)(blockIdx.x / (unsigned)nwin);
+    const int ncw = ((int)gridDim.x - w + nwin - 1) / nwin;                  // workgroups that hold window w
+    const int k0 = w * window, k1 = k0 + window < ncols ? k0 + window : ncols;
+    {
+        const int n2 = (k1 - k0) * R2;
+        const double2 *src = reinterpret_cast<const double2 *>(U + (size_t)k0 * R);
+        for (int i = threadIdx.x; i < n2; i += kFiberThreads) urows[i] = src[i];
+    }
+    __syncthreads();
+    const int g = threadIdx.x / L, j = threadIdx.x % L;
+    const int Gw = ncw * kGroups, mine = cw * kGroups + g;
+    const int per = nwin + 1;
+    auto piece_of = [&](int t) { return t * Gw + ((t & 1) ? Gw - 1 - mine : mine); };
+    const int rounds = (nheavy + Gw - 1) / Gw;
+    // bounds of the first piece
+    int h = piece_of(0), p0 = 0, p1 = 0;
+    if (rounds > 0 && h < nheavy) { p0 = wstart[(size_t)h * per + w]; p1 = wstart[(size_t)h * per + w + 1]; }
+    for (int t = 0; t < rounds; ++t) {
+        // bounds of the next piece: in flight during this one
+        const int hn = piece_of(t + 1);
+        int p0n = 0, p1n = 0;
+        if (t + 1 < rounds && hn < nheavy) { p0n = wstart[(size_t)hn * per + w]; p1n = wstart[(size_t)hn * per + w + 1]; }
+        double acc[V];
+#pragma unroll
+        for (int q = 0; q < V; ++q) acc[q] = 0.0;
+        int c_cur = 0;
+        double a_cur = 0.0;
+        if (p0 + j < p1) { c_cur = crd[p0 + j]; a_cur = vals[p0 + j]; }
+        int p = p0;
+        auto block = [&](auto checked) {                                   // L items: one per lane, taken one by one
+            int c_nxt = 0;
+            double a_nxt = 0.0;
+            if (p + L + j < p1) { c_nxt = crd[p + L + j]; a_nxt = vals[p + L + j]; }
+            const int rowoff = (c_cur - k0) * R2;                          // of this lane's item, in 16-byte pieces
+            static_for<0, L>([&](auto sc) {
+                constexpr int s_ = decltype(sc)::value;
+                if (!decltype(checked)::value || p + s_ < p1) {             // the same for the whole group
+                    const int o = grp_bcast_i<L, s_>(rowoff) + j;
+                    const double a = grp_bcast_d<L, s_>(a_cur);
+#pragma unroll
+                    for (int q = 0; q < V / 2; ++q) {
+                        const double2 d = urows[o + L * q];
+                        acc[2 * q] = fma(a, d.x, acc[2 * q]);
+                        acc[2 * q + 1] = fma(a, d.y, acc[2 * q + 1]);
+                    }
+                }
+            });
+            c_cur = c_nxt; a_cur = a_nxt;
+            p += L;
+        };
+        while (p + L <= p1) block(IntC<0>{});
+        if (p < p1) block(IntC<1>{});
+        if (h < nheavy) {
+            double2 *dst = reinterpret_cast<double2 *>(partial + ((size_t)h * nwin + w) * R) + j;
+#pragma unroll
+            for (int q = 0; q < V / 2; ++q) dst[L * q] = make_double2(acc[2 * q], acc[2 * q + 1]);
+        }
+        h = hn; p0 = p0n; p1 = p1n;
+    }
+}
+
+// out[fiber(h), r] = sum over the windows of the partial rows of heavy fiber h, in window order
+__global__ void __launch_bounds__(256) k_fiber_reduce(const double *__restrict__ partial, const int32_t *__restrict__ hseg,
+                                                      int64_t nheavy, int nwin, int R, double *__restrict__ out) {
+    const int64_t gidx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gidx >= nheavy * R) return;
+    const int64_t h = gidx / R;
+    const int r = (int)(gidx - h * R);
+    double s = 0.0;
+    for (int w = 0; w < nwin; ++w) s += partial[((size_t)h * nwin + w) * R + r];
+    out[(int64_t)hseg[h] * R + r] = s;
+}
+
+// flags[f] = (length << 32) | 1 for a light fiber, 0 for a heavy one: one exclusive scan then gives every light
+// fiber its row number (low half) and the position of its first nonzero in the copy (high half)
+__global__ void __launch_bounds__(256) k_light_flags(const int32_t *__restrict__ pos, int64_t nseg, int32_t min_len,
+                                                     uint64_t *__restrict__ flags) {
+    const int64_t f = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (f >= nseg) return;
+    const int len = pos[f + 1] - pos[f];
+    flags[f] = len < min_len ? (((uint64_t)(uint32_t)len << 32) | 1u) : 0u;
+}
+
+// 8 lanes copy the nonzeros of one light fiber
+__global__ void __launch_bounds__(256) k_light_copy(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
+                                                    const double *__restrict__ vals, int64_t nseg, int32_t min_len,
+                                                    const uint64_t *__restrict__ before, int32_t *__restrict__ lrows,
+                                                    int32_t *__restrict__ lpos, int32_t *__restrict__ lcrd,
+                                                    double *__restrict__ lvals) {
+    const int64_t f = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 3;
+    const int j = threadIdx.x & 7;
+    if (f >= nseg) return;
+    const int b = pos[f], len = pos[f + 1] - b;
+    if (len >= min_len) return;
+    const uint64_t w = before[f];
+    const int64_t r = (int64_t)(w & 0xffffffffu), p0 = (int64_t)(w >> 32);
+    if (j == 0) { lrows[r] = (int32_t)f; lpos[r] = (int32_t)p0; }
+    for (int i = j; i < len; i += 8) { lcrd[p0 + i] = crd[b + i]; lvals[p0 + i] = vals[b + i]; }
+}
+
+int fiber_plan_index(int64_t R) { return R == 16 ? 0 : (R == 32 ? 1 : -1); }
+
+}  // namespace
+
+bool fiber_supports(const FiberPlan &plan, int64_t R) {
+    const int k = fiber_plan_index(R);
+    return plan.nheavy > 0 && k >= 0 && plan.nwin[k] > 0;
+}
+
+size_t fiber_partial_bytes(const FiberPlan &plan, int64_t R) {
+    const int k = fiber_plan_index(R);
+    if (plan.nheavy <= 0 || k < 0) return 0;
+    return ((size_t)plan.nheavy * (size_t)plan.nwin[k] * (size_t)R * sizeof(double) + 255) & ~(size_t)255;
+}
+
+hipError_t fiber_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd, const double *vals, int64_t nnz,
+                            int64_t ncols, FiberPlan &plan, hipStream_t st) {
+    plan = FiberPlan();
+    const int window[2] = {kFiberLdsBytes / (16 * 8), kFiberLdsBytes / (32 * 8)};
+    if (nnz < (int64_t(1) << 20) || nseg < 1 || ncols < 1 || ncols > (int64_t)window[1] * kFiberMaxWindows) return hipSuccess;
+    DevRef counters = dev_alloc(3 * sizeof(unsigned long long));
+    if (!counters) return hipErrorOutOfMemory;
+    unsigned long long *cn = (unsigned long long *)counters->ptr;
+    hipError_t e = hipMemsetAsync(cn, 0, 3 * sizeof(unsigned long long), st);
+    if (e != hipSuccess) return e;
+    const unsigned grid = (unsigned)((nseg + 255) / 256);
+    hipLaunchKernelGGL(k_count_heavy, dim3(grid), dim3(256), 0, st, pos, nseg, (int32_t)kFiberLen, cn);
+    unsigned long long hc[2] = {0, 0};
+    e = hipMemcpyAsync(hc, cn, sizeof hc, hipMemcpyDeviceToHost, st);
+    if (e != hipSuccess) return e;
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return e;
+    const int64_t nheavy = (int64_t)hc[0], heavy_nnz = (int64_t)hc[1];
+    if (nheavy < 1 || heavy_nnz * 4 < nnz || nheavy > (int64_t(1) << 24)) return hipSuccess;   // the long fibers hold under a quarter
+    DevRef list = dev_alloc(sizeof(int2) * nheavy);
+    if (!list) return hipErrorOutOfMemory;
+    hipLaunchKernelGGL(k_collect_heavy, dim3(grid), dim3(256), 0, st, pos, nseg, (int32_t)kFiberLen, cn + 2,
+                       (int2 *)list->ptr, nheavy);
+    std::vector<int2> fib((size_t)nheavy);
+    e = hipMemcpyAsync(fib.data(), list->ptr, sizeof(int2) * nheavy, hipMemcpyDeviceToHost, st);
+    if (e != hipSuccess) return e;
+    e = hipStreamSynchronize(st);
+    if (e != hipSuccess) return e;
+    // longest first, ties by fiber: the dealing (and with it nothing but the schedule) does not depend on how the
+    // collection kernel happened to run
+    std::sort(fib.begin(), fib.end(), [](const int2 &a, const int2 &b) { return a.y != b.y ? a.y > b.y : a.x < b.x; });
+    std::vector<int32_t> hseg((size_t)nheavy);
+    for (int64_t k = 0; k < nheavy; ++k) hseg[(size_t)k] = fib[(size_t)k].x;
+    plan.hseg = dev_alloc(sizeof(int32_t) * nheavy);
+    if (!plan.hseg) { plan = FiberPlan(); return hipErrorOutOfMemory; }
+    e = hipMemcpyAsync(plan.hseg->ptr, hseg.data(), sizeof(int32_t) * nheavy, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) { plan = FiberPlan(); return e; }
+    for (int k = 0; k < 2; ++k) {
+        const int64_t nwin = (ncols + window[k] - 1) / window[k];
+        if (nwin > kFiberMaxWindows) continue;
+        const int64_t cells = nheavy * (nwin + 1);
+        plan.wstart[k] = dev_alloc(sizeof(int32_t) * (size_t)cells);
+        if (!plan.wstart[k]) { plan = FiberPlan(); return hipErrorOutOfMemory; }
+        hipLaunchKernelGGL(k_build_wstart, dim3((unsigned)((cells + 255) / 256)), dim3(256), 0, st, pos, crd,
+                           (const int32_t *)plan.hseg->ptr, nheavy, (int)nwin, window[k], (int32_t *)plan.wstart[k]->ptr);
+        plan.window[k] = window[k];
+        plan.nwin[k] = (int32_t)nwin;
+    }
+    e = hipStreamSynchronize(st);                                          // the host vector goes out of scope
+    if (e != hipSuccess) { plan = FiberPlan(); return e; }
+    if (plan.nwin[0] == 0 && plan.nwin[1] == 0) { plan = FiberPlan(); return hipSuccess; }
+    // the light fibers, copied out as a matrix
+    const int64_t nlight = nseg - nheavy, light_nnz = nnz - heavy_nnz;
+    if (nlight < 1 || light_nnz < 1) { plan = FiberPlan(); return hipSuccess; }
+    {
+        DevRef flags = dev_alloc(sizeof(uint64_t) * nseg), before = dev_alloc(sizeof(uint64_t) * nseg);
+        plan.light_root = dev_alloc(2 * sizeof(int32_t));
+        plan.light_rows = dev_alloc(sizeof(int32_t) * nlight);
+        plan.light_pos = dev_alloc(sizeof(int32_t) * (nlight + 1));
+        plan.light_crd = dev_alloc(sizeof(int32_t) * light_nnz);
+        plan.light_vals = dev_alloc(sizeof(double) * light_nnz);
+        if (!flags || !before || !plan.light_root || !plan.light_rows || !plan.light_pos || !plan.light_crd || !plan.light_vals) {
+            plan = FiberPlan();
+            return hipErrorOutOfMemory;
+        }
+        hipLaunchKernelGGL(k_light_flags, dim3(grid), dim3(256), 0, st, pos, nseg, (int32_t)kFiberLen, (uint64_t *)flags->ptr);
+        size_t temp_bytes = 0;
+        e = reorder_scan_flags(nullptr, &temp_bytes, (const uint64_t *)flags->ptr, (uint64_t *)before->ptr, nseg, st);
+        if (e != hipSuccess) { plan = FiberPlan(); return e; }
+        DevRef temp = dev_alloc(temp_bytes ? temp_bytes : 16);
+        if (!temp) { plan = FiberPlan(); return hipErrorOutOfMemory; }
+        e = reorder_scan_flags(temp->ptr, &temp_bytes, (const uint64_t *)flags->ptr, (uint64_t *)before->ptr, nseg, st);
+        if (e != hipSuccess) { plan = FiberPlan(); return e; }
+        hipLaunchKernelGGL(k_light_copy, dim3((unsigned)((nseg * 8 + 255) / 256)), dim3(256), 0, st, pos, crd, vals, nseg,
+                           (int32_t)kFiberLen, (const uint64_t *)before->ptr, (int32_t *)plan.light_rows->ptr,
+                           (int32_t *)plan.light_pos->ptr, (int32_t *)plan.light_crd->ptr, (double *)plan.light_vals->ptr);
+        const int32_t root[2] = {0, (int32_t)nlight}, last = (int32_t)light_nnz;
+        e = hipMemcpyAsync(plan.light_root->ptr, root, sizeof root, hipMemcpyHostToDevice, st);
+        if (e == hipSuccess)
+            e = hipMemcpyAsync((int32_t *)plan.light_pos->ptr + nlight, &last, sizeof last, hipMemcpyHostToDevice, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);                 // host values and temporaries go out of scope
+        if (e != hipSuccess) { plan = FiberPlan(); return e; }
+    }
+    plan.nlight = nlight; plan.light_nnz = light_nnz;
+    plan.nheavy = nheavy; plan.heavy_nnz = heavy_nnz; plan.min_len = kFiberLen;
+    return hipGetLastError();
+}
+
+hipError_t fiber_ttm(const FiberPlan &plan, const int32_t *crd, const double *vals, const double *Dn, int64_t ncols,
+                     int64_t R, double *out, void *partial, hipStream_t st) {
+    if (!fiber_supports(plan, R)) return hipErrorNotSupported;
+    const int k = fiber_plan_index(R);
+    const int ncu = current_device_cu_count();
+    const unsigned grid = (unsigned)(ncu < plan.nwin[k] ? plan.nwin[k] : ncu);      // every window needs a workgroup
+    const size_t lds = (size_t)plan.window[k] * (size_t)R * sizeof(double);
+    double *pp = (double *)partial;
+    hipError_t e;
+    if (R == 16) {
+        static hipError_t attr = hipFuncSetAttribute((const void *)k_fiber_sweep<8, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if ((e = attr) != hipSuccess) return e;
+        hipLaunchKernelGGL((k_fiber_sweep<8, 2>), dim3(grid), dim3(kFiberThreads), lds, st, crd, vals, (const int32_t *)plan.wstart[k]->ptr,
+                           (int)plan.nheavy, (int)plan.nwin[k], (int)plan.window[k], Dn, (int)ncols, pp);
+    } else {
+        static hipError_t attr = hipFuncSetAttribute((const void *)k_fiber_sweep<8, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if ((e = attr) != hipSuccess) return e;
+        hipLaunchKernelGGL((k_fiber_sweep<8, 4>), dim3(grid), dim3(kFiberThreads), lds, st, crd, vals, (const int32_t *)plan.wstart[k]->ptr,
+                           (int)plan.nheavy, (int)plan.nwin[k], (int)plan.window[k], Dn, (int)ncols, pp);
+    }
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t threads = plan.nheavy * R;
+    hipLaunchKernelGGL(k_fiber_reduce, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, (const double *)pp,
+                       (const int32_t *)plan.hseg->ptr, plan.nheavy, (int)plan.nwin[k], (int)R, out);
+    return hipGetLastError();
+}
+
 }  // namespace comet

@@ -49,6 +49,19 @@ size_t heavy_partial_bytes(const HeavyPlan &plan, int64_t R);
 hipError_t heavy_spmm(const HeavyPlan &plan, const int32_t *rowmap, const double *Dn, int64_t R, double *out, void *partial,
                       hipStream_t st, Epilogue ep = Epilogue());
 
+// ---- heavy-fiber sweep of TTM (kernels_heavy.hip) --------------------------------------------------
+// Builds the plan for the leaf level of a [CU,CU,CU] tensor (pos over nseg fibers, crd with coordinates < ncols);
+// leaves plan.nheavy = 0 when the operand rows do not fit a few LDS windows or the long fibers hold too small a
+// share.  The plan also holds a copy of all other fibers as a [CU,CU] matrix (row = fiber).  Synchronises.
+hipError_t fiber_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd, const double *vals, int64_t nnz,
+                            int64_t ncols, FiberPlan &plan, hipStream_t st);
+bool   fiber_supports(const FiberPlan &plan, int64_t R);          // ranks 16 and 32
+size_t fiber_partial_bytes(const FiberPlan &plan, int64_t R);
+// out[fiber, :] = sum over the fiber of vals * Dn[crd, :] for every heavy fiber (Dn has ncols rows of R);
+// `partial` holds fiber_partial_bytes(plan, R).
+hipError_t fiber_ttm(const FiberPlan &plan, const int32_t *crd, const double *vals, const double *Dn, int64_t ncols,
+                     int64_t R, double *out, void *partial, hipStream_t st);
+
 // Number of compute units of the current device (cached per device).
 int current_device_cu_count();
 

@@ -62,6 +62,29 @@ struct HeavyPlan {
     DevRef  wend;         // int32 [wavefronts][windows per range + 1]: first position of each window in the stream
 };
 
+// Plan of the heavy-fiber sweep of TTM (kernels_heavy.hip), built once at creation for order-3 tensors whose
+// last mode is small enough for its dense operand to be cut into a few LDS-sized windows of rows and whose long
+// fibers (at least `min_len` nonzeros) hold a large share of the nonzeros.  Fibers are sorted by coordinate, so
+// the nonzeros of a fiber that fall into one window are consecutive: the plan only holds where they start.
+// Two window sizes are kept (index 0: ranks up to 16, index 1: ranks up to 32) so that a window of operand rows
+// fills the same 128 KB of LDS for both.
+struct FiberPlan {
+    int64_t nheavy = 0, heavy_nnz = 0;
+    int32_t min_len = 0;
+    int32_t window[2] = {0, 0}, nwin[2] = {0, 0};
+    DevRef  hseg;         // int32 [nheavy]: leaf segment (fiber) of heavy fiber h, longest fibers first
+    DevRef  wstart[2];    // int32 [nheavy][nwin + 1]: first position of fiber h with coordinate >= w * window
+    // The other fibers, copied out so that the nonzero-tiled kernel walks them without the long ones in between
+    // (skipping inside the original arrays saves nothing: the lane groups of a wavefront sit 128 items apart, and
+    // a wavefront step is free only where all of them skip).  A [CU,CU] matrix: row r is fiber light_rows[r].
+    int64_t nlight = 0, light_nnz = 0;
+    DevRef  light_root;   // int32 [2]: {0, nlight}
+    DevRef  light_rows;   // int32 [nlight]: fiber of light row r, increasing
+    DevRef  light_pos;    // int32 [nlight + 1]
+    DevRef  light_crd;    // int32 [light_nnz]
+    DevRef  light_vals;   // double [light_nnz]
+};
+
 // Per-tensor schedule for the nonzero-tiled kernels, built once at creation.
 //   The leaf level's nonzeros are cut into tiles of kTile consecutive positions; seg_begin[t] is
 //   the segment (row / fiber) that contains the first nonzero of tile t (seg_begin[0] = 0 and
@@ -82,6 +105,7 @@ struct Schedule {
     int64_t max_parent_len = 0;   // CSF3: most nonzeros under one slice (0 = unknown)
     int64_t max_root_gap = -1;    // compressed root level: longest run of absent root coordinates (-1 = unknown)
     HeavyPlan heavy;              // matrices only; nunits = 0 when the sweep does not apply
+    FiberPlan fibers;             // CSF3 only; nheavy = 0 when the sweep does not apply
 };
 
 }  // namespace comet
@@ -115,6 +139,8 @@ struct comet_tensor {
     // a sorted coordinate list keeps a compressed ([CU,CU,CU]) copy of itself for the operations whose
     // kernels need the fiber / slice structure (TTM, MTTKRP); built on their first use
     mutable std::unique_ptr<comet_tensor> shadow;
+    // [CU,CU,CU] with a heavy-fiber plan: the short fibers as a matrix handle over the plan's copy (see FiberPlan)
+    std::unique_ptr<comet_tensor> light;
 
     // results of TTV / TTM remember what produced them so the handle can be reused
     const comet_tensor *result_of = nullptr;

@@ -273,6 +273,41 @@ def test_ttm(comet, name, R, variant):
     assert_values_close(np_(Y.vals()).reshape(-1, R), ref["vals"], ref["abs"], "ttm %s R=%d" % (name, R))
 
 
+def _heavy_fiber_tensor(K=3000):
+    """1.1 M nonzeros; fibers of 255 / 256 / 257 nonzeros around the heavy-fiber threshold, fibers that fill
+    most of the last mode, fibers next to each other and alone in their slice, short ones in between; the last
+    mode spans three (rank 16) or six (rank 32) windows of operand rows, the last of them ragged."""
+    block = [2500, 256, 255, 257, 1, 1024, 3, 2700, 2600, 300, 2, 1500, 511, 512, 7, 2047, 2049, 40, 600]
+    lens = torch.tensor([2650] + block * 65 + [256, 1, 2000], dtype=torch.int64)
+    J = 7
+    rows, cols, vals = gen.matrix_from_row_lengths(lens.numel(), K, lens, 22)
+    I = (lens.numel() + J - 1) // J
+    return (I, J, K), (rows // J, rows % J, cols, vals), lens
+
+
+@pytest.mark.parametrize("layout", ["csf", "coo"])
+@pytest.mark.parametrize("R,variant", [(16, 0), (32, 0), (16, 2), (32, 2), (16, 3), (16, 1), (8, 0), (64, 0)])
+def test_ttm_with_heavy_fibers(comet, R, variant, layout):
+    """A tensor whose long fibers go to the heavy-fiber sweep of TTM (ranks 16 and 32; the other ranks and
+    variants 1 and 3 stay on the kernels that take every fiber).  Every element, two runs bit for bit."""
+    dims, (i, j, k, vals), lens = _heavy_fiber_tensor()
+    say("ttm heavy fibers layout=%s R=%d variant=%d nnz=%d" % (layout, R, variant, vals.numel()))
+    L = (fmt.pack_csf3(dims, i, j, k, vals) if layout == "csf" else fmt.pack_coo(dims, (i, j, k), vals)).to("cuda")
+    X = comet.from_levels(L).set_variant(variant)
+    if layout == "csf":
+        hf, hn = X.heavy_plan()
+        assert hf == int((lens >= 256).sum()) and hn == int(lens[lens >= 256].sum()) and hn * 4 >= vals.numel()
+    U = gen.dense_operand(4, 0, (dims[2], R))
+    Y = comet.comet_ttm(X, 2, dev(U))
+    torch.cuda.synchronize()
+    ref = oracle.ttm(np_(i), np_(j), np_(k), np_(vals), dims, np_(U))
+    assert_values_close(np_(Y.vals()).reshape(-1, R), ref["vals"], ref["abs"], "ttm heavy fibers R=%d" % R)
+    first = Y.vals().clone()
+    comet.comet_ttm(X, 2, dev(U), Y)
+    torch.cuda.synchronize()
+    assert torch.equal(first, Y.vals()), "two runs differ"
+
+
 @pytest.mark.parametrize("variant", VARIANTS)
 @pytest.mark.parametrize("R", [1, 8, 16, 64])
 @pytest.mark.parametrize("name", ["zipf_mttkrp", "zipf_ttv", "mode_of_two", "single_slice", "single_fiber", "long_slice",
