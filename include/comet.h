@@ -83,7 +83,8 @@ typedef struct {
                                               /* (order 3: fibers that comet_ttm hands to its heavy-fiber sweep) */
     int64_t        heavy_nnz;                 /* ... and the nonzeros they hold (both 0: no sweep planned)   */
     int64_t        heavy_stream_bytes;        /* device memory of the sweep's re-ordered copy of those rows   */
-                                              /* (order 3: of the compacted copy of all other fibers)         */
+                                              /* plus the compacted copy of all other rows (order 3: of the   */
+                                              /* compacted copy of all other fibers)                          */
 } comet_tensor_info_t;
 
 /*

@@ -51,6 +51,22 @@ comet_status read_i32(const int32_t *dev, int n, int32_t *host, hipStream_t st) 
     return COMET_OK;
 }
 
+// The segments a sweep leaves to the tiled kernel, as a matrix handle of their own over the plan's copy of them
+// (row r of the copy writes result row lc.rows[r]; `nrows_total` only bounds those row numbers).
+static comet_status make_light_handle(comet_tensor &t, const comet::LightCopy &lc, int64_t nrows_total, int64_t ncols,
+                                      hipStream_t st) {
+    const int64_t dims2[2] = {nrows_total, ncols};
+    const comet_level_t lv[2] = {COMET_CU, COMET_CU};
+    const int32_t *pp[2] = {(const int32_t *)lc.root->ptr, (const int32_t *)lc.pos->ptr};
+    const int32_t *cc[2] = {(const int32_t *)lc.rows->ptr, (const int32_t *)lc.crd->ptr};
+    const int64_t pl[2] = {2, lc.nrows + 1}, cl[2] = {lc.nrows, lc.nnz};
+    comet_tensor *lh = nullptr;
+    comet_status ls = comet_tensor_create(&lh, 2, dims2, lv, pp, pl, cc, cl, (const double *)lc.vals->ptr, lc.nnz, 0, st);
+    if (ls != COMET_OK) return ls;
+    t.light.reset(lh);
+    return COMET_OK;
+}
+
 // Builds the tile tables of the nonzero-tiled kernels for the formats that have them.
 comet_status build_schedule(comet_tensor &t, hipStream_t st) {
     comet::Schedule &sc = t.sched;
@@ -97,23 +113,19 @@ comet_status build_schedule(comet_tensor &t, hipStream_t st) {
             if (rs != COMET_OK) return rs;
             sc.max_root_gap = h;
         }
-        if (t.fmt == Format::CSR || t.fmt == Format::DCSR)
-            HIP_TRY(comet::heavy_plan_build(t.pos_i(1), sc.nseg, t.crd_i(1), t.vals_d(), sc.nnz, t.dims[1], sc.heavy, st));
+        if (t.fmt == Format::CSR || t.fmt == Format::DCSR) {
+            HIP_TRY(comet::heavy_plan_build(t.pos_i(1), sc.nseg, t.crd_i(1), t.vals_d(), sc.nnz, t.dims[1],
+                                            t.fmt == Format::DCSR ? t.crd_i(0) : nullptr, sc.heavy, st));
+            if (sc.heavy.nunits > 0 && sc.heavy.light.nrows > 0) {
+                comet_status ls = make_light_handle(t, sc.heavy.light, t.dims[0], t.dims[1], st);
+                if (ls != COMET_OK) return ls;
+            }
+        }
         if (t.fmt == Format::CSF3) {
             HIP_TRY(comet::fiber_plan_build(t.pos_i(2), sc.nseg, t.crd_i(2), t.vals_d(), sc.nnz, t.dims[2], sc.fibers, st));
             if (sc.fibers.nheavy > 0) {
-                // the short fibers as a matrix handle of their own (rows = fibers) over the plan's arrays
-                const comet::FiberPlan &fp = sc.fibers;
-                const int64_t dims2[2] = {sc.nseg, t.dims[2]};
-                const comet_level_t lv[2] = {COMET_CU, COMET_CU};
-                const int32_t *pp[2] = {(const int32_t *)fp.light_root->ptr, (const int32_t *)fp.light_pos->ptr};
-                const int32_t *cc[2] = {(const int32_t *)fp.light_rows->ptr, (const int32_t *)fp.light_crd->ptr};
-                const int64_t pl[2] = {2, fp.nlight + 1}, cl[2] = {fp.nlight, fp.light_nnz};
-                comet_tensor *lh = nullptr;
-                comet_status ls = comet_tensor_create(&lh, 2, dims2, lv, pp, pl, cc, cl, (const double *)fp.light_vals->ptr,
-                                                      fp.light_nnz, 0, st);
+                comet_status ls = make_light_handle(t, sc.fibers.light, sc.nseg, t.dims[2], st);
                 if (ls != COMET_OK) return ls;
-                t.light.reset(lh);
             }
         }
         if (t.fmt == Format::CSF3) {
@@ -442,8 +454,9 @@ comet_status comet_tensor_info(const comet_tensor *t, comet_tensor_info_t *info)
     info->nvals = t->nvals;
     info->heavy_rows = t->sched.heavy.nunits > 0 ? t->sched.heavy.nheavy : t->sched.fibers.nheavy;
     info->heavy_nnz = t->sched.heavy.nunits > 0 ? t->sched.heavy.heavy_nnz : t->sched.fibers.heavy_nnz;
-    info->heavy_stream_bytes = t->sched.heavy.nunits > 0 ? t->sched.heavy.stream_items * 16
-                                                         : t->sched.fibers.light_nnz * 12 + t->sched.fibers.nlight * 8;
+    info->heavy_stream_bytes = t->sched.heavy.nunits > 0
+                                   ? t->sched.heavy.stream_items * 16 + (int64_t)t->sched.heavy.light.bytes()
+                                   : (int64_t)t->sched.fibers.light.bytes();
     return COMET_OK;
 }
 
@@ -739,10 +752,21 @@ static comet_status matrix_product(const comet_tensor *A, const double *Dn, int6
             if (rs != COMET_OK) return rs;
             scr = A->scratch->ptr;
         }
-        HIP_TRY(comet::stream_segreduce(A->sched, A->pos_i(1), A->crd_i(1), A->vals_d(), rowmap, Dn, A->dims[1], R, out,
-                                        scr, A->variant == 3, st, heavy ? A->sched.heavy.min_len : 0, ep));
-        if (heavy)
+        if (heavy) {
+            // the long rows from the sweep, all other rows from the tiled kernel run on the plan's copy of them
+            // (whose rows carry their result rows, DCSR's included)
+            const comet_tensor *Lh = A->light.get();
+            if (Lh && Lh->sched.ntiles > 0) {
+                comet_status rs = ensure_scratch(Lh, comet::stream_scratch_bytes(Lh->sched.ntiles, R));
+                if (rs != COMET_OK) return rs;
+                HIP_TRY(comet::stream_segreduce(Lh->sched, Lh->pos_i(1), Lh->crd_i(1), Lh->vals_d(), Lh->crd_i(0), Dn,
+                                                A->dims[1], R, out, Lh->scratch->ptr, false, st, ep));
+            }
             HIP_TRY(comet::heavy_spmm(A->sched.heavy, rowmap, Dn, R, out, (char *)scr + carry, st, ep));
+            return COMET_OK;
+        }
+        HIP_TRY(comet::stream_segreduce(A->sched, A->pos_i(1), A->crd_i(1), A->vals_d(), rowmap, Dn, A->dims[1], R, out,
+                                        scr, A->variant == 3, st, ep));
         return COMET_OK;
     }
     HIP_TRY(comet::simple_segreduce(A->pos_i(1), A->crd_i(1), A->vals_d(), nseg, nnz, rowmap, Dn, R, out, st, ep));

@@ -101,6 +101,67 @@ __global__ void __launch_bounds__(256) k_build_wstart(const int32_t *__restrict_
     wstart[g] = lo;
 }
 
+// flags[f] = (length << 32) | 1 for a light segment, 0 for a heavy one: one exclusive scan then gives every light
+// segment its row number (low half) and the position of its first nonzero in the copy (high half)
+__global__ void __launch_bounds__(256) k_light_flags(const int32_t *__restrict__ pos, int64_t nseg, int32_t min_len,
+                                                     uint64_t *__restrict__ flags) {
+    const int64_t f = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (f >= nseg) return;
+    const int len = pos[f + 1] - pos[f];
+    flags[f] = len < min_len ? (((uint64_t)(uint32_t)len << 32) | 1u) : 0u;
+}
+
+// 8 lanes copy the nonzeros of one light segment; its result row is rowmap[segment] if there is a map
+__global__ void __launch_bounds__(256) k_light_copy(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
+                                                    const double *__restrict__ vals, int64_t nseg, int32_t min_len,
+                                                    const uint64_t *__restrict__ before,
+                                                    const int32_t *__restrict__ rowmap, int32_t *__restrict__ lrows,
+                                                    int32_t *__restrict__ lpos, int32_t *__restrict__ lcrd,
+                                                    double *__restrict__ lvals) {
+    const int64_t f = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 3;
+    const int j = threadIdx.x & 7;
+    if (f >= nseg) return;
+    const int b = pos[f], len = pos[f + 1] - b;
+    if (len >= min_len) return;
+    const uint64_t w = before[f];
+    const int64_t r = (int64_t)(w & 0xffffffffu), p0 = (int64_t)(w >> 32);
+    if (j == 0) { lrows[r] = rowmap ? rowmap[f] : (int32_t)f; lpos[r] = (int32_t)p0; }
+    for (int i = j; i < len; i += 8) { lcrd[p0 + i] = crd[b + i]; lvals[p0 + i] = vals[b + i]; }
+}
+
+
+// Copies the segments of fewer than min_len nonzeros out (see LightCopy); nlight / light_nnz are their counts.
+hipError_t light_copy_build(const int32_t *pos, int64_t nseg, const int32_t *crd, const double *vals, int32_t min_len,
+                            const int32_t *rowmap, int64_t nlight, int64_t light_nnz, LightCopy &lc, hipStream_t st) {
+    lc = LightCopy();
+    DevRef flags = dev_alloc(sizeof(uint64_t) * nseg), before = dev_alloc(sizeof(uint64_t) * nseg);
+    lc.root = dev_alloc(2 * sizeof(int32_t));
+    lc.rows = dev_alloc(sizeof(int32_t) * nlight);
+    lc.pos = dev_alloc(sizeof(int32_t) * (nlight + 1));
+    lc.crd = dev_alloc(sizeof(int32_t) * light_nnz);
+    lc.vals = dev_alloc(sizeof(double) * light_nnz);
+    if (!flags || !before || !lc.root || !lc.rows || !lc.pos || !lc.crd || !lc.vals) { lc = LightCopy(); return hipErrorOutOfMemory; }
+    const unsigned grid = (unsigned)((nseg + 255) / 256);
+    hipLaunchKernelGGL(k_light_flags, dim3(grid), dim3(256), 0, st, pos, nseg, min_len, (uint64_t *)flags->ptr);
+    size_t temp_bytes = 0;
+    hipError_t e = reorder_scan_flags(nullptr, &temp_bytes, (const uint64_t *)flags->ptr, (uint64_t *)before->ptr, nseg, st);
+    if (e != hipSuccess) { lc = LightCopy(); return e; }
+    DevRef temp = dev_alloc(temp_bytes ? temp_bytes : 16);
+    if (!temp) { lc = LightCopy(); return hipErrorOutOfMemory; }
+    e = reorder_scan_flags(temp->ptr, &temp_bytes, (const uint64_t *)flags->ptr, (uint64_t *)before->ptr, nseg, st);
+    if (e != hipSuccess) { lc = LightCopy(); return e; }
+    hipLaunchKernelGGL(k_light_copy, dim3((unsigned)((nseg * 8 + 255) / 256)), dim3(256), 0, st, pos, crd, vals, nseg, min_len,
+                       (const uint64_t *)before->ptr, rowmap, (int32_t *)lc.rows->ptr, (int32_t *)lc.pos->ptr,
+                       (int32_t *)lc.crd->ptr, (double *)lc.vals->ptr);
+    const int32_t root[2] = {0, (int32_t)nlight}, last = (int32_t)light_nnz;
+    e = hipMemcpyAsync(lc.root->ptr, root, sizeof root, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipMemcpyAsync((int32_t *)lc.pos->ptr + nlight, &last, sizeof last, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);                     // host values and temporaries go out of scope
+    if (e != hipSuccess) { lc = LightCopy(); return e; }
+    lc.nrows = nlight; lc.nnz = light_nnz;
+    return hipGetLastError();
+}
+
 // ---- laying out the streams (once per tensor) ------------------------------------------------------------
 // Unit of lane-group slot gs (0 .. kGroupSlots-1) in round k: units come longest first and are dealt back and forth.
 __device__ __host__ inline int unit_of_slot(int gs, int k) { return k * kGroupSlots + ((k & 1) ? kGroupSlots - 1 - gs : gs); }
@@ -354,7 +415,7 @@ size_t heavy_partial_bytes(const HeavyPlan &plan, int64_t R) {
 }
 
 hipError_t heavy_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd, const double *vals, int64_t nnz,
-                            int64_t ncols, HeavyPlan &plan, hipStream_t st) {
+                            int64_t ncols, const int32_t *rowmap, HeavyPlan &plan, hipStream_t st) {
     plan = HeavyPlan();
     // worth it only when the dense operand is far larger than the caches and there is real work
     if (nnz < (int64_t(1) << 20) || ncols < (int64_t(1) << 16) || nseg < 1) return hipSuccess;
@@ -476,6 +537,14 @@ hipError_t heavy_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd
                        (int32_t *)plan.scode->ptr, (double *)plan.sval->ptr);
     e = hipStreamSynchronize(st);                                          // the host vectors and the temporaries go out of scope
     if (e != hipSuccess) { plan = HeavyPlan(); return e; }
+    // all other rows, copied out as a matrix (a matrix made of long rows only needs none)
+    if (nseg - nheavy > 0 && nnz - heavy_nnz > 0) {
+        e = light_copy_build(pos, nseg, crd, vals, (int32_t)kHeavyLen, rowmap, nseg - nheavy, nnz - heavy_nnz, plan.light, st);
+        if (e != hipSuccess) { plan = HeavyPlan(); return e; }
+    } else if (nseg - nheavy > 0) {
+        plan = HeavyPlan();                                                // empty rows only: leave it to the tiled kernel
+        return hipSuccess;
+    }
     plan.nheavy = nheavy; plan.nunits = nunits; plan.heavy_nnz = heavy_nnz; plan.nu = nu;
     plan.min_len = kHeavyLen; plan.window = kWindow; plan.nwin = (int32_t)nwin; plan.stream_items = npos;
     return hipGetLastError();
@@ -602,33 +671,6 @@ __global__ void __launch_bounds__(256) k_fiber_reduce(const double *__restrict__
     out[(int64_t)hseg[h] * R + r] = s;
 }
 
-// flags[f] = (length << 32) | 1 for a light fiber, 0 for a heavy one: one exclusive scan then gives every light
-// fiber its row number (low half) and the position of its first nonzero in the copy (high half)
-__global__ void __launch_bounds__(256) k_light_flags(const int32_t *__restrict__ pos, int64_t nseg, int32_t min_len,
-                                                     uint64_t *__restrict__ flags) {
-    const int64_t f = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (f >= nseg) return;
-    const int len = pos[f + 1] - pos[f];
-    flags[f] = len < min_len ? (((uint64_t)(uint32_t)len << 32) | 1u) : 0u;
-}
-
-// 8 lanes copy the nonzeros of one light fiber
-__global__ void __launch_bounds__(256) k_light_copy(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
-                                                    const double *__restrict__ vals, int64_t nseg, int32_t min_len,
-                                                    const uint64_t *__restrict__ before, int32_t *__restrict__ lrows,
-                                                    int32_t *__restrict__ lpos, int32_t *__restrict__ lcrd,
-                                                    double *__restrict__ lvals) {
-    const int64_t f = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 3;
-    const int j = threadIdx.x & 7;
-    if (f >= nseg) return;
-    const int b = pos[f], len = pos[f + 1] - b;
-    if (len >= min_len) return;
-    const uint64_t w = before[f];
-    const int64_t r = (int64_t)(w & 0xffffffffu), p0 = (int64_t)(w >> 32);
-    if (j == 0) { lrows[r] = (int32_t)f; lpos[r] = (int32_t)p0; }
-    for (int i = j; i < len; i += 8) { lcrd[p0 + i] = crd[b + i]; lvals[p0 + i] = vals[b + i]; }
-}
-
 int fiber_plan_index(int64_t R) { return R == 16 ? 0 : (R == 32 ? 1 : -1); }
 
 }  // namespace
@@ -695,39 +737,11 @@ hipError_t fiber_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd
     e = hipStreamSynchronize(st);                                          // the host vector goes out of scope
     if (e != hipSuccess) { plan = FiberPlan(); return e; }
     if (plan.nwin[0] == 0 && plan.nwin[1] == 0) { plan = FiberPlan(); return hipSuccess; }
-    // the light fibers, copied out as a matrix
+    // all other fibers, copied out as a matrix
     const int64_t nlight = nseg - nheavy, light_nnz = nnz - heavy_nnz;
     if (nlight < 1 || light_nnz < 1) { plan = FiberPlan(); return hipSuccess; }
-    {
-        DevRef flags = dev_alloc(sizeof(uint64_t) * nseg), before = dev_alloc(sizeof(uint64_t) * nseg);
-        plan.light_root = dev_alloc(2 * sizeof(int32_t));
-        plan.light_rows = dev_alloc(sizeof(int32_t) * nlight);
-        plan.light_pos = dev_alloc(sizeof(int32_t) * (nlight + 1));
-        plan.light_crd = dev_alloc(sizeof(int32_t) * light_nnz);
-        plan.light_vals = dev_alloc(sizeof(double) * light_nnz);
-        if (!flags || !before || !plan.light_root || !plan.light_rows || !plan.light_pos || !plan.light_crd || !plan.light_vals) {
-            plan = FiberPlan();
-            return hipErrorOutOfMemory;
-        }
-        hipLaunchKernelGGL(k_light_flags, dim3(grid), dim3(256), 0, st, pos, nseg, (int32_t)kFiberLen, (uint64_t *)flags->ptr);
-        size_t temp_bytes = 0;
-        e = reorder_scan_flags(nullptr, &temp_bytes, (const uint64_t *)flags->ptr, (uint64_t *)before->ptr, nseg, st);
-        if (e != hipSuccess) { plan = FiberPlan(); return e; }
-        DevRef temp = dev_alloc(temp_bytes ? temp_bytes : 16);
-        if (!temp) { plan = FiberPlan(); return hipErrorOutOfMemory; }
-        e = reorder_scan_flags(temp->ptr, &temp_bytes, (const uint64_t *)flags->ptr, (uint64_t *)before->ptr, nseg, st);
-        if (e != hipSuccess) { plan = FiberPlan(); return e; }
-        hipLaunchKernelGGL(k_light_copy, dim3((unsigned)((nseg * 8 + 255) / 256)), dim3(256), 0, st, pos, crd, vals, nseg,
-                           (int32_t)kFiberLen, (const uint64_t *)before->ptr, (int32_t *)plan.light_rows->ptr,
-                           (int32_t *)plan.light_pos->ptr, (int32_t *)plan.light_crd->ptr, (double *)plan.light_vals->ptr);
-        const int32_t root[2] = {0, (int32_t)nlight}, last = (int32_t)light_nnz;
-        e = hipMemcpyAsync(plan.light_root->ptr, root, sizeof root, hipMemcpyHostToDevice, st);
-        if (e == hipSuccess)
-            e = hipMemcpyAsync((int32_t *)plan.light_pos->ptr + nlight, &last, sizeof last, hipMemcpyHostToDevice, st);
-        if (e == hipSuccess) e = hipStreamSynchronize(st);                 // host values and temporaries go out of scope
-        if (e != hipSuccess) { plan = FiberPlan(); return e; }
-    }
-    plan.nlight = nlight; plan.light_nnz = light_nnz;
+    e = light_copy_build(pos, nseg, crd, vals, (int32_t)kFiberLen, nullptr, nlight, light_nnz, plan.light, st);
+    if (e != hipSuccess) { plan = FiberPlan(); return e; }
     plan.nheavy = nheavy; plan.heavy_nnz = heavy_nnz; plan.min_len = kFiberLen;
     return hipGetLastError();
 }

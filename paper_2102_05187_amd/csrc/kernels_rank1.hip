@@ -220,7 +220,7 @@ __global__ void __launch_bounds__(256) k_stream_rank1(const int32_t *__restrict_
     const int64_t tb = t * (int64_t)kTile;
     Rank1Half h0;
     rank1_load_half(h0, crd, vals, tb + (int64_t)(threadIdx.x >> 6) * kWaveItems, threadIdx.x & 63, nnz);
-    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, 1, 0, 0, false, ep);
+    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, 1, false, ep);
     walk_rank1<ROWMAP>(h0, ts, crd, vals, x, rowmap, out, tb, nnz, wsum_ht, wsum_open, wsum_first, wsum_first_id, ep);
     __syncthreads();
     finish_tile_rank1<ROWMAP>(wsum_ht, wsum_open, wsum_first, wsum_first_id, rowmap, out, carry_view(scratch, ntiles, 1), t, ep);
@@ -571,10 +571,9 @@ size_t stream_scratch_bytes(int64_t ntiles, int64_t R) {
 
 hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                             const int32_t *rowmap, const double *Dn, int64_t dense_rows, int64_t R, double *out,
-                            void *scratch, bool plain, hipStream_t st, int32_t heavy_len, Epilogue ep) {
+                            void *scratch, bool plain, hipStream_t st, Epilogue ep) {
     if (sc.ntiles <= 0) return hipSuccess;
     if (!stream_supports_rank(R)) return hipErrorNotSupported;
-    if (heavy_len > 0 && (R == 1 || heavy_len < 256)) return hipErrorNotSupported;
     const int32_t *sb = (const int32_t *)sc.seg_begin->ptr;
     hipError_t e = hipSuccess;
     if (R == 1) {
@@ -610,7 +609,7 @@ hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_
                                rowmap, Dn, out, sc.nnz, sc.ntiles, scratch, ep);
         e = hipGetLastError();
     } else {
-        e = stream_segreduce_rankR(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st, heavy_len, ep);
+        e = stream_segreduce_rankR(sc, pos, crd, vals, rowmap, Dn, (int)R, out, scratch, st, ep);
     }
     if (e != hipSuccess) return e;
     // the rank-R kernel publishes result rows as ids, the rank-1 kernel segment numbers

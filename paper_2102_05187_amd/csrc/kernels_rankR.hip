@@ -7,15 +7,13 @@ namespace {
 
 // ROWMAP: segment s writes result row rowmap[s]; the tail map then holds rows, and so do the ids this kernel
 // publishes in its carries (the fix-up takes them as rows).
-// HEAVY: segments of at least heavy_len nonzeros belong to the heavy-row sweep: their nonzeros are skipped
-// (no gather, nothing added) and their rows are not written.
-template <int L, int V, bool WIDE, bool ROWMAP, bool HEAVY>
+template <int L, int V, bool WIDE, bool ROWMAP>
 __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict__ pos, const int32_t *__restrict__ crd,
                                                       const double *__restrict__ vals,
                                                       const int32_t *__restrict__ seg_begin,
                                                       const int32_t *__restrict__ rowmap, const double *__restrict__ Dn,
                                                       double *__restrict__ out, int64_t nnz, int64_t ntiles, int R,
-                                                      void *scratch, int32_t heavy_len, int32_t nseg, Epilogue ep) {
+                                                      void *scratch, Epilogue ep) {
     constexpr int NW = 256 / L;                // walkers per tile
     constexpr int WI = kTile / NW;             // items per walker
     using RL = RecLayout<L, 2>;                // record = {row offset in doubles, tail id} + value
@@ -28,19 +26,9 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
     const int64_t tb = t * (int64_t)kTile;
     const int g = threadIdx.x / L, j = threadIdx.x % L;
     const int64_t gb = tb + (int64_t)g * WI;                      // first item of this walker
-    if constexpr (HEAVY) {
-        // one heavy segment covers the whole tile: nothing to do but to publish an empty summary
-        const int32_t s0 = seg_begin[t], s1 = seg_begin[t + 1];
-        if (s0 == s1 && pos[s0 + 1] - pos[s0] >= heavy_len) {
-            CarryView cb = carry_view(scratch, ntiles, R);
-            for (int r = threadIdx.x; r < R; r += 256) { cb.first[t * R + r] = 0.0; cb.open[t * R + r] = 0.0; }
-            if (threadIdx.x == 0) { cb.has_tail[t] = 0; cb.first_id[t] = -1; }
-            return;
-        }
-    }
     LaneItems cur;
     lane_load_items(cur, crd, vals, gb + 4 * j, nnz);             // in flight while the map is built
-    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, R, HEAVY ? heavy_len : 0, nseg, ROWMAP, ep);
+    build_tail_map_from_pos(ts, pos, rowmap, tb, seg_begin[t], seg_begin[t + 1], out, R, ROWMAP, ep);
 
     WalkState<V> st;
 #pragma unroll
@@ -58,12 +46,6 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
         if (sb + 1 < WI / SB) lane_load_items(nxt, crd, vals, i0 + SB, nnz);
         {
             const int4 t4 = *reinterpret_cast<const int4 *>(ts + (i0 - tb));
-            if constexpr (HEAVY) {                                // skipped items add 0 * 0
-                if (t4.x == kSkipItem) cur.va[0] = 0.0;
-                if (t4.y == kSkipItem) cur.va[1] = 0.0;
-                if (t4.z == kSkipItem) cur.va[2] = 0.0;
-                if (t4.w == kSkipItem) cur.va[3] = 0.0;
-            }
             *reinterpret_cast<int4 *>(rec + 8 * j) =
                 make_int4((int)((unsigned)cur.cr[0] * Ru), t4.x, (int)((unsigned)cur.cr[1] * Ru), t4.y);
             *reinterpret_cast<int4 *>(rec + 8 * j + 4) =
@@ -80,12 +62,7 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
                 const int2 ct = *reinterpret_cast<const int2 *>(rec + 2 * k);
                 b.a = *reinterpret_cast<const double *>(rec + RL::kVal + 2 * k);
                 b.tail = ct.y;
-                if (HEAVY && ct.y == kSkipItem) {
-#pragma unroll
-                    for (int q = 0; q < V; ++q) b.d[q] = 0.0;
-                } else {
-                    grp_load_row_off<L, V, WIDE>(Dn, (unsigned)ct.x + slot, R, j, b.d);
-                }
+                grp_load_row_off<L, V, WIDE>(Dn, (unsigned)ct.x + slot, R, j, b.d);
             });
         };
         auto consume = [&](auto gc, const RowBuf<V> *bb) {
@@ -130,28 +107,19 @@ __global__ void __launch_bounds__(256) k_stream_rankR(const int32_t *__restrict_
                                     carry_view(scratch, ntiles, R), t, ep);
 }
 
-template <int L, int V, bool WIDE, bool ROWMAP, bool HEAVY>
+template <int L, int V, bool WIDE, bool ROWMAP>
 void launch_rankR_one(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals, const int32_t *rowmap,
-                      const double *Dn, int R, double *out, void *scratch, hipStream_t st, int32_t heavy_len, Epilogue ep) {
-    hipLaunchKernelGGL((k_stream_rankR<L, V, WIDE, ROWMAP, HEAVY>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
-                       (const int32_t *)sc.seg_begin->ptr, rowmap, Dn, out, sc.nnz, sc.ntiles, R, scratch, heavy_len,
-                       (int32_t)sc.nseg, ep);
+                      const double *Dn, int R, double *out, void *scratch, hipStream_t st, Epilogue ep) {
+    hipLaunchKernelGGL((k_stream_rankR<L, V, WIDE, ROWMAP>), dim3((unsigned)sc.ntiles), dim3(256), 0, st, pos, crd, vals,
+                       (const int32_t *)sc.seg_begin->ptr, rowmap, Dn, out, sc.nnz, sc.ntiles, R, scratch, ep);
 }
 
 template <int L, int V, bool WIDE>
 hipError_t launch_rankR(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                         const int32_t *rowmap, const double *Dn, int R, double *out, void *scratch, hipStream_t st,
-                        int32_t heavy_len, Epilogue ep) {
-    if constexpr (WIDE && L == 8) {                           // the heavy-row sweep exists for these ranks only
-        if (heavy_len > 0) {
-            if (rowmap) launch_rankR_one<L, V, WIDE, true, true>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, heavy_len, ep);
-            else launch_rankR_one<L, V, WIDE, false, true>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, heavy_len, ep);
-            return hipGetLastError();
-        }
-    }
-    if (heavy_len > 0) return hipErrorNotSupported;
-    if (rowmap) launch_rankR_one<L, V, WIDE, true, false>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, 0, ep);
-    else launch_rankR_one<L, V, WIDE, false, false>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, 0, ep);
+                        Epilogue ep) {
+    if (rowmap) launch_rankR_one<L, V, WIDE, true>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, ep);
+    else launch_rankR_one<L, V, WIDE, false>(sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, ep);
     return hipGetLastError();
 }
 
@@ -159,8 +127,8 @@ hipError_t launch_rankR(const Schedule &sc, const int32_t *pos, const int32_t *c
 
 hipError_t stream_segreduce_rankR(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                                   const int32_t *rowmap, const double *Dn, int R, double *out, void *scratch,
-                                  hipStream_t st, int32_t heavy_len, Epilogue ep) {
-    return COMET_DISPATCH_RANK(launch_rankR, R, sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, heavy_len, ep);
+                                  hipStream_t st, Epilogue ep) {
+    return COMET_DISPATCH_RANK(launch_rankR, R, sc, pos, crd, vals, rowmap, Dn, R, out, scratch, st, ep);
 }
 
 }  // namespace comet

@@ -39,7 +39,7 @@ hipError_t run_fixup(void *scratch, int64_t ntiles, int R, const int32_t *rowmap
 // Rank-R part of stream_segreduce (defined in kernels_rankR.hip).
 hipError_t stream_segreduce_rankR(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                                   const int32_t *rowmap, const double *Dn, int R, double *out, void *scratch,
-                                  hipStream_t st, int32_t heavy_len, Epilogue ep = Epilogue());
+                                  hipStream_t st, Epilogue ep = Epilogue());
 
 namespace {
 
@@ -68,48 +68,25 @@ __host__ __device__ inline CarryView carry_view(void *scratch, int64_t n, int64_
 // ---- phase A/B for compressed levels: fill the tail map from pos, zero-fill empty segments -------
 // Segments [seg_begin[t], seg_begin[t+1]) end inside tile t (the segment that contains the first
 // item of the next tile ends later), so each of them owns exactly one map entry.
-// heavy_len > 0: segments of at least heavy_len nonzeros are left to another kernel -- they get no map
-// entry (their result row is not written here) and their items inside the tile are marked kSkipItem.
 // rows_in_map: the entry of a segment end is the segment's result row rowmap[s] instead of s (looked up here by
 // all threads at once, so that the walk has no dependent load at a segment end); ids are opaque to the fix-up.
-constexpr int32_t kSkipItem = -2;
 __device__ __forceinline__ void build_tail_map_from_pos(int32_t *ts, const int32_t *__restrict__ pos,
                                                         const int32_t *__restrict__ rowmap, int64_t tb, int32_t s0,
                                                         int32_t s1, double *__restrict__ out, int R,
-                                                        int32_t heavy_len = 0, int32_t nseg = 0,
                                                         bool rows_in_map = false, const Epilogue ep = Epilogue()) {
-    __shared__ int hv_lo[24], hv_hi[24], hv_n;      // heavy pieces inside the tile: at most kTile / heavy_len + 2
-    if (threadIdx.x == 0) hv_n = 0;
     for (int i = threadIdx.x * 4; i < kTile; i += blockDim.x * 4)
         *reinterpret_cast<int4 *>(ts + i) = make_int4(-1, -1, -1, -1);
     __syncthreads();
     for (int32_t s = s0 + threadIdx.x; s < s1; s += blockDim.x) {
         int32_t b = pos[s], e = pos[s + 1];
-        if (heavy_len > 0 && e - b >= heavy_len) {
-            const int k = atomicAdd(&hv_n, 1);
-            if (k < 24) { hv_lo[k] = (int64_t)b > tb ? (int)((int64_t)b - tb) : 0; hv_hi[k] = (int)((int64_t)e - tb); }
-        } else if (e > b) {
+        if (e > b) {
             ts[(int64_t)e - 1 - tb] = rows_in_map ? rowmap[s] : s;
         } else {
             int64_t row = rowmap ? (int64_t)rowmap[s] : (int64_t)s;
             for (int r = 0; r < R; ++r) out[row * R + r] = ep_empty(ep, out + row * R + r);
         }
     }
-    if (heavy_len > 0 && threadIdx.x == 0 && s1 < nseg) {
-        // the segment that holds the first item of the next tile: its leading part may lie in this tile
-        const int32_t b = pos[s1], e = pos[s1 + 1];
-        if (e - b >= heavy_len && (int64_t)b < tb + kTile) {
-            const int k = atomicAdd(&hv_n, 1);
-            if (k < 24) { hv_lo[k] = (int64_t)b > tb ? (int)((int64_t)b - tb) : 0; hv_hi[k] = kTile; }
-        }
-    }
     __syncthreads();
-    if (heavy_len > 0) {
-        const int n = hv_n < 24 ? hv_n : 24;
-        for (int k = 0; k < n; ++k)
-            for (int i = hv_lo[k] + (int)threadIdx.x; i < hv_hi[k]; i += blockDim.x) ts[i] = kSkipItem;
-        __syncthreads();
-    }
 }
 
 // Cross-lane broadcast inside a lane group (quad_perm inside a quad, plus one row_shr:4 / row_shl:4 with a

@@ -25,11 +25,9 @@ size_t stream_scratch_bytes(int64_t ntiles, int64_t R);
 // Every segment of the level is written (empty ones with zeros).  dense_rows = number of rows of Dn.
 // plain = true keeps rank-1 work on the per-tile kernel that gathers the vector through L1 (measurement
 // baseline) instead of the kernel that stages it in LDS.
-// heavy_len > 0 (rank > 1 only): segments of at least that many nonzeros are left out altogether -- their
-// nonzeros are skipped and their rows are not written; the heavy-row sweep produces them.
 hipError_t stream_segreduce(const Schedule &sc, const int32_t *pos, const int32_t *crd, const double *vals,
                             const int32_t *rowmap, const double *Dn, int64_t dense_rows, int64_t R, double *out,
-                            void *scratch, bool plain, hipStream_t st, int32_t heavy_len = 0, Epilogue ep = Epilogue());
+                            void *scratch, bool plain, hipStream_t st, Epilogue ep = Epilogue());
 
 // Sorted COO [CN,S,S]: one output (i, j, value) per run of equal (c0, c1).
 hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *c1, const int32_t *c2,
@@ -39,8 +37,9 @@ hipError_t stream_ttv_coo(const Schedule &sc, const int32_t *c0, const int32_t *
 // ---- heavy-row sweep of SpMM (kernels_heavy.hip) ---------------------------------------------------
 // Builds the plan for a [*,CU] matrix level (pos over nseg segments, crd with coordinates < ncols); leaves
 // plan.nunits = 0 when the rows of >= min_len nonzeros hold too small a share to matter.  Synchronises.
+// rowmap (or null): result row of segment s, composed into the copy of the other rows (plan.light).
 hipError_t heavy_plan_build(const int32_t *pos, int64_t nseg, const int32_t *crd, const double *vals, int64_t nnz,
-                            int64_t ncols, HeavyPlan &plan, hipStream_t st);
+                            int64_t ncols, const int32_t *rowmap, HeavyPlan &plan, hipStream_t st);
 // The sweep exists for ranks 16, 32, 48 and 64, as long as the sums of a compute unit's units fit its LDS.
 bool   heavy_supports(const HeavyPlan &plan, int64_t R);
 size_t heavy_partial_bytes(const HeavyPlan &plan, int64_t R);

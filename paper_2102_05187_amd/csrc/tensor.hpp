@@ -45,6 +45,21 @@ constexpr int kTile = 4096;
 // Items per chunk of the wavefront-per-chunk kernel (one wavefront's share of a tile).
 constexpr int kChunk = 1024;
 
+// The segments (rows / fibers) of a compressed level that a sweep does NOT take, copied out as a [CU,CU] matrix
+// of their own: row r of the copy holds the nonzeros of one such segment and stands for result row rows[r].
+// The nonzero-tiled kernel then walks them without the long segments in between -- skipping those inside the
+// original arrays saves little: the lane groups of a wavefront sit 128 items apart, a wavefront step is free
+// only where all of them skip, and the per-tile work stays.
+struct LightCopy {
+    int64_t nrows = 0, nnz = 0;
+    DevRef  root;         // int32 [2]: {0, nrows}
+    DevRef  rows;         // int32 [nrows]: result row of row r of the copy, increasing
+    DevRef  pos;          // int32 [nrows + 1]
+    DevRef  crd;          // int32 [nnz]
+    DevRef  vals;         // double [nnz]
+    size_t bytes() const { return (size_t)nnz * 12 + (size_t)nrows * 8; }
+};
+
 // Plan of the heavy-row sweep of SpMM (kernels_heavy.hip), built once at creation for matrices whose long
 // rows hold a large share of the nonzeros.  Rows of at least `min_len` nonzeros are "heavy"; each is cut
 // into units of roughly equal length, every lane group of the sweep owns `nu` units, and the nonzeros of
@@ -60,6 +75,7 @@ struct HeavyPlan {
     DevRef  scrd, scode, sval;   // the streams: column, item code (-1 plain, -2 padding, k >= 0: ends unit slot k's piece), value
     DevRef  block_start;  // int32 [wavefronts + 1]: first super-block (8 groups x 32 positions) of each wavefront's stream
     DevRef  wend;         // int32 [wavefronts][windows per range + 1]: first position of each window in the stream
+    LightCopy light;      // all other rows
 };
 
 // Plan of the heavy-fiber sweep of TTM (kernels_heavy.hip), built once at creation for order-3 tensors whose
@@ -74,15 +90,7 @@ struct FiberPlan {
     int32_t window[2] = {0, 0}, nwin[2] = {0, 0};
     DevRef  hseg;         // int32 [nheavy]: leaf segment (fiber) of heavy fiber h, longest fibers first
     DevRef  wstart[2];    // int32 [nheavy][nwin + 1]: first position of fiber h with coordinate >= w * window
-    // The other fibers, copied out so that the nonzero-tiled kernel walks them without the long ones in between
-    // (skipping inside the original arrays saves nothing: the lane groups of a wavefront sit 128 items apart, and
-    // a wavefront step is free only where all of them skip).  A [CU,CU] matrix: row r is fiber light_rows[r].
-    int64_t nlight = 0, light_nnz = 0;
-    DevRef  light_root;   // int32 [2]: {0, nlight}
-    DevRef  light_rows;   // int32 [nlight]: fiber of light row r, increasing
-    DevRef  light_pos;    // int32 [nlight + 1]
-    DevRef  light_crd;    // int32 [light_nnz]
-    DevRef  light_vals;   // double [light_nnz]
+    LightCopy light;      // all other fibers (row = fiber)
 };
 
 // Per-tensor schedule for the nonzero-tiled kernels, built once at creation.
