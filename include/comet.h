@@ -62,6 +62,9 @@ typedef enum {
 #define COMET_BORROW   0u   /* default: the caller keeps pos/crd/vals alive until destroy       */
 #define COMET_COPY     1u   /* the library copies pos/crd/vals into memory it owns              */
 #define COMET_VALIDATE 2u   /* run the device-side structure check (see below)                  */
+#define COMET_LEAN     4u   /* keep no copies of parts of the tensor: the heavy-row sweep of    */
+                            /* comet_spmm and the heavy-fiber sweep of comet_ttm are not planned */
+                            /* (same results from the nonzero-tiled kernels alone, less memory) */
 
 typedef struct comet_tensor comet_tensor;   /* opaque, library-owned */
 
@@ -100,7 +103,7 @@ typedef struct {
  *            Expected lengths: D 1; root CU or CN 2; non-root CU (#parent positions)+1.
  *   crd      host array of [order] device pointers; crd_len host, [order].  NULL / 0 for D.
  *   vals     device, [nvals]; one value per position of the last level.  nvals < 2^31.
- *   flags    COMET_BORROW | COMET_COPY, optionally | COMET_VALIDATE.
+ *   flags    COMET_BORROW | COMET_COPY, optionally | COMET_VALIDATE, optionally | COMET_LEAN.
  *
  * Cheap consistency checks (lengths, root pos contents, D size == dims) always run.  With
  * COMET_VALIDATE a device pass also checks: pos starts at 0, is non-decreasing and ends at

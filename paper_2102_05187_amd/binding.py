@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcomet_hip.so")
 
 COMET_D, COMET_CU, COMET_CN, COMET_S = 0, 1, 2, 3
-COMET_BORROW, COMET_COPY, COMET_VALIDATE = 0, 1, 2
+COMET_BORROW, COMET_COPY, COMET_VALIDATE, COMET_LEAN = 0, 1, 2, 4
 COMET_OK = 0
 COMET_MAX_ORDER = 4
 

@@ -61,7 +61,7 @@ static comet_status make_light_handle(comet_tensor &t, const comet::LightCopy &l
     const int32_t *cc[2] = {(const int32_t *)lc.rows->ptr, (const int32_t *)lc.crd->ptr};
     const int64_t pl[2] = {2, lc.nrows + 1}, cl[2] = {lc.nrows, lc.nnz};
     comet_tensor *lh = nullptr;
-    comet_status ls = comet_tensor_create(&lh, 2, dims2, lv, pp, pl, cc, cl, (const double *)lc.vals->ptr, lc.nnz, 0, st);
+    comet_status ls = comet_tensor_create(&lh, 2, dims2, lv, pp, pl, cc, cl, (const double *)lc.vals->ptr, lc.nnz, COMET_LEAN, st);
     if (ls != COMET_OK) return ls;
     t.light.reset(lh);
     return COMET_OK;
@@ -113,20 +113,22 @@ comet_status build_schedule(comet_tensor &t, hipStream_t st) {
             if (rs != COMET_OK) return rs;
             sc.max_root_gap = h;
         }
-        if (t.fmt == Format::CSR || t.fmt == Format::DCSR) {
-            HIP_TRY(comet::heavy_plan_build(t.pos_i(1), sc.nseg, t.crd_i(1), t.vals_d(), sc.nnz, t.dims[1],
-                                            t.fmt == Format::DCSR ? t.crd_i(0) : nullptr, sc.heavy, st));
-            if (sc.heavy.nunits > 0 && sc.heavy.light.nrows > 0) {
-                comet_status ls = make_light_handle(t, sc.heavy.light, t.dims[0], t.dims[1], st);
-                if (ls != COMET_OK) return ls;
-            }
+        if ((t.fmt == Format::CSR || t.fmt == Format::DCSR) && !t.lean) {
+            // the plans are optional: without the memory for one, the tiled kernel takes everything
+            hipError_t pe = comet::heavy_plan_build(t.pos_i(1), sc.nseg, t.crd_i(1), t.vals_d(), sc.nnz, t.dims[1],
+                                                    t.fmt == Format::DCSR ? t.crd_i(0) : nullptr, sc.heavy, st);
+            if (pe == hipErrorOutOfMemory) { (void)hipGetLastError(); sc.heavy = comet::HeavyPlan(); pe = hipSuccess; }
+            HIP_TRY(pe);
+            if (sc.heavy.nunits > 0 && sc.heavy.light.nrows > 0 &&
+                make_light_handle(t, sc.heavy.light, t.dims[0], t.dims[1], st) != COMET_OK)
+                sc.heavy = comet::HeavyPlan();          // no sweep then: the tiled kernel takes every row
         }
-        if (t.fmt == Format::CSF3) {
-            HIP_TRY(comet::fiber_plan_build(t.pos_i(2), sc.nseg, t.crd_i(2), t.vals_d(), sc.nnz, t.dims[2], sc.fibers, st));
-            if (sc.fibers.nheavy > 0) {
-                comet_status ls = make_light_handle(t, sc.fibers.light, sc.nseg, t.dims[2], st);
-                if (ls != COMET_OK) return ls;
-            }
+        if (t.fmt == Format::CSF3 && !t.lean) {
+            hipError_t pe = comet::fiber_plan_build(t.pos_i(2), sc.nseg, t.crd_i(2), t.vals_d(), sc.nnz, t.dims[2], sc.fibers, st);
+            if (pe == hipErrorOutOfMemory) { (void)hipGetLastError(); sc.fibers = comet::FiberPlan(); pe = hipSuccess; }
+            HIP_TRY(pe);
+            if (sc.fibers.nheavy > 0 && make_light_handle(t, sc.fibers.light, sc.nseg, t.dims[2], st) != COMET_OK)
+                sc.fibers = comet::FiberPlan();         // no sweep then: the tiled kernel takes every fiber
         }
         if (t.fmt == Format::CSF3) {
             HIP_TRY(hipMemsetAsync(mx->ptr, 0, sizeof(int32_t), st));
@@ -291,7 +293,7 @@ comet_status comet_tensor_create(comet_tensor **out, int order, const int64_t *d
     if (order < 1 || order > COMET_MAX_ORDER) return COMET_ERR_UNSUPPORTED;
     if (nvals < 0 || nvals >= (int64_t(1) << 31)) return COMET_ERR_INVALID_ARG;
     if (nvals > 0 && !vals) return COMET_ERR_INVALID_ARG;
-    if (flags & ~(COMET_COPY | COMET_VALIDATE)) return COMET_ERR_INVALID_ARG;
+    if (flags & ~(COMET_COPY | COMET_VALIDATE | COMET_LEAN)) return COMET_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
 
     comet_tensor *t = new (std::nothrow) comet_tensor();
@@ -299,6 +301,7 @@ comet_status comet_tensor_create(comet_tensor **out, int order, const int64_t *d
     std::unique_ptr<comet_tensor> guard(t);
     t->order = order;
     t->nvals = nvals;
+    t->lean = (flags & COMET_LEAN) != 0;
     for (int l = 0; l < order; ++l) {
         if (dims[l] < 0 || dims[l] >= (int64_t(1) << 31)) return COMET_ERR_INVALID_ARG;
         if ((int)levels[l] < 0 || (int)levels[l] > 3) return COMET_ERR_INVALID_ARG;
@@ -656,6 +659,7 @@ static comet_status restore(const comet_tensor *X, const int32_t *mode_order, Ta
         }
     }
     t->fmt = classify(order, t->levels);
+    t->lean = X->lean;                          // a lean handle's re-stored forms are lean too
     comet_status rs = build_schedule(*t, st);   // synchronises: the temporaries above may go
     if (rs != COMET_OK) return rs;
     *out = guard.release();

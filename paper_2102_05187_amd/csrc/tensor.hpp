@@ -130,6 +130,7 @@ struct comet_tensor {
     comet::Format fmt = comet::Format::OTHER;
     comet::Schedule sched;
     int variant = 0;
+    bool lean = false;     // created with COMET_LEAN: no sweep plans, no copies
 
     // Scratch owned by the handle (carry buffers of the tiled kernels and the partial sums of the heavy-row
     // sweep).  It only ever grows: when an operation needs more than there is, a larger buffer is allocated

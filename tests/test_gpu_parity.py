@@ -141,6 +141,29 @@ def test_spmm_with_heavy_rows(comet, name, layout, R, variant):
     assert torch.equal(C, C2), "two runs differ"
 
 
+def test_lean_handles_plan_no_sweeps_and_give_the_same_results(comet):
+    """COMET_LEAN: no sweep plans and none of their copies; SpMM and TTM then run on the tiled kernels alone."""
+    (I, J), (rows, cols, vals) = _heavy_row_matrix()
+    L = fmt.pack_csr(I, J, rows, cols, vals).to("cuda")
+    full = comet.from_levels(L)
+    lean = comet.from_levels(L, flags=comet.COMET_VALIDATE | comet.COMET_LEAN)
+    assert full.heavy_plan()[0] > 0 and full.heavy_stream_bytes() > 0
+    assert lean.heavy_plan() == (0, 0) and lean.heavy_stream_bytes() == 0
+    B = dev(gen.dense_operand(2, 0, (J, 32)))
+    ref, absum = oracle.spmm(np_(rows), np_(cols), np_(vals), (I, J), np_(B))
+    assert_values_close(np_(comet.comet_spmm(lean, B)), ref, absum, "lean spmm")
+    assert_values_close(np_(comet.comet_spmm(full, B)), ref, absum, "spmm with the sweep")
+    dims, (i, j, k, v), _ = _heavy_fiber_tensor()
+    T = fmt.pack_csf3(dims, i, j, k, v).to("cuda")
+    lean3 = comet.from_levels(T, flags=comet.COMET_VALIDATE | comet.COMET_LEAN)
+    assert lean3.heavy_plan() == (0, 0) and lean3.heavy_stream_bytes() == 0
+    U = gen.dense_operand(4, 0, (dims[2], 16))
+    Y = comet.comet_ttm(lean3, 2, dev(U))
+    torch.cuda.synchronize()
+    reft = oracle.ttm(np_(i), np_(j), np_(k), np_(v), dims, np_(U))
+    assert_values_close(np_(Y.vals()).reshape(-1, 16), reft["vals"], reft["abs"], "lean ttm")
+
+
 @pytest.mark.parametrize("R", [1, 16])
 @pytest.mark.parametrize("name", ["zipf_rows", "edge_lengths", "hypersparse", "empty", "single"])
 def test_products_of_a_coordinate_list_matrix(comet, name, R):
