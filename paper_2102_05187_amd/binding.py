@@ -135,6 +135,7 @@ class Tensor:
         self._h = ctypes.c_void_p(handle)
         self._keep = list(keep)
         self._parent = parent      # a result shares level arrays with its input
+        self._dims = None
 
     @property
     def handle(self) -> ctypes.c_void_p:
@@ -158,8 +159,11 @@ class Tensor:
         return [int(inf.levels[l]) for l in range(inf.order)]
 
     def dims(self) -> List[int]:
-        inf = self.info()
-        return [int(inf.dims[l]) for l in range(inf.order)]
+        # sizes per level never change for a handle: looked up once (the products are launch-bound on small inputs)
+        if self._dims is None:
+            inf = self.info()
+            self._dims = [int(inf.dims[l]) for l in range(inf.order)]
+        return list(self._dims)
 
     def mode_of_level(self) -> List[int]:
         inf = self.info()
