@@ -10,15 +10,26 @@
 
 namespace {
 
+// Each workgroup takes consecutive 32 KB pieces (eight 16-byte loads per lane in flight, each one a contiguous
+// 4 KB across the workgroup), workgroups taking the pieces in turn; non-temporal loads as for the operations' streams.
 __global__ void __launch_bounds__(256) k_cal_read(const double2 *__restrict__ a, int64_t n2, double *__restrict__ sink) {
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    typedef double v2d __attribute__((ext_vector_type(2)));
+    const v2d *p = reinterpret_cast<const v2d *>(a);
+    constexpr int kPer = 8;
+    const int64_t piece = 256 * kPer, npieces = n2 / piece;
     double s = 0.0;
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < n2; i += 4 * stride) {
-        const double2 v0 = a[i], v1 = a[i + stride], v2 = a[i + 2 * stride], v3 = a[i + 3 * stride];
-        s += (v0.x + v0.y) + (v1.x + v1.y) + (v2.x + v2.y) + (v3.x + v3.y);
+    for (int64_t pc = blockIdx.x; pc < npieces; pc += gridDim.x) {
+        const int64_t base = pc * piece + threadIdx.x;
+        v2d v[kPer];
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) v[u] = __builtin_nontemporal_load(p + base + 256 * u);
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) s += v[u].x + v[u].y;
     }
-    for (; i < n2; i += stride) { const double2 v = a[i]; s += v.x + v.y; }
+    for (int64_t i = npieces * piece + (int64_t)blockIdx.x * 256 + threadIdx.x; i < n2; i += (int64_t)gridDim.x * 256) {
+        const v2d v = p[i];
+        s += v.x + v.y;
+    }
     if (s == 1.2345e300) sink[0] = s;                      // never true for finite data: keeps the loads alive
 }
 
