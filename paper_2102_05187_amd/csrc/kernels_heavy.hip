@@ -1,3 +1,9 @@
+// The two sweeps that take the long segments of a power-law tensor out of the nonzero-tiled kernels' hands,
+// and the compacted copy of all other segments that those kernels then walk:
+//   - the heavy-row sweep of SpMM (this comment; kernels k_heavy_sweep, k_heavy_reduce),
+//   - the heavy-fiber sweep of TTM (second half of the file; k_fiber_sweep, k_fiber_reduce),
+//   - light_copy_build (the copy; see LightCopy in tensor.hpp).
+//
 // Heavy-row sweep of SpMM: the long rows of a power-law matrix, processed so that the rows of the dense
 // operand they gather are shared through the L2 caches instead of being fetched from memory once per nonzero.
 //

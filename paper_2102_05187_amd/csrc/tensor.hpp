@@ -64,8 +64,8 @@ struct LightCopy {
 // rows hold a large share of the nonzeros.  Rows of at least `min_len` nonzeros are "heavy"; each is cut
 // into units of roughly equal length, every lane group of the sweep owns `nu` units, and the nonzeros of
 // the heavy rows are laid out again as one stream per wavefront in the order the sweep takes them (window
-// by window, unit by unit; 16 bytes per stream item, padding included) -- the one place where the library
-// keeps a re-ordered copy of (a part of) a tensor, because the order is what makes the cache reuse work.
+// by window, unit by unit; 16 bytes per stream item, padding included) -- a re-ordered copy of a part of the
+// tensor, kept because the order is what makes the cache reuse work.
 struct HeavyPlan {
     int64_t nheavy = 0, nunits = 0, heavy_nnz = 0, stream_items = 0;
     int32_t min_len = 0, window = 0, nwin = 0, nu = 0;

@@ -563,3 +563,42 @@ def test_operations_replay_from_a_captured_graph(comet):
         got = (C, y, M, Yv.vals(), Ym.vals())
         for a, b in zip(got, want):
             assert torch.equal(a, b), "replay %d differs from the eager result" % rep
+
+
+def test_the_sweeps_replay_from_a_captured_graph(comet):
+    """SpMM with its heavy-row sweep and TTM with its heavy-fiber sweep (each with the tiled kernel on the copy
+    of the other rows / fibers) are kernel launches only once the scratch exists: captured and replayed, with
+    eager work in between, they reproduce the eager results bit for bit."""
+    (I, J), (rows, cols, vals) = _heavy_row_matrix()
+    A = comet.from_levels(fmt.pack_csr(I, J, rows, cols, vals).to("cuda"))
+    dims, (i, j, k, tv), _ = _heavy_fiber_tensor()
+    X = comet.from_levels(fmt.pack_csf3(dims, i, j, k, tv).to("cuda"))
+    assert A.heavy_plan()[0] > 0 and X.heavy_plan()[0] > 0
+    A.reserve(32)
+    X.reserve(16)
+    B = dev(gen.dense_operand(43, 0, (J, 32)))
+    U = dev(gen.dense_operand(43, 1, (dims[2], 16)))
+    C = torch.empty((I, 32), dtype=torch.float64, device="cuda")
+    Y = comet.comet_ttm(X, 2, U)
+
+    def run_all():
+        comet.comet_spmm(A, B, C)
+        comet.comet_ttm(X, 2, U, Y)
+
+    run_all()
+    torch.cuda.synchronize()
+    want = [C.clone(), Y.vals().clone()]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run_all()
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        run_all()
+    for rep in range(3):
+        C.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(C, want[0]) and torch.equal(Y.vals(), want[1]), "replay %d differs from the eager result" % rep
