@@ -42,8 +42,8 @@ namespace {
 
 constexpr int kXcd = 8;              // XCDs of the device = number of column ranges
 constexpr int kWindow = 4096;        // columns per window
-constexpr int kHeavyLen = 256;       // a row with at least this many nonzeros is heavy
-constexpr int kUnitLen = 2048;       // target nonzeros per unit
+constexpr int kHeavyLen = 128;       // a row with at least this many nonzeros is heavy
+constexpr int kUnitLen = 4096;       // target nonzeros per unit
 constexpr int kHeavyThreads = 1024;  // one workgroup fills a compute unit: 16 wavefronts, 128 lane groups of 8 lanes
 constexpr int kHeavyGroups = kHeavyThreads / 8;
 constexpr int kSlots = 32;           // workgroups per column range (= compute units of an XCD)

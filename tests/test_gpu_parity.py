@@ -104,12 +104,15 @@ def test_spmm(comet, name, layout, R, variant):
     assert_values_close(np_(C), ref, absum, "spmm %s R=%d" % (name, R))
 
 
+HEAVY_ROW = 128      # rows of at least this many nonzeros go to the heavy-row sweep of SpMM
+
+
 def _heavy_row_matrix():
-    """1.3 M nonzeros in 300 000 columns; rows of 255 / 256 / 257 nonzeros around the heavy-row threshold, long
+    """1.3 M nonzeros in 300 000 columns; rows of 127 / 128 / 129 nonzeros around the heavy-row threshold, long
     rows first, last and next to each other, rows longer than a tile and than a unit, empty and short rows."""
     J = 300_000
-    block = [5000, 0, 256, 255, 257, 1, 4096, 3, 8192, 8193, 300, 0, 0, 2, 20000, 511, 512, 7, 2047, 2049]
-    lens = torch.tensor([9000] + block * 20 + [256, 1, 6000], dtype=torch.int64)
+    block = [5000, 0, 128, 127, 129, 1, 4096, 3, 8192, 8193, 300, 0, 0, 2, 20000, 255, 256, 7, 4095, 4097]
+    lens = torch.tensor([9000] + block * 20 + [128, 1, 6000], dtype=torch.int64)
     return (lens.numel(), J), gen.matrix_from_row_lengths(lens.numel(), J, lens, 21)
 
 
@@ -129,7 +132,7 @@ def test_spmm_with_heavy_rows(comet, name, layout, R, variant):
     A = comet.from_levels(pack(I, J, rows, cols, vals).to("cuda")).set_variant(variant)
     hrows, hnnz = A.heavy_plan()
     lens = torch.bincount(rows, minlength=I)
-    assert hrows == int((lens >= 256).sum()) and hnnz == int(lens[lens >= 256].sum()) and hrows > 0
+    assert hrows == int((lens >= HEAVY_ROW).sum()) and hnnz == int(lens[lens >= HEAVY_ROW].sum()) and hrows > 0
     B = gen.dense_operand(2, 0, (J, R))
     C = torch.full((I, R), float("nan"), dtype=torch.float64, device="cuda")
     comet.comet_spmm(A, dev(B), C)
