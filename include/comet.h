@@ -59,7 +59,7 @@ typedef enum {
 } comet_status;
 
 /* comet_tensor_create flags */
-#define COMET_BORROW   0u   /* default: the caller keeps pos/crd/vals alive until destroy       */
+#define COMET_BORROW   0u   /* default: the caller keeps pos/crd/vals alive and unchanged until destroy */
 #define COMET_COPY     1u   /* the library copies pos/crd/vals into memory it owns              */
 #define COMET_VALIDATE 2u   /* run the device-side structure check (see below)                  */
 #define COMET_LEAN     4u   /* keep no copies of parts of the tensor: the heavy-row sweep of    */
@@ -110,6 +110,11 @@ typedef struct {
  * crd_len; every coordinate lies in [0, dim); coordinates are strictly increasing inside each CU
  * segment; a CN/S coordinate list is lexicographically sorted without duplicates.  Failures give
  * COMET_ERR_BAD_FORMAT and no handle.  Explicit zeros in vals are legal stored entries.
+ *
+ * The arrays must not change while the handle lives: besides the tile tables below, a handle may keep
+ * copies of parts of the tensor, values included (the plans of the two sweeps, see COMET_LEAN and
+ * heavy_stream_bytes; the compressed copy of a coordinate list), and these would not follow.  Values that
+ * change call for a new handle.
  *
  * The call also builds the per-tensor schedule (nonzero-balanced tile tables used by the
  * kernels; load imbalance is what Section 8.3 identifies as the main source of slowdown), which
